@@ -1,0 +1,320 @@
+/*
+ * CPU oracle for the batched exact 0/1 multiple-knapsack solver.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP path is checked against.  It shares no code with the HIP path, is never
+ * called by it, and may be used only by the tests, the smoke check and the
+ * benchmark's cpu_baseline leg.
+ *
+ * What it follows (DeFT, arXiv 2503.16815):
+ *   - Section III.B, Problem 1: one 0/1 knapsack, items = bucket communication
+ *     times, capacity = a merged computation window, constraint inclusive.
+ *     The paper's "NaiveKnapsack" (Algorithm 1) is never spelled out; it is
+ *     read here as the textbook exact DP over integer capacities.
+ *   - Section III.A/III.B (Cases 1-4, coverage ratio N:M): backward and forward
+ *     windows of successive iterations each take what is left over by the
+ *     previous window -> m knapsacks filled one after the other in a given
+ *     order; each stage is solved exactly on the items still unplaced.
+ *   - Section III.C, Problem 2: two knapsacks (links), each item in at most
+ *     one; generalised to a separate weight per link (the paper's single c_j
+ *     with a capacity scaled by mu is the case w1 == w2).
+ *
+ * Conventions the paper leaves open, fixed here:
+ *   - an item is taken at capacity c only if it strictly improves the value;
+ *     traceback runs from the last item down.  Among all optimal selections
+ *     this yields the one with the smallest mask sum_t x_t 2^t.
+ *   - joint DP: per item the order of tests is skip, link 0, link 1, each
+ *     replacing the incumbent only if strictly greater.
+ *   - values and weights are separate arrays (value == weight is Problem 1).
+ *
+ * Arithmetic: int64 accumulators; inputs int32.  No blocking, no bit packing:
+ * the keep table is one byte per (item, capacity cell).
+ *
+ * Pins: tests/test_oracle_*.py (brute force over all 2^n / 3^n selections,
+ * the bitset subset-sum recurrence, closed forms, invariants, the Table II
+ * bucket times as a worked vector).
+ */
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ST_OK = 0, ST_INVALID = 1, ST_LIMIT = 2, ST_OVERFLOW = 3, ST_OOM = 4 };
+
+#define VALUE_SUM_LIMIT ((int64_t)1 << 31)
+
+/* Problem 1 on the items listed in act[0..A) (ascending original index).
+ * Returns the optimal value; marks chosen[t] and returns the placed weight. */
+static int single_stage(int A, const int32_t *aw, const int32_t *av, int32_t C,
+                        int64_t *value, int64_t *load, uint8_t *chosen,
+                        int64_t *touched, int64_t *table)
+{
+    size_t cells = (size_t)C + 1;
+    int64_t *row = (int64_t *)calloc(cells, sizeof(int64_t));
+    uint8_t *keep = (uint8_t *)calloc((size_t)(A > 0 ? A : 1) * cells, 1);
+    if (!row || !keep) { free(row); free(keep); return ST_OOM; }
+
+    for (int t = 0; t < A; ++t) {
+        int64_t w = aw[t], v = av[t];
+        *table += (int64_t)cells;
+        if (w <= C) *touched += (int64_t)C - w + 1;
+        for (int64_t c = C; c >= w; --c) {
+            int64_t cand = row[c - w] + v;
+            if (cand > row[c]) {
+                row[c] = cand;
+                keep[(size_t)t * cells + (size_t)c] = 1;
+            }
+        }
+    }
+    *value = row[C];
+
+    int64_t c = C;
+    for (int t = A - 1; t >= 0; --t) {
+        chosen[t] = 0;
+        if (keep[(size_t)t * cells + (size_t)c]) {
+            chosen[t] = 1;
+            c -= aw[t];
+        }
+    }
+    *load = (int64_t)C - c;
+    free(row);
+    free(keep);
+    return ST_OK;
+}
+
+static void clear_outputs(int32_t n_slots, int32_t m_slots, int64_t *total,
+                          int32_t *knap_value, int32_t *knap_load, int32_t *assign)
+{
+    *total = 0;
+    for (int j = 0; j < m_slots; ++j) { knap_value[j] = 0; knap_load[j] = 0; }
+    for (int i = 0; i < n_slots; ++i) assign[i] = -1;
+}
+
+/*
+ * Sequential multiple knapsack for one instance.
+ * order may be NULL (= 0,1,2,...).  cap_limit < 0 means "no limit".
+ * assign has item_stride slots, knap_* have knap_stride slots; all are
+ * written (unused slots: -1 / 0).
+ */
+int deft_oracle_sequential(int32_t n, int32_t item_stride, const int32_t *w, const int32_t *v,
+                           int32_t m, int32_t knap_stride, const int32_t *cap,
+                           const int32_t *order, int32_t cap_limit,
+                           int64_t *total, int32_t *knap_value, int32_t *knap_load,
+                           int32_t *assign, int64_t *touched_cells, int64_t *table_cells)
+{
+    int64_t touched = 0, table = 0;
+    clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+    if (touched_cells) *touched_cells = 0;
+    if (table_cells) *table_cells = 0;
+
+    if (n < 0 || n > item_stride || m < 0 || m > knap_stride) return ST_INVALID;
+    for (int i = 0; i < n; ++i)
+        if (w[i] < 1 || v[i] < 0) return ST_INVALID;
+    for (int j = 0; j < m; ++j)
+        if (cap[j] < 0) return ST_INVALID;
+    if (order) {
+        uint8_t *seen = (uint8_t *)calloc((size_t)(m > 0 ? m : 1), 1);
+        if (!seen) return ST_OOM;
+        for (int s = 0; s < m; ++s) {
+            int32_t j = order[s];
+            if (j < 0 || j >= m || seen[j]) { free(seen); return ST_INVALID; }
+            seen[j] = 1;
+        }
+        free(seen);
+    }
+    if (cap_limit >= 0)
+        for (int j = 0; j < m; ++j)
+            if (cap[j] > cap_limit) return ST_LIMIT;
+    int64_t vsum = 0;
+    for (int i = 0; i < n; ++i) vsum += v[i];
+    if (vsum >= VALUE_SUM_LIMIT) return ST_OVERFLOW;
+
+    int32_t *act = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    int32_t *aw = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    int32_t *av = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    uint8_t *chosen = (uint8_t *)malloc((size_t)(n > 0 ? n : 1));
+    int rc = ST_OK;
+    if (!act || !aw || !av || !chosen) rc = ST_OOM;
+
+    int64_t sum = 0;
+    for (int s = 0; s < m && rc == ST_OK; ++s) {
+        int32_t j = order ? order[s] : s;
+        int A = 0;
+        for (int i = 0; i < n; ++i)
+            if (assign[i] == -1) { act[A] = i; aw[A] = w[i]; av[A] = v[i]; ++A; }
+        int64_t value = 0, load = 0;
+        rc = single_stage(A, aw, av, cap[j], &value, &load, chosen, &touched, &table);
+        if (rc != ST_OK) break;
+        for (int t = 0; t < A; ++t)
+            if (chosen[t]) assign[act[t]] = j;
+        knap_value[j] = (int32_t)value;
+        knap_load[j] = (int32_t)load;
+        sum += value;
+    }
+    free(act); free(aw); free(av); free(chosen);
+    if (rc != ST_OK) {
+        clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+        return rc;
+    }
+    *total = sum;
+    if (touched_cells) *touched_cells = touched;
+    if (table_cells) *table_cells = table;
+    return ST_OK;
+}
+
+/*
+ * Joint two-link DP (Problem 2 with per-link weights) for one instance.
+ * w1 = weights on link 0 (capacity cap[0]), w2 = weights on link 1 (cap[1]).
+ * assign: 0 / 1 / -1.  knap_value[j] = value placed on link j.
+ */
+int deft_oracle_joint2(int32_t n, int32_t item_stride, const int32_t *w1, const int32_t *w2,
+                       const int32_t *v, int32_t m, int32_t knap_stride, const int32_t *cap,
+                       int32_t c1_limit, int32_t c2_limit,
+                       int64_t *total, int32_t *knap_value, int32_t *knap_load,
+                       int32_t *assign, int64_t *touched_cells, int64_t *table_cells)
+{
+    clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+    if (touched_cells) *touched_cells = 0;
+    if (table_cells) *table_cells = 0;
+
+    if (n < 0 || n > item_stride || m != 2 || knap_stride < 2) return ST_INVALID;
+    for (int i = 0; i < n; ++i)
+        if (w1[i] < 1 || w2[i] < 1 || v[i] < 0) return ST_INVALID;
+    if (cap[0] < 0 || cap[1] < 0) return ST_INVALID;
+    if ((c1_limit >= 0 && cap[0] > c1_limit) || (c2_limit >= 0 && cap[1] > c2_limit)) return ST_LIMIT;
+    int64_t vsum = 0;
+    for (int i = 0; i < n; ++i) vsum += v[i];
+    if (vsum >= VALUE_SUM_LIMIT) return ST_OVERFLOW;
+
+    int64_t C1 = cap[0], C2 = cap[1];
+    size_t cols = (size_t)C2 + 1, cells = ((size_t)C1 + 1) * cols;
+    int64_t *old = (int64_t *)calloc(cells, sizeof(int64_t));
+    int64_t *cur = (int64_t *)calloc(cells, sizeof(int64_t));
+    uint8_t *code = (uint8_t *)calloc((size_t)(n > 0 ? n : 1) * cells, 1);
+    if (!old || !cur || !code) { free(old); free(cur); free(code); return ST_OOM; }
+
+    for (int i = 0; i < n; ++i) {
+        int64_t a1 = w1[i], a2 = w2[i], val = v[i];
+        for (int64_t a = 0; a <= C1; ++a) {
+            for (int64_t b = 0; b <= C2; ++b) {
+                size_t at = (size_t)a * cols + (size_t)b;
+                int64_t best = old[at];
+                uint8_t how = 0;
+                if (a >= a1) {
+                    int64_t cand = old[(size_t)(a - a1) * cols + (size_t)b] + val;
+                    if (cand > best) { best = cand; how = 1; }
+                }
+                if (b >= a2) {
+                    int64_t cand = old[(size_t)a * cols + (size_t)(b - a2)] + val;
+                    if (cand > best) { best = cand; how = 2; }
+                }
+                cur[at] = best;
+                code[(size_t)i * cells + at] = how;
+            }
+        }
+        int64_t *tmp = old; old = cur; cur = tmp;
+    }
+    int64_t opt = old[(size_t)C1 * cols + (size_t)C2];
+
+    int64_t a = C1, b = C2, val0 = 0, val1 = 0;
+    for (int i = n - 1; i >= 0; --i) {
+        uint8_t how = code[(size_t)i * cells + (size_t)a * cols + (size_t)b];
+        if (how == 1) { assign[i] = 0; a -= w1[i]; val0 += v[i]; }
+        else if (how == 2) { assign[i] = 1; b -= w2[i]; val1 += v[i]; }
+    }
+    knap_value[0] = (int32_t)val0;
+    knap_value[1] = (int32_t)val1;
+    knap_load[0] = (int32_t)(C1 - a);
+    knap_load[1] = (int32_t)(C2 - b);
+    *total = opt;
+    if (touched_cells) *touched_cells = (int64_t)n * (int64_t)cells;
+    if (table_cells) *table_cells = (int64_t)n * (int64_t)cells;
+    free(old); free(cur); free(code);
+    return ST_OK;
+}
+
+/* ---- batch driver: instances split statically over nthreads ------------- */
+
+typedef struct {
+    int32_t mode, batch, item_stride, knap_stride;
+    const int32_t *n_items, *n_knapsacks, *weights, *values, *capacities, *fill_order;
+    int32_t cap_limit, c1_limit, c2_limit;
+    int64_t *total;
+    int32_t *knap_value, *knap_load, *assign, *status;
+    int64_t *touched, *table;
+} batch_args_t;
+
+typedef struct { const batch_args_t *a; int lo, hi; } slice_t;
+
+static void solve_one(const batch_args_t *a, int b)
+{
+    size_t is = (size_t)a->item_stride, ks = (size_t)a->knap_stride;
+    int64_t touched = 0, table = 0;
+    int st;
+    if (a->mode == 0) {
+        st = deft_oracle_sequential(a->n_items[b], a->item_stride, a->weights + b * is,
+                                    a->values + b * is, a->n_knapsacks[b], a->knap_stride,
+                                    a->capacities + b * ks,
+                                    a->fill_order ? a->fill_order + b * ks : NULL, a->cap_limit,
+                                    a->total + b, a->knap_value + b * ks, a->knap_load + b * ks,
+                                    a->assign + b * is, &touched, &table);
+    } else {
+        st = deft_oracle_joint2(a->n_items[b], a->item_stride, a->weights + b * 2 * is,
+                                a->weights + b * 2 * is + is, a->values + b * is,
+                                a->n_knapsacks[b], a->knap_stride, a->capacities + b * ks,
+                                a->c1_limit, a->c2_limit, a->total + b, a->knap_value + b * ks,
+                                a->knap_load + b * ks, a->assign + b * is, &touched, &table);
+    }
+    a->status[b] = st;
+    if (a->touched) a->touched[b] = touched;
+    if (a->table) a->table[b] = table;
+}
+
+static void *worker(void *p)
+{
+    const slice_t *s = (const slice_t *)p;
+    for (int b = s->lo; b < s->hi; ++b) solve_one(s->a, b);
+    return NULL;
+}
+
+/* Returns the number of threads actually used (>= 1), or -1 on bad arguments. */
+int deft_oracle_solve_batch(int32_t mode, int32_t batch, int32_t item_stride, int32_t knap_stride,
+                            const int32_t *n_items, const int32_t *n_knapsacks,
+                            const int32_t *weights, const int32_t *values,
+                            const int32_t *capacities, const int32_t *fill_order,
+                            int32_t cap_limit, int32_t c1_limit, int32_t c2_limit,
+                            int64_t *total, int32_t *knap_value, int32_t *knap_load,
+                            int32_t *assign, int32_t *status, int64_t *touched, int64_t *table,
+                            int32_t nthreads)
+{
+    if ((mode != 0 && mode != 1) || batch < 0 || item_stride < 0 || knap_stride < 0) return -1;
+    batch_args_t a = { mode, batch, item_stride, knap_stride, n_items, n_knapsacks, weights,
+                       values, capacities, fill_order, cap_limit, c1_limit, c2_limit, total,
+                       knap_value, knap_load, assign, status, touched, table };
+    if (nthreads < 1) nthreads = 1;
+    if (nthreads > batch) nthreads = batch > 0 ? batch : 1;
+    if (nthreads == 1) {
+        for (int b = 0; b < batch; ++b) solve_one(&a, b);
+        return 1;
+    }
+    pthread_t *tid = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)nthreads);
+    slice_t *sl = (slice_t *)malloc(sizeof(slice_t) * (size_t)nthreads);
+    char *live = (char *)calloc((size_t)nthreads, 1);
+    if (!tid || !sl || !live) { free(tid); free(sl); free(live); return -1; }
+    int started = 0;
+    for (int t = 0; t < nthreads; ++t) {
+        sl[t].a = &a;
+        sl[t].lo = (int)((int64_t)batch * t / nthreads);
+        sl[t].hi = (int)((int64_t)batch * (t + 1) / nthreads);
+        if (pthread_create(&tid[t], NULL, worker, &sl[t]) != 0) {
+            worker(&sl[t]);                 /* run the slice inline if no thread */
+        } else {
+            live[t] = 1;
+            ++started;
+        }
+    }
+    for (int t = 0; t < nthreads; ++t)
+        if (live[t]) pthread_join(tid[t], NULL);
+    free(tid); free(sl); free(live);
+    return started > 0 ? nthreads : 1;
+}

@@ -1,0 +1,215 @@
+"""Seeded synthetic knapsack batches shaped on the paper's three DNN profiles.
+
+This module only draws inputs; it holds none of the solver's arithmetic and is
+the one piece shared by the CPU oracle's tests and the HIP path's tests/bench.
+It depends on numpy alone.
+
+The paper's real per-bucket profiles are not available, so every batch is a
+stand-in built from the aggregate times it prints:
+
+* Table I gives forward / backward / communication time per iteration
+  (ResNet-101 59/118/242 ms, VGG-19 37/93/258 ms, GPT-2 169/381/546.4 ms):
+  the backward and forward windows are the knapsack capacities, the
+  communication time is the total item weight (Section III.B, Problem 1).
+* Table II gives six VGG-19 bucket times with one bucket far above every
+  window: the VGG-shaped generator reproduces that heavy tail.
+* Section III.A (coverage ratio N:M) and III.B: when communication exceeds
+  the windows of one iteration, leftovers are served by the windows of later
+  iterations, so the (backward, forward) pair is repeated k times -> m = 2k
+  knapsacks filled in time order.
+* Section III.C, Problem 2: two links of different speed; one item costs a
+  different time on each link.
+
+Times are discretised by the caller: 10 us units for the ResNet/VGG shapes,
+1 us units for the GPT-2 shape.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+MODE_SEQUENTIAL = 0
+MODE_JOINT2 = 1
+
+SEED_TINY = 1001
+SEED_RESNET = 1002
+SEED_VGG = 1003
+SEED_GPT2 = 1004
+SEED_HETERO = 1005
+
+
+@dataclass
+class KnapsackBatch:
+    """Host-side (numpy, int32, C-contiguous) image of one solver call.
+
+    weights: [batch, item_stride] (sequential) or [batch, 2, item_stride] (joint)
+    values: [batch, item_stride]
+    capacities, fill_order: [batch, knap_stride]; fill_order may be None
+    """
+
+    name: str
+    mode: int
+    batch: int
+    item_stride: int
+    knap_stride: int
+    n_items: np.ndarray
+    n_knapsacks: np.ndarray
+    weights: np.ndarray
+    values: np.ndarray
+    capacities: np.ndarray
+    fill_order: Optional[np.ndarray] = None
+    meta: dict = field(default_factory=dict)
+
+    def slice(self, lo: int, hi: int) -> "KnapsackBatch":
+        fo = None if self.fill_order is None else np.ascontiguousarray(self.fill_order[lo:hi])
+        return KnapsackBatch(
+            name=f"{self.name}[{lo}:{hi}]", mode=self.mode, batch=hi - lo,
+            item_stride=self.item_stride, knap_stride=self.knap_stride,
+            n_items=np.ascontiguousarray(self.n_items[lo:hi]),
+            n_knapsacks=np.ascontiguousarray(self.n_knapsacks[lo:hi]),
+            weights=np.ascontiguousarray(self.weights[lo:hi]),
+            values=np.ascontiguousarray(self.values[lo:hi]),
+            capacities=np.ascontiguousarray(self.capacities[lo:hi]),
+            fill_order=fo, meta=dict(self.meta))
+
+    def max_capacity(self) -> int:
+        return int(self.capacities.max()) if self.capacities.size else 0
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def _rescale_to_sum(x: np.ndarray, total: float) -> np.ndarray:
+    """Round x * total / sum(x) per row to integers >= 1 (time discretisation)."""
+    s = x.sum(axis=-1, keepdims=True)
+    return np.maximum(1, np.rint(x * (total / s))).astype(np.int64)
+
+
+def _sequential(name, weights, values, capacities, fill_order=None, meta=None) -> KnapsackBatch:
+    weights = _i32(weights)
+    b, n = weights.shape
+    capacities = _i32(capacities)
+    m = capacities.shape[1]
+    return KnapsackBatch(
+        name=name, mode=MODE_SEQUENTIAL, batch=b, item_stride=n, knap_stride=m,
+        n_items=_i32(np.full(b, n)), n_knapsacks=_i32(np.full(b, m)),
+        weights=weights, values=_i32(values), capacities=capacities,
+        fill_order=None if fill_order is None else _i32(fill_order), meta=meta or {})
+
+
+def tiny_single(seed: int = SEED_TINY) -> KnapsackBatch:
+    """One instance: n=32, w~U{1..200}, v~U{1..1000}, capacities (1000, 500)."""
+    r = _rng(seed)
+    w = r.integers(1, 201, size=(1, 32))
+    v = r.integers(1, 1001, size=(1, 32))
+    return _sequential("tiny_single", w, v, [[1000, 500]], meta={"seed": seed})
+
+
+def tiny_bruteforce(seed: int = SEED_TINY, batch: int = 64, n: int = 16) -> KnapsackBatch:
+    """64 instances small enough (n=16) to enumerate; capacities (500, 250)."""
+    r = _rng(seed + 7919)
+    w = r.integers(1, 201, size=(batch, n))
+    v = r.integers(1, 1001, size=(batch, n))
+    cap = np.tile(np.array([[500, 250]]), (batch, 1))
+    return _sequential("tiny_bruteforce", w, v, cap, meta={"seed": seed})
+
+
+def resnet101_shaped(k: int = 1, batch: int = 1024, n: int = 314,
+                     seed: int = SEED_RESNET) -> KnapsackBatch:
+    """ResNet-101 shape (Table I, 10 us units): total comm 24200, backward
+    window 11800 and forward window 5900 each jittered +-10 % per instance,
+    the pair repeated k times (m = 2k); value = weight (Problem 1)."""
+    r = _rng(seed)
+    x = r.lognormal(mean=0.0, sigma=1.2, size=(batch, n))
+    w = _rescale_to_sum(x, 24200.0)
+    u = r.uniform(0.9, 1.1, size=(batch, 2))
+    pair = np.rint(np.array([11800.0, 5900.0])[None, :] * u).astype(np.int64)
+    cap = np.tile(pair, (1, k))
+    return _sequential(f"resnet101_k{k}", w, w.copy(), cap, meta={"seed": seed, "k": k})
+
+
+def vgg19_shaped(k: int = 1, batch: int = 4096, n: int = 38,
+                 seed: int = SEED_VGG) -> KnapsackBatch:
+    """VGG-19 shape (Tables I and II, 10 us units): total comm 25800 with three
+    heavy items holding about 85 % of it; windows 9300 / 3700; value = weight."""
+    r = _rng(seed)
+    heavy_share = r.uniform(0.9, 1.1, size=(batch, 3))
+    heavy_share = heavy_share / heavy_share.sum(axis=1, keepdims=True)
+    heavy = np.maximum(1, np.rint(heavy_share * (0.85 * 25800.0))).astype(np.int64)
+    light = _rescale_to_sum(r.lognormal(0.0, 1.0, size=(batch, n - 3)), 0.15 * 25800.0)
+    w = np.empty((batch, n), dtype=np.int64)
+    for b in range(batch):
+        pos = r.permutation(n)
+        w[b, pos[:3]] = heavy[b]
+        w[b, pos[3:]] = light[b]
+    cap = np.tile(np.array([[9300, 3700]]), (batch, k))
+    return _sequential(f"vgg19_k{k}", w, w.copy(), cap, meta={"seed": seed, "k": k})
+
+
+def gpt2_shaped(batch: int = 256, n: int = 148, seed: int = SEED_GPT2) -> KnapsackBatch:
+    """GPT-2 shape (Table I, 1 us units): total comm 546400, windows 381000 /
+    169000; value = weight x U[1,4] priority."""
+    r = _rng(seed)
+    w = _rescale_to_sum(r.lognormal(0.0, 0.8, size=(batch, n)), 546400.0)
+    v = np.rint(w * r.uniform(1.0, 4.0, size=(batch, n))).astype(np.int64)
+    cap = np.tile(np.array([[381000, 169000]]), (batch, 1))
+    return _sequential("gpt2", w, v, cap, meta={"seed": seed})
+
+
+def hetero_joint(batch: int = 256, n: int = 64, c1: int = 512, c2: int = 512,
+                 seed: int = SEED_HETERO) -> KnapsackBatch:
+    """Two-link shape (Problem 2 with per-link times): w1~U{1..64} on the fast
+    link, w2 = w1 x U{3..6} on the slow link, v~U{1..1000}, C1 = C2 = 512."""
+    r = _rng(seed)
+    w1 = r.integers(1, 65, size=(batch, n))
+    w2 = w1 * r.integers(3, 7, size=(batch, n))
+    v = r.integers(1, 1001, size=(batch, n))
+    w = np.stack([w1, w2], axis=1)
+    return KnapsackBatch(
+        name="hetero_joint", mode=MODE_JOINT2, batch=batch, item_stride=n, knap_stride=2,
+        n_items=_i32(np.full(batch, n)), n_knapsacks=_i32(np.full(batch, 2)),
+        weights=_i32(w), values=_i32(v),
+        capacities=_i32(np.tile(np.array([[c1, c2]]), (batch, 1))), meta={"seed": seed})
+
+
+def random_sequential(seed: int, batch: int, n_max: int, m_max: int, w_hi: int, v_hi: int,
+                      cap_hi: int, ragged: bool = True, ties: bool = False,
+                      permute_order: bool = True) -> KnapsackBatch:
+    """General ragged batch for parity and edge-case tests: per-instance n in
+    [0, n_max], m in [0, m_max], capacities in [0, cap_hi], optional random fill
+    order, optional value = weight (tie-heavy)."""
+    r = _rng(seed)
+    n_items = r.integers(0, n_max + 1, size=batch) if ragged else np.full(batch, n_max)
+    n_knap = r.integers(0, m_max + 1, size=batch) if ragged else np.full(batch, m_max)
+    w = r.integers(1, w_hi + 1, size=(batch, n_max))
+    v = w.copy() if ties else r.integers(0, v_hi + 1, size=(batch, n_max))
+    cap = r.integers(0, cap_hi + 1, size=(batch, max(m_max, 1)))
+    order = np.tile(np.arange(max(m_max, 1)), (batch, 1))
+    if permute_order:
+        for b in range(batch):
+            m = int(n_knap[b])
+            order[b, :m] = r.permutation(m)
+    kb = _sequential(f"random_seq_{seed}", w, v, cap, order, meta={"seed": seed})
+    kb.n_items = _i32(n_items)
+    kb.n_knapsacks = _i32(n_knap)
+    return kb
+
+
+def random_joint(seed: int, batch: int, n_max: int, w_hi: int, v_hi: int, c1_hi: int,
+                 c2_hi: int, ragged: bool = True) -> KnapsackBatch:
+    r = _rng(seed)
+    n_items = r.integers(0, n_max + 1, size=batch) if ragged else np.full(batch, n_max)
+    w = r.integers(1, w_hi + 1, size=(batch, 2, n_max))
+    v = r.integers(0, v_hi + 1, size=(batch, n_max))
+    cap = np.stack([r.integers(0, c1_hi + 1, size=batch), r.integers(0, c2_hi + 1, size=batch)], axis=1)
+    return KnapsackBatch(
+        name=f"random_joint_{seed}", mode=MODE_JOINT2, batch=batch, item_stride=n_max, knap_stride=2,
+        n_items=_i32(n_items), n_knapsacks=_i32(np.full(batch, 2)), weights=_i32(w), values=_i32(v),
+        capacities=_i32(cap), meta={"seed": seed})
