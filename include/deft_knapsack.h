@@ -1,0 +1,173 @@
+/*
+ * deft_knapsack.h - C ABI of the batched exact 0/1 multiple-knapsack solver
+ * for AMD MI355X (gfx950).
+ *
+ * The solver is the data-parallel core of DeFT's communication scheduler
+ * (arXiv 2503.16815): gradient buckets are items weighted by communication
+ * time, merged forward/backward computation windows are knapsacks, and many
+ * candidate schedules (instances) are solved per call.
+ *
+ * All array arguments are DEVICE pointers owned by the caller (never retained,
+ * never freed by the library).  All integers are int32 unless stated.  The
+ * library never prints, throws or aborts: every failure is a return code or a
+ * per-instance status.  A handle owns its scratch memory and serves one
+ * in-flight batch at a time (not thread-safe; use one handle per stream).
+ */
+#ifndef DEFT_KNAPSACK_H
+#define DEFT_KNAPSACK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct deft_knapsack deft_knapsack_t; /* opaque */
+
+typedef enum {
+    DEFT_OK = 0,
+    DEFT_ERR_INVALID_ARG = 1, /* NULL pointer, negative count, bad mode, bad data          */
+    DEFT_ERR_LIMIT = 2,       /* exceeds a limit given at create time                      */
+    DEFT_ERR_OVERFLOW = 3,    /* sum of an instance's values >= 2^31                       */
+    DEFT_ERR_OOM = 4,         /* scratch allocation failed                                 */
+    DEFT_ERR_DEVICE = 5       /* HIP runtime error, wrong architecture, launch failure     */
+} deft_status_t;
+
+enum {
+    DEFT_MODE_SEQUENTIAL = 0, /* m knapsacks filled one after the other (Sec. III.B)       */
+    DEFT_MODE_JOINT2 = 1      /* two links, one joint 2-D DP (Sec. III.C, Problem 2)       */
+};
+
+/* Limits fixed at create time; they size the scratch memory and select the
+ * kernel variants.  A limit of 0 disables the corresponding mode. */
+typedef struct {
+    int32_t device;        /* HIP device ordinal                                           */
+    int32_t max_batch;     /* instances per call                                           */
+    int32_t max_items;     /* item_stride upper bound (1..4096)                            */
+    int32_t max_knapsacks; /* knap_stride upper bound (1..64)                              */
+    int32_t max_capacity;  /* sequential mode: largest capacity (0 = mode unused)          */
+    int32_t max_c1;        /* joint mode: largest capacity of link 0 (0 = mode unused)     */
+    int32_t max_c2;        /* joint mode: largest capacity of link 1                       */
+    uint32_t flags;        /* must be 0                                                    */
+} deft_knapsack_config_t;
+
+/*
+ * deft_knapsack_create: validate the limits, check that the device is a
+ * gfx950, allocate the scratch (keep / choice tables, large rows) on
+ * cfg->device and return a handle in *out.
+ * Errors: INVALID_ARG (NULL, non-positive limits, flags != 0), LIMIT (limits
+ * beyond what the library supports), OOM, DEVICE.  *out is NULL on error.
+ */
+deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knapsack_t **out);
+
+/*
+ * One call = `batch` independent instances.
+ *
+ * DEFT_MODE_SEQUENTIAL (Sec. III.B, Problem 1, one stage per knapsack):
+ *   for s = 0 .. n_knapsacks-1:  j = fill_order[s]  (or s when fill_order is NULL)
+ *     solve  max sum v_i x_i  s.t.  sum w_i x_i <= capacities[j],  x in {0,1}
+ *     exactly, over the items not yet placed; place the chosen items in j.
+ *   Each stage is the textbook exact DP ("NaiveKnapsack" of Algorithm 1); an
+ *   item is taken at a capacity only when it strictly improves the value and
+ *   the selection is traced back from the last item, so among optimal subsets
+ *   the one with the smallest mask sum_t x_t 2^t (t = rank among the offered
+ *   items) is returned.  The paper's value is the communication time itself
+ *   (values == weights); separate values are accepted.
+ *
+ * DEFT_MODE_JOINT2 (Sec. III.C, Problem 2 with one weight per link):
+ *   max sum_i v_i [a_i != none]  s.t.  sum_{a_i = 0} w0_i <= capacities[0],
+ *   sum_{a_i = 1} w1_i <= capacities[1], each item on at most one link.
+ *   Exact 2-D DP; per item the tests run skip, link 0, link 1, each replacing
+ *   the incumbent only when strictly greater; traced back from the last item.
+ *   n_knapsacks must be 2.
+ *
+ * Layout (row-major, device memory):
+ *   n_items     [batch]                      0 <= n_items[b] <= item_stride
+ *   n_knapsacks [batch]                      0 <= n_knapsacks[b] <= knap_stride
+ *   weights     SEQUENTIAL [batch][item_stride]      each >= 1
+ *               JOINT2     [batch][2][item_stride]   row 0 = link 0, row 1 = link 1
+ *   values      [batch][item_stride]         each >= 0, sum per instance < 2^31
+ *   capacities  [batch][knap_stride]         indexed by knapsack id, each >= 0
+ *   fill_order  [batch][knap_stride] or NULL a permutation of 0..n_knapsacks[b]-1
+ * Outputs (every slot of every row is written):
+ *   total_value [batch] int64                sum of knap_value
+ *   knap_value  [batch][knap_stride]         value placed in knapsack j (unused slots 0)
+ *   knap_load   [batch][knap_stride]         weight placed in knapsack j (<= capacity)
+ *   assignment  [batch][item_stride]         knapsack id, or -1 (also for slots >= n_items)
+ *   status      [batch]                      deft_status_t of the instance
+ * A faulted instance (status != DEFT_OK: bad n/m, w < 1, v < 0, capacity < 0,
+ * fill_order not a permutation -> INVALID_ARG; capacity above the create-time
+ * limit -> LIMIT; value sum >= 2^31 -> OVERFLOW; in that precedence) gets
+ * total_value 0, knap_value/knap_load 0 and assignment -1; other instances are
+ * unaffected.
+ */
+typedef struct {
+    int32_t mode;        /* DEFT_MODE_*                                                    */
+    int32_t batch;       /* 0 .. max_batch (0 is a no-op)                                  */
+    int32_t item_stride; /* 1 .. max_items                                                 */
+    int32_t knap_stride; /* 1 .. max_knapsacks (>= 2 for JOINT2)                           */
+    const int32_t *n_items;
+    const int32_t *n_knapsacks;
+    const int32_t *weights;
+    const int32_t *values;
+    const int32_t *capacities;
+    const int32_t *fill_order; /* may be NULL */
+    int64_t *total_value;
+    int32_t *knap_value;
+    int32_t *knap_load;
+    int32_t *assignment;
+    int32_t *status;
+    void *stream; /* hipStream_t; NULL = the default stream */
+} deft_knapsack_batch_t;
+
+/*
+ * deft_knapsack_solve_batch: enqueue the whole solve (all stages, traceback
+ * included) on batch->stream and return without waiting; outputs are valid once
+ * the stream has been synchronised.  Host-checkable faults (NULL handle / batch
+ * / required array, batch < 0, strides < 1, bad mode) return INVALID_ARG, counts
+ * above the create-time limits or a mode whose limit was 0 return LIMIT, a failed
+ * launch returns DEVICE; in all these cases nothing was enqueued.
+ */
+deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *batch);
+
+/* deft_knapsack_destroy: free the scratch and the handle.  NULL is a no-op. */
+void deft_knapsack_destroy(deft_knapsack_t *h);
+
+/* ---- introspection and measurement (not part of the paper's method) ------ */
+
+typedef struct {
+    int64_t scratch_bytes;     /* device memory owned by the handle                        */
+    int32_t seq_path;          /* 0 none, 1 wavefront-per-instance LDS, 2 workgroup-per-
+                                  instance LDS, 3 rows in global memory                    */
+    int32_t seq_threads;       /* threads cooperating on one instance                      */
+    int32_t seq_cells_per_thread;
+    int32_t seq_lds_bytes;     /* LDS per workgroup                                        */
+    int32_t seq_workgroups_per_cu; /* co-resident workgroups reported by the runtime       */
+    int32_t joint_path;        /* 0 none, 1 rows in global memory                          */
+    int32_t compute_units;
+} deft_knapsack_info_t;
+
+/* Fill *info for a live handle.  INVALID_ARG on NULL. */
+deft_status_t deft_knapsack_get_info(const deft_knapsack_t *h, deft_knapsack_info_t *info);
+
+typedef struct {
+    float total_ms;        /* first launch to last launch of the last profiled call        */
+    float sweep_ms;        /* summed duration of the DP sweep kernel launches              */
+    int32_t sweep_launches;
+    float other_ms;        /* set-up and traceback launches outside the sweep kernel       */
+} deft_knapsack_profile_t;
+
+/* Turn per-call HIP-event timing on (1) or off (0); off by default. */
+deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t enable);
+
+/* Wait for the last profiled call to finish and read its timings.
+ * INVALID_ARG if profiling is off or no call has been made. */
+deft_status_t deft_knapsack_get_profile(deft_knapsack_t *h, deft_knapsack_profile_t *out);
+
+/* Static string for a status code ("DEFT_OK", ...); never NULL. */
+const char *deft_knapsack_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEFT_KNAPSACK_H */

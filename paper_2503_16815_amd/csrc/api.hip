@@ -1,0 +1,265 @@
+// C ABI of the solver: argument validation, scratch ownership, kernel choice
+// and launch sequencing.  See include/deft_knapsack.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace deft;
+
+namespace {
+
+constexpr int32_t kMaxItems = 4096;
+constexpr int32_t kMaxKnapsacks = 64;
+constexpr int32_t kMaxBatch = 1 << 20;
+constexpr int32_t kMaxCapacity = 1 << 24;
+constexpr int32_t kMaxJointCapacity = 4095;
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard()
+    {
+        if (ok && prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+}  // namespace
+
+struct deft_knapsack {
+    deft_knapsack_config_t cfg{};
+    int compute_units = 0;
+    int64_t scratch_bytes = 0;
+
+    int seq_path = 0;  // 0 none, 1 wave LDS, 2 workgroup LDS, 3 global rows
+    SeqLdsPlan lds_plan{};
+    uint32_t *keep = nullptr;  // LDS path: keep table
+    SeqGlobalPlan glob_plan{};
+    void *glob_scratch = nullptr;
+
+    int joint_path = 0;
+    JointPlan joint_plan{};
+    void *joint_scratch = nullptr;
+
+    bool profiling = false;
+    Profiler prof;
+};
+
+namespace {
+
+void free_handle(deft_knapsack *h)
+{
+    if (!h) return;
+    DeviceGuard g(h->cfg.device);
+    if (h->keep) (void)hipFree(h->keep);
+    if (h->glob_scratch) (void)hipFree(h->glob_scratch);
+    if (h->joint_scratch) (void)hipFree(h->joint_scratch);
+    h->prof.destroy();
+    delete h;
+}
+
+deft_status_t alloc(void **p, int64_t bytes, int64_t *total)
+{
+    *p = nullptr;
+    if (bytes <= 0) return DEFT_OK;
+    hipError_t e = hipMalloc(p, (size_t)bytes);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return DEFT_ERR_OOM;
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return DEFT_ERR_DEVICE;
+    }
+    *total += bytes;
+    return DEFT_OK;
+}
+
+}  // namespace
+
+extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knapsack_t **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return DEFT_ERR_INVALID_ARG;
+    if (cfg->flags != 0 || cfg->device < 0 || cfg->max_batch < 1 || cfg->max_items < 1 ||
+        cfg->max_knapsacks < 1 || cfg->max_capacity < 0 || cfg->max_c1 < 0 || cfg->max_c2 < 0)
+        return DEFT_ERR_INVALID_ARG;
+    const bool want_seq = cfg->max_capacity > 0;
+    const bool want_joint = cfg->max_c1 > 0 || cfg->max_c2 > 0;
+    if (!want_seq && !want_joint) return DEFT_ERR_INVALID_ARG;
+    if (cfg->max_items > kMaxItems || cfg->max_knapsacks > kMaxKnapsacks || cfg->max_batch > kMaxBatch ||
+        cfg->max_capacity > kMaxCapacity || cfg->max_c1 > kMaxJointCapacity ||
+        cfg->max_c2 > kMaxJointCapacity)
+        return DEFT_ERR_LIMIT;
+    if (want_joint && cfg->max_knapsacks < 2) return DEFT_ERR_INVALID_ARG;
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess) {
+        (void)hipGetLastError();
+        return DEFT_ERR_DEVICE;
+    }
+    if (cfg->device >= ndev) return DEFT_ERR_INVALID_ARG;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) {
+        (void)hipGetLastError();
+        return DEFT_ERR_DEVICE;
+    }
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return DEFT_ERR_DEVICE;
+
+    DeviceGuard g(cfg->device);
+    if (!g.ok) return DEFT_ERR_DEVICE;
+
+    deft_knapsack *h = new (std::nothrow) deft_knapsack;
+    if (!h) return DEFT_ERR_OOM;
+    h->cfg = *cfg;
+    h->compute_units = prop.multiProcessorCount;
+
+    deft_status_t st = DEFT_OK;
+    if (want_seq) {
+        const int lds_wg = (int)prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin
+                                                                : (int)prop.sharedMemPerBlock;
+        const int lds_cu = (int)prop.maxSharedMemoryPerMultiProcessor;
+        if (seq_lds_plan(cfg->max_capacity, cfg->max_items, lds_cu, lds_wg, &h->lds_plan) &&
+            seq_lds_prepare(&h->lds_plan) == hipSuccess) {
+            h->seq_path = h->lds_plan.threads == 64 ? 1 : 2;
+            st = alloc(reinterpret_cast<void **>(&h->keep),
+                       h->lds_plan.keep_words_per_inst * 4 * (int64_t)cfg->max_batch, &h->scratch_bytes);
+        } else {
+            (void)hipGetLastError();
+            h->seq_path = 3;
+            seq_global_plan(cfg->max_capacity, cfg->max_items, cfg->max_batch, &h->glob_plan);
+            st = alloc(&h->glob_scratch, h->glob_plan.scratch_bytes, &h->scratch_bytes);
+        }
+    }
+    if (st == DEFT_OK && want_joint) {
+        h->joint_path = 1;
+        joint_plan(cfg->max_c1, cfg->max_c2, cfg->max_items, cfg->max_batch, &h->joint_plan);
+        st = alloc(&h->joint_scratch, h->joint_plan.scratch_bytes, &h->scratch_bytes);
+    }
+    if (st != DEFT_OK) {
+        free_handle(h);
+        return st;
+    }
+    *out = h;
+    return DEFT_OK;
+}
+
+extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *b)
+{
+    if (!h || !b) return DEFT_ERR_INVALID_ARG;
+    if (b->mode != DEFT_MODE_SEQUENTIAL && b->mode != DEFT_MODE_JOINT2) return DEFT_ERR_INVALID_ARG;
+    if (b->batch < 0 || b->item_stride < 1 || b->knap_stride < 1) return DEFT_ERR_INVALID_ARG;
+    if (b->mode == DEFT_MODE_JOINT2 && b->knap_stride < 2) return DEFT_ERR_INVALID_ARG;
+    if (!b->n_items || !b->n_knapsacks || !b->weights || !b->values || !b->capacities || !b->total_value ||
+        !b->knap_value || !b->knap_load || !b->assignment || !b->status)
+        return DEFT_ERR_INVALID_ARG;
+    if (b->batch > h->cfg.max_batch || b->item_stride > h->cfg.max_items ||
+        b->knap_stride > h->cfg.max_knapsacks)
+        return DEFT_ERR_LIMIT;
+    if (b->mode == DEFT_MODE_SEQUENTIAL && h->seq_path == 0) return DEFT_ERR_LIMIT;
+    if (b->mode == DEFT_MODE_JOINT2 && h->joint_path == 0) return DEFT_ERR_LIMIT;
+    if (b->batch == 0) return DEFT_OK;
+
+    DeviceGuard g(h->cfg.device);
+    if (!g.ok) return DEFT_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(b->stream);
+
+    BatchArgs a;
+    a.batch = b->batch;
+    a.item_stride = b->item_stride;
+    a.knap_stride = b->knap_stride;
+    a.max_capacity = h->cfg.max_capacity;
+    a.max_c1 = h->cfg.max_c1;
+    a.max_c2 = h->cfg.max_c2;
+    a.n_items = b->n_items;
+    a.n_knapsacks = b->n_knapsacks;
+    a.weights = b->weights;
+    a.values = b->values;
+    a.capacities = b->capacities;
+    a.fill_order = b->fill_order;
+    a.total_value = b->total_value;
+    a.knap_value = b->knap_value;
+    a.knap_load = b->knap_load;
+    a.assignment = b->assignment;
+    a.status = b->status;
+
+    Profiler *prof = h->profiling ? &h->prof : nullptr;
+    if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
+
+    hipError_t e = hipSuccess;
+    if (b->mode == DEFT_MODE_SEQUENTIAL) {
+        if (h->seq_path == 3) {
+            e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof);
+        } else {
+            if (prof) prof->sweep_begin(st);
+            e = seq_lds_launch(h->lds_plan, a, h->keep, st);
+            if (prof) prof->sweep_end(st);
+        }
+    } else {
+        e = joint_launch(h->joint_plan, a, h->joint_scratch, st, prof);
+    }
+    if (prof) prof->end(st);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return DEFT_ERR_DEVICE;
+    }
+    return DEFT_OK;
+}
+
+extern "C" void deft_knapsack_destroy(deft_knapsack_t *h) { free_handle(h); }
+
+extern "C" deft_status_t deft_knapsack_get_info(const deft_knapsack_t *h, deft_knapsack_info_t *info)
+{
+    if (!h || !info) return DEFT_ERR_INVALID_ARG;
+    std::memset(info, 0, sizeof(*info));
+    info->scratch_bytes = h->scratch_bytes;
+    info->seq_path = h->seq_path;
+    if (h->seq_path == 1 || h->seq_path == 2) {
+        info->seq_threads = h->lds_plan.threads;
+        info->seq_cells_per_thread = h->lds_plan.cells_per_thread;
+        info->seq_lds_bytes = h->lds_plan.lds_bytes;
+        info->seq_workgroups_per_cu = h->lds_plan.wg_per_cu;
+    } else if (h->seq_path == 3) {
+        info->seq_threads = h->glob_plan.threads;
+        info->seq_cells_per_thread = h->glob_plan.cells_per_thread;
+    }
+    info->joint_path = h->joint_path;
+    info->compute_units = h->compute_units;
+    return DEFT_OK;
+}
+
+extern "C" deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t enable)
+{
+    if (!h) return DEFT_ERR_INVALID_ARG;
+    h->profiling = enable != 0;
+    return DEFT_OK;
+}
+
+extern "C" deft_status_t deft_knapsack_get_profile(deft_knapsack_t *h, deft_knapsack_profile_t *out)
+{
+    if (!h || !out || !h->profiling) return DEFT_ERR_INVALID_ARG;
+    DeviceGuard g(h->cfg.device);
+    if (!g.ok) return DEFT_ERR_DEVICE;
+    return h->prof.read(out);
+}
+
+extern "C" const char *deft_knapsack_status_string(int32_t s)
+{
+    switch (s) {
+    case DEFT_OK: return "DEFT_OK";
+    case DEFT_ERR_INVALID_ARG: return "DEFT_ERR_INVALID_ARG";
+    case DEFT_ERR_LIMIT: return "DEFT_ERR_LIMIT";
+    case DEFT_ERR_OVERFLOW: return "DEFT_ERR_OVERFLOW";
+    case DEFT_ERR_OOM: return "DEFT_ERR_OOM";
+    case DEFT_ERR_DEVICE: return "DEFT_ERR_DEVICE";
+    default: return "DEFT_ERR_UNKNOWN";
+    }
+}

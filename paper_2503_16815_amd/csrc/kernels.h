@@ -1,0 +1,89 @@
+// Internal interface between the C ABI (api.hip) and the kernel files.
+// Nothing here is visible to users of include/deft_knapsack.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/deft_knapsack.h"
+
+namespace deft {
+
+// Arguments of one solve call as the kernels see them (all device pointers).
+struct BatchArgs {
+    int32_t batch, item_stride, knap_stride;
+    int32_t max_capacity, max_c1, max_c2;  // create-time limits (per-instance LIMIT status)
+    const int32_t *n_items, *n_knapsacks, *weights, *values, *capacities, *fill_order;
+    int64_t *total_value;
+    int32_t *knap_value, *knap_load, *assignment, *status;
+};
+
+// ---- sequential mode, capacity row resident in LDS (seq_lds.hip) ------------
+// One instance is owned by `threads` lanes (64 = one wavefront, several
+// instances per workgroup; otherwise one workgroup).  Each lane keeps
+// `cells_per_thread` row cells in registers.
+struct SeqLdsPlan {
+    int32_t variant;           // index into the compiled (threads, cells_per_thread) table
+    int32_t threads;           // T
+    int32_t cells_per_thread;  // K
+    int32_t keep_words;        // 32-bit keep words per lane and item: ceil(K / 32)
+    int32_t row_cells;         // LDS row length (multiple of 64, covers max_capacity)
+    int32_t n_pad;             // item slots in LDS (multiple of 4, >= max_items)
+    int32_t lds_bytes;         // dynamic LDS per workgroup
+    int32_t wg_threads;        // workgroup size
+    int32_t inst_per_wg;       // instances per workgroup
+    int32_t wg_per_cu;         // co-resident workgroups (runtime's occupancy answer)
+    int64_t keep_words_per_inst;  // max_items * keep_words * T
+};
+
+// Picks the variant for the limits; returns false when no LDS variant fits.
+bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_cu_bytes,
+                  int32_t lds_per_wg_bytes, SeqLdsPlan *plan);
+// Sets the kernel's dynamic-LDS attribute and queries occupancy.
+hipError_t seq_lds_prepare(SeqLdsPlan *plan);
+hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, uint32_t *keep,
+                          hipStream_t stream);
+
+// ---- per-call HIP-event timing (profile.hip) ---------------------------------
+class Profiler {
+public:
+    bool begin(hipStream_t st);        // start of a profiled call
+    void sweep_begin(hipStream_t st);  // brackets one launch of the DP sweep kernel
+    void sweep_end(hipStream_t st);
+    void end(hipStream_t st);
+    deft_status_t read(deft_knapsack_profile_t *out);  // waits for the call to finish
+    void destroy();
+
+private:
+    hipEvent_t next();
+    hipEvent_t *ev_ = nullptr;
+    int cap_ = 0, used_ = 0;
+    bool failed_ = false, have_call_ = false;
+};
+
+// ---- sequential mode, rows in global memory (seq_global.hip) -------------------
+// For capacities whose row does not fit LDS.  One launch per offered item: the
+// row ping-pongs between two global buffers, keep bits go out as 64-bit words.
+struct SeqGlobalPlan {
+    int32_t threads, cells_per_thread;
+    int32_t row_len;           // int32 cells per row buffer (multiple of the tile)
+    int32_t keep_words;        // 64-bit keep words per item
+    int32_t max_items, max_batch;
+    int64_t scratch_bytes;     // rows + keep + offered-item lists + per-instance state
+};
+void seq_global_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, SeqGlobalPlan *plan);
+hipError_t seq_global_launch(const SeqGlobalPlan &plan, const BatchArgs &args, void *scratch,
+                             hipStream_t stream, Profiler *prof);
+
+// ---- joint two-link mode, table in global memory (joint2.hip) -----------------
+struct JointPlan {
+    int32_t pitch;             // int32 cells per table row (multiple of 64)
+    int32_t rows;              // max_c1 + 1
+    int32_t max_items, max_batch;
+    int64_t scratch_bytes;
+};
+void joint_plan(int32_t max_c1, int32_t max_c2, int32_t max_items, int32_t max_batch, JointPlan *plan);
+hipError_t joint_launch(const JointPlan &plan, const BatchArgs &args, void *scratch, hipStream_t stream,
+                        Profiler *prof);
+
+}  // namespace deft
