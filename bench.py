@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Throughput of the batched knapsack solver on one MI355X.
+
+A step is one pass of the whole hot path (validation, every stage's DP sweep,
+keep-table stream, traceback, outputs) over one synthetic batch resident in
+HBM.  Prints ONE JSON line: DP cell-updates/s (touched cells, counted by the CPU
+oracle), instances/s, the LDS roofline of the sweep kernel from HIP events on
+the launch stream, and the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X figures used for the rooflines
+N_CU = 256
+CLOCK_HZ = 2.4e9
+LDS_BYTES_PER_CLK_PER_CU = 128
+PEAK_LDS_GBS = N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9      # 78643 GB/s
+PEAK_INT_LANE_OPS = N_CU * 64 * CLOCK_HZ                              # 39.3e12 int32 lane-ops/s
+PEAK_HBM_GBS = 8000.0
+
+
+def make_workload(name: str, batch_scale: float):
+    from paper_2503_16815_amd import workloads as W
+    sc = lambda b: max(1, int(round(b * batch_scale)))
+    if name == "resnet101":
+        calls = [W.resnet101_shaped(k=k, batch=sc(1024)) for k in (1, 2, 3, 4)]
+        desc = f"ResNet-101-shaped: 4 calls (k=1..4, m=2k), each batch {sc(1024)}, n=314, windows 11800/5900 +-10%, v=w"
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+    elif name == "vgg19":
+        calls = [W.vgg19_shaped(k=k, batch=sc(4096)) for k in (1, 2, 3, 4)]
+        desc = f"VGG-19-shaped: 4 calls (k=1..4, m=2k), each batch {sc(4096)}, n=38, windows 9300/3700, v=w"
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+    elif name == "gpt2":
+        calls = [W.gpt2_shaped(batch=sc(256))]
+        desc = f"GPT-2-shaped: batch {sc(256)}, n=148, windows 381000/169000 (1 us units), v=w*U[1,4]"
+        algo = dict(bound="hbm", bytes_per_cell=8.125, ops_per_cell=4.0)
+    elif name == "hetero":
+        calls = [W.hetero_joint(batch=sc(256))]
+        desc = f"two-link joint DP: batch {sc(256)}, n=64, C1=C2=512"
+        algo = dict(bound="hbm", bytes_per_cell=8.25, ops_per_cell=6.0)
+    elif name == "tiny":
+        calls = [W.tiny_bruteforce(batch=sc(64))]
+        desc = f"Tiny: batch {sc(64)}, n=16, capacities 500/250"
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+    else:
+        raise SystemExit(f"unknown workload {name}")
+    return calls, desc, algo
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet101",
+                    choices=["resnet101", "vgg19", "gpt2", "hetero", "tiny"])
+    ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (instances are independent; sharding is by "
+              "instance index and is not part of this build); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2503_16815_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    calls, desc, algo = make_workload(args.workload, args.batch_scale)
+    seq = calls[0].mode == 0
+    cap = max(int(kb.capacities.max()) for kb in calls)
+    limits = dict(max_batch=max(kb.batch for kb in calls), max_items=max(kb.item_stride for kb in calls),
+                  max_knapsacks=max(kb.knap_stride for kb in calls))
+    if seq:
+        limits["max_capacity"] = cap
+    else:
+        limits["max_c1"] = max(int(kb.capacities[:, 0].max()) for kb in calls)
+        limits["max_c2"] = max(int(kb.capacities[:, 1].max()) for kb in calls)
+
+    # ---- CPU oracle: cell counts for the metric, reference outputs, cpu_baseline
+    from oracle import oracle
+    oracle.build()
+    threads = min(os.cpu_count() or 1, 16)
+    cpu = None
+    refs = []
+    t_cpu = 0.0
+    for kb in calls:
+        t0 = time.perf_counter()
+        refs.append(oracle.solve_batch(kb, nthreads=threads))
+        t_cpu += time.perf_counter() - t0
+    touched = [int(r.touched_cells.sum()) for r in refs]
+    table = [int(r.table_cells.sum()) for r in refs]
+    cells_step = sum(touched)
+    inst_step = sum(kb.batch for kb in calls)
+    if not args.no_cpu:
+        cpu = dict(value=cells_step / t_cpu, unit="cell-updates/s", cores=int(refs[0].threads), kind="oracle",
+                   sample=f"the full step ({inst_step} instances, {cells_step} cell-updates), "
+                          f"instances split statically over {int(refs[0].threads)} threads, {t_cpu:.2f} s wall",
+                   instances_per_s=inst_step / t_cpu)
+
+    # ---- GPU
+    dev = torch.device("cuda", 0)
+    stream = torch.cuda.Stream(device=dev)
+    with binding.DeftKnapsack(device=0, **limits) as h:
+        info = h.info()
+        dbs = [h.upload(kb) for kb in calls]
+        torch.cuda.synchronize(dev)
+
+        def step():
+            for db in dbs:
+                h.solve_batch(db, stream)
+
+        for _ in range(args.warmup):
+            step()
+        stream.synchronize()
+        torch.cuda.synchronize(dev)
+        h.set_profiling(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        stream.synchronize()
+        torch.cuda.synchronize(dev)
+        t1 = time.perf_counter()
+        prof = h.get_profile()
+        h.set_profiling(False)
+
+        parity = True
+        for db, ref in zip(dbs, refs):
+            o = db.out
+            parity &= bool(np.array_equal(o.status.cpu().numpy(), ref.status))
+            parity &= bool(np.array_equal(o.total_value.cpu().numpy(), ref.total_value))
+            parity &= bool(np.array_equal(o.knap_value.cpu().numpy(), ref.knap_value))
+            parity &= bool(np.array_equal(o.knap_load.cpu().numpy(), ref.knap_load))
+            parity &= bool(np.array_equal(o.assignment.cpu().numpy(), ref.assignment))
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    value = cells_step / (ms_step * 1e-3)
+    launches = int(prof.sweep_launches)
+    sweep_s = float(prof.sweep_ms) * 1e-3
+    algo_bytes_total = cells_step * args.steps * algo["bytes_per_cell"]
+    achieved_gbs = algo_bytes_total / sweep_s / 1e9 if sweep_s > 0 else 0.0
+    peak = PEAK_LDS_GBS if algo["bound"] == "lds" else PEAK_HBM_GBS
+    roofline = dict(
+        bound=algo["bound"], achieved=achieved_gbs, peak=peak, unit="GB/s", frac=achieved_gbs / peak,
+        traffic=None,
+        kernel="seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep" if seq else "jt_sweep"),
+        bytes_per_cell=algo["bytes_per_cell"], launches=launches,
+        avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
+        algorithmic_bytes_per_launch=algo_bytes_total / max(launches, 1),
+        sweep_cell_updates_per_s=cells_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
+        alu=dict(ops_per_cell=algo["ops_per_cell"], peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
+                 frac=(cells_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
+                 if sweep_s > 0 else 0.0))
+    line = dict(
+        metric="knapsack DP cell-updates/sec", value=value, unit="cell-updates/s", n_gpus=1,
+        steps=args.steps, warmup=args.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
+        vs_baseline=None, dtype="int32", data="synthetic",
+        config=dict(workload=desc, instances_per_step=inst_step, cell_updates_per_step=cells_step,
+                    table_cells_per_step=sum(table), seq_path=int(info.seq_path),
+                    threads_per_instance=int(info.seq_threads), cells_per_thread=int(info.seq_cells_per_thread),
+                    lds_bytes_per_workgroup=int(info.seq_lds_bytes),
+                    workgroups_per_cu=int(info.seq_workgroups_per_cu), scratch_bytes=int(info.scratch_bytes)),
+        instances_per_s=inst_step / (ms_step * 1e-3), parity_vs_oracle=parity,
+        profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
+                     sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
+        roofline=roofline, cpu_baseline=cpu)
+    print(json.dumps(line))
+    return 0 if parity else 3
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -151,17 +151,19 @@ typedef struct {
 deft_status_t deft_knapsack_get_info(const deft_knapsack_t *h, deft_knapsack_info_t *info);
 
 typedef struct {
-    float total_ms;        /* first launch to last launch of the last profiled call        */
+    float total_ms;        /* summed duration of the profiled calls (first to last launch) */
     float sweep_ms;        /* summed duration of the DP sweep kernel launches              */
     int32_t sweep_launches;
-    float other_ms;        /* set-up and traceback launches outside the sweep kernel       */
+    float other_ms;        /* total_ms - sweep_ms: set-up, traceback, launch gaps          */
 } deft_knapsack_profile_t;
 
-/* Turn per-call HIP-event timing on (1) or off (0); off by default. */
+/* Turn HIP-event timing of solve calls on (1) or off (0); off by default.
+ * Events are recorded on each call's stream; nothing waits until they are read. */
 deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t enable);
 
-/* Wait for the last profiled call to finish and read its timings.
- * INVALID_ARG if profiling is off or no call has been made. */
+/* Wait for the last profiled call to finish, return the sums over every call
+ * made since profiling was enabled or last read, and start a new sum.
+ * INVALID_ARG if profiling is off or no call has been made since. */
 deft_status_t deft_knapsack_get_profile(deft_knapsack_t *h, deft_knapsack_profile_t *out);
 
 /* Static string for a status code ("DEFT_OK", ...); never NULL. */

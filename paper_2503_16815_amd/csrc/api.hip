@@ -240,6 +240,7 @@ extern "C" deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t
 {
     if (!h) return DEFT_ERR_INVALID_ARG;
     h->profiling = enable != 0;
+    h->prof.reset();
     return DEFT_OK;
 }
 

@@ -47,18 +47,26 @@ hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, uint32_
 // ---- per-call HIP-event timing (profile.hip) ---------------------------------
 class Profiler {
 public:
+    void reset() { ncall_ = nsweep_ = 0; failed_ = false; }
     bool begin(hipStream_t st);        // start of a profiled call
     void sweep_begin(hipStream_t st);  // brackets one launch of the DP sweep kernel
     void sweep_end(hipStream_t st);
     void end(hipStream_t st);
-    deft_status_t read(deft_knapsack_profile_t *out);  // waits for the call to finish
+    // waits for the last recorded call, sums every call since reset(), resets
+    deft_status_t read(deft_knapsack_profile_t *out);
     void destroy();
 
 private:
-    hipEvent_t next();
-    hipEvent_t *ev_ = nullptr;
-    int cap_ = 0, used_ = 0;
-    bool failed_ = false, have_call_ = false;
+    struct Pool {
+        hipEvent_t *ev = nullptr;
+        int cap = 0;
+        hipEvent_t get(int i);  // event i, created on demand; nullptr on failure
+        void destroy();
+    };
+    void record(Pool &p, int idx, hipStream_t st);
+    Pool call_, sweep_;
+    int ncall_ = 0, nsweep_ = 0;  // events used (two per call / per launch)
+    bool failed_ = false;
 };
 
 // ---- sequential mode, rows in global memory (seq_global.hip) -------------------

@@ -67,3 +67,86 @@ def test_random_ragged_every_lds_variant(binding, oracle, cap_hi, max_capacity):
     kt = W.random_sequential(2000 + cap_hi, batch=19, n_max=60, m_max=3, w_hi=max(9, cap_hi // 40),
                              v_hi=9, cap_hi=cap_hi, ties=True)
     run(binding, oracle, kt, max_capacity=max_capacity)
+
+
+def test_global_row_path_large_capacity(binding, oracle):
+    """Rows too long for LDS go through the global-memory path: several 2048-cell
+    wave chunks, a ragged tail, ragged n/m, random fill order."""
+    kb = W.random_sequential(3001, batch=9, n_max=40, m_max=3, w_hi=9000, v_hi=5000, cap_hi=70000)
+    run(binding, oracle, kb, max_capacity=70000)
+    kt = W.random_sequential(3002, batch=5, n_max=50, m_max=2, w_hi=3000, v_hi=9, cap_hi=50000, ties=True)
+    run(binding, oracle, kt, max_capacity=50000)
+
+
+def test_joint_two_link(binding, oracle):
+    run(binding, oracle, W.random_joint(4001, batch=21, n_max=30, w_hi=40, v_hi=1000, c1_hi=150, c2_hi=200))
+    run(binding, oracle, W.hetero_joint(batch=6, n=40, c1=200, c2=129))
+    kb = W.random_joint(4002, batch=8, n_max=20, w_hi=6, v_hi=6, c1_hi=40, c2_hi=70, ragged=False)
+    kb.weights[:, 1] = kb.weights[:, 0]
+    kb.values[:] = kb.weights[:, 0]          # w0 == w1 == v: the paper's Problem 2, tie-heavy
+    run(binding, oracle, kb)
+
+
+def test_paper_shaped_batches_reduced(binding, oracle):
+    run(binding, oracle, W.resnet101_shaped(k=4, batch=48))
+    run(binding, oracle, W.vgg19_shaped(k=4, batch=192))
+    run(binding, oracle, W.gpt2_shaped(batch=3))
+    run(binding, oracle, W.hetero_joint(batch=4))
+
+
+def _faulty_sequential():
+    kb = W.random_sequential(61, batch=9, n_max=6, m_max=2, w_hi=9, v_hi=9, cap_hi=20, ragged=False,
+                             permute_order=False)
+    kb.weights[1, 2] = 0
+    kb.values[2, 0] = -1
+    kb.capacities[3, 1] = -5
+    kb.fill_order[4] = [1, 1]
+    kb.values[5, :] = 2 ** 30
+    kb.capacities[6, 0] = 1000
+    kb.n_items[7] = 7
+    kb.n_knapsacks[8] = -1
+    return kb
+
+
+def test_per_instance_status_lds_and_global_paths(binding, oracle):
+    kb = _faulty_sequential()
+    ref = run(binding, oracle, kb, max_capacity=100)
+    assert ref.status.tolist() == [0, 1, 1, 1, 1, 3, 2, 1, 1]
+    run(binding, oracle, kb, max_capacity=50000)           # same data through the global-row path
+    kj = W.random_joint(62, 5, 5, 5, 5, 10, 10, ragged=False)
+    kj.n_knapsacks[1] = 1
+    kj.capacities[2, 1] = 11
+    kj.weights[3, 1, 4] = 0
+    kj.values[4, :] = 2 ** 30
+    refj = run(binding, oracle, kj, max_c1=10, max_c2=10)
+    assert refj.status.tolist() == [0, 1, 2, 1, 3]
+
+
+def test_empty_and_degenerate(binding, oracle):
+    kb = W.random_sequential(71, batch=6, n_max=5, m_max=2, w_hi=9, v_hi=9, cap_hi=20, ragged=False)
+    kb.n_items[0] = 0
+    kb.n_knapsacks[1] = 0
+    kb.capacities[2] = 0
+    kb.weights[3] = 100              # nothing fits
+    kb.values[4] = 0                 # zero values: nothing is ever taken
+    run(binding, oracle, kb)
+    run(binding, oracle, kb, max_capacity=45000)
+
+
+def test_repeat_runs_are_bit_identical(binding, oracle):
+    """The in-place LDS sweep has a read-before-write hazard across wavefronts
+    that the barriers must close: repeated solves must agree exactly."""
+    import torch
+    kb = W.resnet101_shaped(k=2, batch=64)
+    with binding.DeftKnapsack(max_batch=64, max_items=314, max_knapsacks=4,
+                              max_capacity=int(kb.capacities.max())) as h:
+        db = h.upload(kb)
+        first = None
+        for _ in range(5):
+            out = h.solve_batch(db)
+            torch.cuda.synchronize()
+            cur = (out.total_value.clone(), out.assignment.clone(), out.knap_load.clone())
+            if first is None:
+                first = cur
+            else:
+                assert all(torch.equal(a, b) for a, b in zip(first, cur))
