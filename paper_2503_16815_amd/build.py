@@ -12,7 +12,7 @@ PKG = "paper_2503_16815_amd"
 SOURCES = ["api.hip", "profile.hip", "seq_lds.hip", "seq_global.hip", "joint2.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wextra", "-Wno-unused-command-line-argument"]
+         "-Wall", "-Wextra", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def build(verbose: bool = False) -> str:

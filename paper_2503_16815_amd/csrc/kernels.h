@@ -34,14 +34,17 @@ struct SeqLdsPlan {
     int32_t inst_per_wg;       // instances per workgroup
     int32_t wg_per_cu;         // co-resident workgroups (runtime's occupancy answer)
     int64_t keep_words_per_inst;  // max_items * keep_words * T
+    int32_t max_items;
+    int64_t items_offset;      // byte offset of the offered-item lists in the scratch
+    int64_t scratch_bytes;     // keep table + offered-item lists
 };
 
 // Picks the variant for the limits; returns false when no LDS variant fits.
-bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_cu_bytes,
-                  int32_t lds_per_wg_bytes, SeqLdsPlan *plan);
+bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
+                  SeqLdsPlan *plan);
 // Sets the kernel's dynamic-LDS attribute and queries occupancy.
 hipError_t seq_lds_prepare(SeqLdsPlan *plan);
-hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, uint32_t *keep,
+hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
                           hipStream_t stream);
 
 // ---- per-call HIP-event timing (profile.hip) ---------------------------------

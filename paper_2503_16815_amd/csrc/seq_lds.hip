@@ -14,9 +14,14 @@
 //   barrier
 // The textbook reverse sweep (c from C down to w) exists to read old values
 // only; reading everything before the barrier gives the same result.
-// Cells below w are not touched: a wavefront skips 64-cell segments that lie
-// wholly below w or above C; in the one segment that straddles w the lanes
-// below w read a guard zone holding INT_MIN, which can never win.
+// Cells below w must not change.  A guard zone of kGuardCells cells holding
+// INT_MIN (which can never win) sits below the row: for w <= kGuardCells every
+// lane simply reads row[c - w], landing in the guard when c < w.  Heavier items
+// skip the chunks of segments that lie wholly below w and clamp the remaining
+// reads into the guard.  Segments above C are skipped per wavefront.
+// Where the row's byte offsets fit 16 bits the LDS traffic uses the
+// ds_{read,write}_addtid_b32 forms (address = M0 + immediate + 4 * lane), which
+// need no address register and no address transfer.
 //
 // After the last item of a stage the same lanes trace the selection back
 // from (last offered item, C) through the keep words just written and mark
@@ -29,7 +34,7 @@ namespace deft {
 
 namespace {
 
-constexpr int kGuardCells = 64;
+constexpr int kGuardCells = 256;
 
 template <int T>
 __device__ __forceinline__ void lds_sync()
@@ -75,16 +80,146 @@ __device__ __forceinline__ uint32_t shift_in_take(uint32_t bits, int cand, int o
     return out;
 }
 
+
+typedef __attribute__((address_space(3))) int32_t lds_i32;
+__device__ __forceinline__ uint32_t lds_offset(int32_t *p)
+{
+    return (uint32_t)(uintptr_t)(lds_i32 *)p;
+}
+
+// LDS reads/writes addressed as M0 + OFF + 4 * lane.  M0 is set inside each asm
+// statement, followed by the one wait state the hardware needs between a scalar
+// write of M0 and an add-TID LDS access (the compiler's hazard pass does not look
+// inside asm).  The compiler does not track these accesses either, so every phase
+// ends with an explicit s_waitcnt lgkmcnt(0).
+__device__ __forceinline__ void read_addtid1(int m0, int o0, int &d0)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%2" : "=v"(d0) : "s"(m0), "n"(o0) : "memory", "m0");
+}
+__device__ __forceinline__ void read_addtid2(int m0, int o0, int o1, int &d0, int &d1)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%3\n\tds_read_addtid_b32 %1 offset:%4"
+                 : "=v"(d0), "=v"(d1) : "s"(m0), "n"(o0), "n"(o1) : "memory", "m0");
+}
+__device__ __forceinline__ void read_addtid3(int m0, int o0, int o1, int o2, int &d0, int &d1, int &d2)
+{
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%4\n\tds_read_addtid_b32 %1 offset:%5\n\t"
+                 "ds_read_addtid_b32 %2 offset:%6"
+                 : "=v"(d0), "=v"(d1), "=v"(d2) : "s"(m0), "n"(o0), "n"(o1), "n"(o2) : "memory", "m0");
+}
+__device__ __forceinline__ void read_addtid4(int m0, int o0, int o1, int o2, int o3, int &d0, int &d1, int &d2,
+                                             int &d3)
+{
+    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%5\n\tds_read_addtid_b32 %1 offset:%6\n\t"
+                 "ds_read_addtid_b32 %2 offset:%7\n\tds_read_addtid_b32 %3 offset:%8"
+                 : "=v"(d0), "=v"(d1), "=v"(d2), "=v"(d3) : "s"(m0), "n"(o0), "n"(o1), "n"(o2), "n"(o3) : "memory", "m0");
+}
+__device__ __forceinline__ void write_addtid(int m0, int o0, int d0)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tds_write_addtid_b32 %0 offset:%2" :: "v"(d0), "s"(m0), "n"(o0) : "memory", "m0");
+}
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 struct LdsLayout {
     int32_t row_cells, n_pad, ints_per_inst;
 };
 
-template <int T, int K>
-__global__ void __launch_bounds__(T == 64 ? 256 : T)
-seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t keep_words_per_inst)
+// All offered items of one stage, for a row of NB register slots per lane (NB is a
+// compile-time multiple of the chunk size, so the code is straight-line per item).
+// Slots 0 .. NB-1 cover cells 0 .. NB*T - 1 >= C; the cells above C are swept along and
+// never read back.
+template <int T, int NB, int NW, bool ADDTID>
+__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int tid, int nact,
+                                            const int4 *items, uint32_t *kp)
+{
+    const int wave_first = tid & ~63;  // first lane of this wavefront within the instance
+    int own[NB];
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+        own[k] = 0;
+        row[k * T + tid] = 0;
+    }
+    global_sync<T>();  // zeroed row (LDS) and item list (global) visible to every lane
+
+    const int m0w = uniform((int)row_off + wave_first * 4);
+    int4 cur = nact > 0 ? items[0] : make_int4(0, 1, 0, 0);
+    for (int q = 0; q < nact; ++q) {
+        const int4 nxt = items[min(q + 1, nact - 1)];  // fetched while this item is swept
+        const int t = uniform(cur.x);
+        const int w = uniform(cur.y);
+        const int v = uniform(cur.z);
+        cur = nxt;
+
+        int rd[NB];
+        if (w <= kGuardCells) {
+            // light item: every lane reads row[c - w]; c < w lands in the guard
+            if constexpr (ADDTID) {
+                const int m0r = uniform((int)row_off + (wave_first - w) * 4);
+                constexpr int R4 = NB / 4 * 4;
+#pragma unroll
+                for (int k = NB - 1; k >= NB - R4; k -= 4)
+                    read_addtid4(m0r, k * T * 4, (k - 1) * T * 4, (k - 2) * T * 4, (k - 3) * T * 4, rd[k], rd[k - 1],
+                                 rd[k - 2], rd[k - 3]);
+                if constexpr (NB - R4 == 3) read_addtid3(m0r, 2 * T * 4, 1 * T * 4, 0, rd[2], rd[1], rd[0]);
+                if constexpr (NB - R4 == 2) read_addtid2(m0r, 1 * T * 4, 0, rd[1], rd[0]);
+                if constexpr (NB - R4 == 1) read_addtid1(m0r, 0, rd[0]);
+                wait_lds();
+            } else {
+                const int32_t *src = row + (tid - w);
+#pragma unroll
+                for (int k = NB - 1; k >= 0; --k) rd[k] = src[k * T];
+            }
+        } else {
+            // heavy item (rare): each lane clamps its read index into the guard, so cells
+            // below w read INT_MIN wherever they are
+            const int idx = tid - w;
+#pragma unroll
+            for (int k = NB - 1; k >= 0; --k) rd[k] = row[max(idx + k * T, -1)];
+        }
+        lds_sync<T>();
+
+        uint32_t bits[NW];
+#pragma unroll
+        for (int x = 0; x < NW; ++x) bits[x] = 0;
+#pragma unroll
+        for (int k = NB - 1; k >= 0; --k) {
+            const int cand = rd[k] + v;
+            bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);  // slot k ends at bit k % 32
+            own[k] = max(own[k], cand);
+            if constexpr (ADDTID) write_addtid(m0w, k * T * 4, own[k]);
+            else row[k * T + tid] = own[k];
+        }
+        if constexpr (ADDTID) wait_lds();
+#pragma unroll
+        for (int x = 0; x < NW; ++x) kp[((size_t)t * NW + x) * T + tid] = bits[x];
+        lds_sync<T>();
+    }
+}
+
+// Picks the sweep_stage instance for the stage's chunk count (1 .. N).
+template <int T, int G, int NW, bool ADDTID, int N>
+__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int tid, int nact,
+                                               const int4 *items, uint32_t *kp)
+{
+    if (nchunk == N) {
+        sweep_stage<T, N * G, NW, ADDTID>(row, row_off, tid, nact, items, kp);
+    } else if constexpr (N > 1) {
+        sweep_dispatch<T, G, NW, ADDTID, N - 1>(nchunk, row, row_off, tid, nact, items, kp);
+    }
+}
+
+// WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
+template <int T, int K, int G, int WPE>
+__global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
+seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, int4 *items_all,
+               int max_items)
 {
     extern __shared__ __align__(16) int32_t lds_raw[];
+    static_assert(K <= 64, "at most 64 segments per wavefront");
     constexpr int NW = (K + 31) / 32;
+    static_assert(K % G == 0, "whole chunks");
+    constexpr bool ADDTID = K * T * 4 <= 65536;  // row offsets fit the 16-bit immediate
+    constexpr int NCH = (K + G - 1) / G;
     constexpr int LOG_T = (T == 64) ? 6 : (T == 256) ? 8 : (T == 512) ? 9 : 10;
     static_assert((1 << LOG_T) == T, "T must be 64, 256, 512 or 1024");
 
@@ -95,9 +230,9 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t 
 
     int32_t *guard = lds_raw + (size_t)sub * lay.ints_per_inst;
     int32_t *row = guard + kGuardCells;
+    const uint32_t row_off = lds_offset(row);
     int16_t *asg = reinterpret_cast<int16_t *>(row + lay.row_cells);
-    int16_t *act = asg + lay.n_pad;
-    int32_t *misc = reinterpret_cast<int32_t *>(act + lay.n_pad);
+    int32_t *misc = reinterpret_cast<int32_t *>(asg + lay.n_pad);
     // misc: [0] fault flags, [1] offered-item count, [2..3] value sum, [4..5] fill-order seen mask
 
     const int n = a.n_items[inst];
@@ -111,6 +246,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t 
     int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
     int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
     uint32_t *kp = keep + (size_t)inst * keep_words_per_inst;
+    int4 *items = items_all + (size_t)inst * max_items;  // offered items of the stage: (index, w, v, -)
 
     // ---- per-instance validation -------------------------------------------
     if (tid < 6) misc[tid] = 0;
@@ -167,7 +303,6 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t 
     }
 
     // ---- stages ----------------------------------------------------------------
-    const int wave_first = tid & ~63;  // first lane index of this wavefront within the instance
     long long total = 0;
     for (int s = 0; s < m; ++s) {
         const int j = uniform(ord ? ord[s] : s);
@@ -178,59 +313,19 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t 
             int cnt = 0;
             for (int i0 = 0; i0 < n; i0 += 64) {
                 const int i = i0 + tid;
-                const bool f = i < n && asg[i] < 0 && W[i] <= C;
+                const int w = i < n ? W[i] : 0;
+                const bool f = i < n && asg[i] < 0 && w <= C;
                 const unsigned long long mask = __ballot(f);
-                if (f) act[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = (int16_t)i;
+                if (f) items[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = make_int4(i, w, V[i], 0);
                 cnt += __popcll(mask);
             }
             if (tid == 0) misc[1] = cnt;
         }
 
-        // 64-cell segments [k*T + wave_first, +64) with k < kmax hold cells <= C
-        const int kmax = uniform(C >= wave_first ? ((C - wave_first) >> LOG_T) + 1 : 0);
-        int own[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            own[k] = 0;
-            if (k < kmax) row[k * T + tid] = 0;
-        }
+        const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
         lds_sync<T>();
         const int nact = uniform(misc[1]);
-
-        for (int q = 0; q < nact; ++q) {
-            const int t = uniform(act[q]);
-            const int w = uniform(W[t]);
-            const int v = uniform(V[t]);
-            // first segment of this wavefront that reaches cell w
-            const int kmin = uniform(max(0, w - wave_first - 63 + T - 1) >> LOG_T);
-            const int32_t *src = row + (tid - w);
-            int rd[K];
-#pragma unroll
-            for (int k = K - 1; k >= 0; --k)
-                if (k >= kmin && k < kmax) rd[k] = src[k * T];
-            lds_sync<T>();
-
-            uint32_t bits[NW];
-#pragma unroll
-            for (int x = 0; x < NW; ++x) bits[x] = 0;
-#pragma unroll
-            for (int k = K - 1; k >= 0; --k) {
-                if (k >= kmin && k < kmax) {
-                    const int cand = rd[k] + v;
-                    bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);
-                    own[k] = max(own[k], cand);
-                    row[k * T + tid] = own[k];
-                }
-            }
-            // the lowest processed slot of word x sits at bit 0: move it to its place
-#pragma unroll
-            for (int x = 0; x < NW; ++x) {
-                const int sh = kmin - 32 * x;
-                if (sh > 0) bits[x] = sh < 32 ? bits[x] << sh : 0u;
-                kp[((size_t)t * NW + x) * T + tid] = bits[x];
-            }
-            lds_sync<T>();
-        }
+        sweep_dispatch<T, G, NW, ADDTID, NCH>(nchunk, row, row_off, tid, nact, items, kp);
 
         const int value = uniform(row[C]);
 
@@ -239,8 +334,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t 
         if (tid == 0) {
             int c = C;
             for (int q = nact - 1; q >= 0; --q) {
-                const int t = act[q];
-                const int w = W[t];
+                const int4 it = items[q];
+                const int t = it.x, w = it.y;
                 if (w <= c) {
                     const int k = c >> LOG_T, lane = c & (T - 1);
                     const uint32_t word = __hip_atomic_load(
@@ -264,46 +359,45 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *__restrict__ keep, int64_t 
 }
 
 struct Variant {
-    int threads, cells;
+    int threads, cells, chunk;
     const void *fn;
 };
 
-#define DEFT_VARIANT(T, K) { T, K, reinterpret_cast<const void *>(&seq_lds_kernel<T, K>) }
+#define DEFT_VARIANT(T, K, G, WPE) { T, K, G, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, G, WPE>) }
 const Variant kVariants[] = {
-    DEFT_VARIANT(64, 16),    // capacity <= 1023: one wavefront per instance, four per workgroup
-    DEFT_VARIANT(256, 16),   // <= 4095
-    DEFT_VARIANT(256, 32),   // <= 8191
-    DEFT_VARIANT(256, 51),   // <= 13055
-    DEFT_VARIANT(512, 51),   // <= 26111
-    DEFT_VARIANT(1024, 40),  // <= 40959 (if LDS allows)
+    DEFT_VARIANT(64, 16, 4, 5),    // capacity <= 1023: one wavefront per instance, four per workgroup
+    DEFT_VARIANT(256, 16, 4, 7),   // <= 4095
+    DEFT_VARIANT(256, 32, 4, 4),   // <= 8191
+    DEFT_VARIANT(256, 51, 3, 3),   // <= 13055
+    DEFT_VARIANT(512, 51, 3, 2),   // <= 26111
+    DEFT_VARIANT(1024, 40, 4, 4),  // <= 40959 (if LDS allows)
 };
 #undef DEFT_VARIANT
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-template <int T, int K>
-hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, hipStream_t st)
+template <int T, int K, int G, int WPE>
+hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, int4 *items, hipStream_t st)
 {
     const LdsLayout lay{p.row_cells, p.n_pad, p.lds_bytes / p.inst_per_wg / 4};
     const unsigned grid = (unsigned)((a.batch + p.inst_per_wg - 1) / p.inst_per_wg);
-    hipLaunchKernelGGL((seq_lds_kernel<T, K>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
-                       a, lay, keep, p.keep_words_per_inst);
+    hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
+                       a, lay, keep, p.keep_words_per_inst, items, p.max_items);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_cu_bytes,
-                  int32_t lds_per_wg_bytes, SeqLdsPlan *plan)
+bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
+                  SeqLdsPlan *plan)
 {
-    (void)lds_per_cu_bytes;
-    const int64_t nseg = (int64_t)max_capacity / 64 + 1;
-    const int32_t n_pad = (max_items + 3) & ~3;
+    const int32_t n_pad = (max_items + 7) & ~7;  // int16 slots; keeps the ints after them 8-byte aligned
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
-        const int64_t seg_per_slot = v.threads / 64;
-        if (nseg > (int64_t)v.cells * seg_per_slot) continue;
-        const int64_t row_cells = nseg * 64;
-        const int64_t per_inst = (kGuardCells + row_cells) * 4 + (int64_t)n_pad * 4 + 8 * 4;
+        // register slots needed by lane 0, rounded up to whole chunks
+        const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
+        if (slots > v.cells) continue;
+        const int64_t row_cells = slots * v.threads;
+        const int64_t per_inst = (kGuardCells + row_cells) * 4 + (int64_t)n_pad * 2 + 8 * 4;
         const int inst_per_wg = v.threads == 64 ? 4 : 1;
         const int64_t lds = per_inst * inst_per_wg;
         if (lds > lds_per_wg_bytes) continue;
@@ -318,6 +412,9 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_cu_by
         plan->inst_per_wg = inst_per_wg;
         plan->wg_per_cu = 0;
         plan->keep_words_per_inst = (int64_t)max_items * plan->keep_words * v.threads;
+        plan->max_items = max_items;
+        plan->items_offset = (plan->keep_words_per_inst * 4 * max_batch + 255) & ~(int64_t)255;
+        plan->scratch_bytes = plan->items_offset + (int64_t)max_batch * max_items * 16;
         return true;
     }
     return false;
@@ -335,15 +432,17 @@ hipError_t seq_lds_prepare(SeqLdsPlan *plan)
     return nb > 0 ? hipSuccess : hipErrorInvalidConfiguration;
 }
 
-hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, hipStream_t st)
+hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
 {
+    uint32_t *keep = static_cast<uint32_t *>(scratch);
+    int4 *items = reinterpret_cast<int4 *>(static_cast<char *>(scratch) + p.items_offset);
     switch (p.variant) {
-    case 0: return launch_one<64, 16>(p, a, keep, st);
-    case 1: return launch_one<256, 16>(p, a, keep, st);
-    case 2: return launch_one<256, 32>(p, a, keep, st);
-    case 3: return launch_one<256, 51>(p, a, keep, st);
-    case 4: return launch_one<512, 51>(p, a, keep, st);
-    case 5: return launch_one<1024, 40>(p, a, keep, st);
+    case 0: return launch_one<64, 16, 4, 5>(p, a, keep, items, st);
+    case 1: return launch_one<256, 16, 4, 7>(p, a, keep, items, st);
+    case 2: return launch_one<256, 32, 4, 4>(p, a, keep, items, st);
+    case 3: return launch_one<256, 51, 3, 3>(p, a, keep, items, st);
+    case 4: return launch_one<512, 51, 3, 2>(p, a, keep, items, st);
+    case 5: return launch_one<1024, 40, 4, 4>(p, a, keep, items, st);
     default: return hipErrorInvalidValue;
     }
 }
