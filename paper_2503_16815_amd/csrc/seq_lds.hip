@@ -130,7 +130,7 @@ struct LdsLayout {
 // never read back.
 template <int T, int NB, int NW, bool ADDTID>
 __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int tid, int nact,
-                                            const int4 *items, uint32_t *kp)
+                                            const int4 *items, uint32_t *kp, int max_items)
 {
     const int wave_first = tid & ~63;  // first lane of this wavefront within the instance
     int own[NB];
@@ -190,8 +190,10 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             else row[k * T + tid] = own[k];
         }
         if constexpr (ADDTID) wait_lds();
+        if (t >= 0 && t < max_items) {  // always true for a well-formed item list
 #pragma unroll
-        for (int x = 0; x < NW; ++x) kp[((size_t)t * NW + x) * T + tid] = bits[x];
+            for (int x = 0; x < NW; ++x) kp[((size_t)t * NW + x) * T + tid] = bits[x];
+        }
         lds_sync<T>();
     }
 }
@@ -199,12 +201,12 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 // Picks the sweep_stage instance for the stage's chunk count (1 .. N).
 template <int T, int G, int NW, bool ADDTID, int N>
 __device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int tid, int nact,
-                                               const int4 *items, uint32_t *kp)
+                                               const int4 *items, uint32_t *kp, int max_items)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID>(row, row_off, tid, nact, items, kp);
+        sweep_stage<T, N * G, NW, ADDTID>(row, row_off, tid, nact, items, kp, max_items);
     } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, N - 1>(nchunk, row, row_off, tid, nact, items, kp);
+        sweep_dispatch<T, G, NW, ADDTID, N - 1>(nchunk, row, row_off, tid, nact, items, kp, max_items);
     }
 }
 
@@ -324,31 +326,84 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
 
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
         lds_sync<T>();
-        const int nact = uniform(misc[1]);
-        sweep_dispatch<T, G, NW, ADDTID, NCH>(nchunk, row, row_off, tid, nact, items, kp);
+        const int nact = min(uniform(misc[1]), max_items);
+        sweep_dispatch<T, G, NW, ADDTID, NCH>(nchunk, row, row_off, tid, nact, items, kp, max_items);
 
         const int value = uniform(row[C]);
 
         // ---- traceback ------------------------------------------------------------
+        // One wavefront walks the keep words back from (last offered item, C).  The
+        // walk is a chain of dependent loads, so six steps are taken per memory round
+        // trip: lane L in [2^d, 2^(d+1)) assumes the decisions spelled by the bits of
+        // L below its leading one for the items q .. q-d+1 (most significant first)
+        // and fetches the keep bit of item q-d at the capacity those decisions leave;
+        // a ballot then gives all 63 answers and the true path is read off it.
         global_sync<T>();
-        if (tid == 0) {
+        if (tid < 64) {
+            const int L = tid;
+            const int d = 31 - __clz(L | 1);
+            const int p = L - (1 << d);
+            // Every index is range-checked before it is used; a violation (never expected)
+            // marks the instance DEFT_ERR_DEVICE instead of touching memory.
+            bool broken = false;
+            auto fetch = [&](int qq) {
+                const bool have = L < 6 && qq - L >= 0;
+                int4 r = make_int4(0, 0, 0, 0);
+                if (have) {
+                    if (qq - L < max_items) r = items[qq - L]; else broken = true;
+                }
+                return r;
+            };
             int c = C;
-            for (int q = nact - 1; q >= 0; --q) {
-                const int4 it = items[q];
-                const int t = it.x, w = it.y;
-                if (w <= c) {
-                    const int k = c >> LOG_T, lane = c & (T - 1);
-                    const uint32_t word = __hip_atomic_load(
-                        &kp[((size_t)t * NW + (k >> 5)) * T + lane], __ATOMIC_RELAXED,
-                        __HIP_MEMORY_SCOPE_AGENT);
-                    if ((word >> (k & 31)) & 1u) {
-                        asg[t] = (int16_t)j;
-                        c -= w;
+            int q = nact - 1;
+            int4 it = fetch(q);
+            while (q >= 0) {
+                int wv[6], tv[6];
+#pragma unroll
+                for (int i = 0; i < 6; ++i) {
+                    tv[i] = __builtin_amdgcn_readlane(it.x, i);
+                    wv[i] = __builtin_amdgcn_readlane(it.y, i);
+                }
+                const int qn = q - 6;
+                const int4 itn = fetch(qn);  // next round's items
+                int cl = c, wd = wv[0], td = tv[0];
+#pragma unroll
+                for (int i = 0; i < 5; ++i) {
+                    if (i < d && ((p >> (d - 1 - i)) & 1)) cl -= wv[i];
+                    if (d == i + 1) { wd = wv[i + 1]; td = tv[i + 1]; }
+                }
+                uint32_t bit = 0;
+                // lane L tests item q-d; items past the head of the list (q-d < 0) carry w = 0
+                // and are excluded here, so cl never leaves [-5*C, C]
+                if (L >= 1 && q - d >= 0 && cl >= 0 && wd <= cl) {
+                    const int k = cl >> LOG_T, lane = cl & (T - 1);
+                    if (td >= 0 && td < max_items && k < K && cl <= C) {
+                        const uint32_t word = __hip_atomic_load(&kp[((size_t)td * NW + (k >> 5)) * T + lane],
+                                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        bit = (word >> (k & 31)) & 1u;
+                    } else {
+                        broken = true;
                     }
                 }
+                const unsigned long long takes = __ballot(bit != 0);
+                int node = 1;
+#pragma unroll
+                for (int i = 0; i < 6; ++i) {
+                    const int b = (int)((takes >> node) & 1ull);
+                    if (b) {
+                        if (L == 0 && tv[i] >= 0 && tv[i] < lay.n_pad) asg[tv[i]] = (int16_t)j;
+                        c -= wv[i];
+                    }
+                    node = 2 * node + b;
+                }
+                q = qn;
+                it = itn;
             }
-            out_kv[j] = value;
-            out_kl[j] = C - c;
+            if (L == 0) {
+                out_kv[j] = value;
+                out_kl[j] = C - c;
+            }
+            if (__ballot(broken) != 0ull && L == 0) a.status[inst] = DEFT_ERR_DEVICE;
         }
         total += value;
         lds_sync<T>();
