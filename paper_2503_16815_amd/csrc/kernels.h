@@ -27,6 +27,7 @@ struct SeqLdsPlan {
     int32_t threads;           // T
     int32_t cells_per_thread;  // K
     int32_t keep_words;        // 32-bit keep words per lane and item: ceil(K / 32)
+    int32_t guard_cells;       // INT_MIN cells below the row
     int32_t row_cells;         // LDS row length (multiple of 64, covers max_capacity)
     int32_t n_pad;             // item slots in LDS (multiple of 4, >= max_items)
     int32_t lds_bytes;         // dynamic LDS per workgroup
@@ -35,8 +36,7 @@ struct SeqLdsPlan {
     int32_t wg_per_cu;         // co-resident workgroups (runtime's occupancy answer)
     int64_t keep_words_per_inst;  // max_items * keep_words * T
     int32_t max_items;
-    int64_t items_offset;      // byte offset of the offered-item lists in the scratch
-    int64_t scratch_bytes;     // keep table + offered-item lists
+    int64_t scratch_bytes;     // keep table
 };
 
 // Picks the variant for the limits; returns false when no LDS variant fits.

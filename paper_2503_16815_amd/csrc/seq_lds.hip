@@ -14,8 +14,8 @@
 //   barrier
 // The textbook reverse sweep (c from C down to w) exists to read old values
 // only; reading everything before the barrier gives the same result.
-// Cells below w must not change.  A guard zone of kGuardCells cells holding
-// INT_MIN (which can never win) sits below the row: for w <= kGuardCells every
+// Cells below w must not change.  A guard zone of 64..256 cells holding
+// INT_MIN (which can never win) sits below the row: for w <= guard size every
 // lane simply reads row[c - w], landing in the guard when c < w.  Heavier items
 // skip the chunks of segments that lie wholly below w and clamp the remaining
 // reads into the guard.  Segments above C are skipped per wavefront.
@@ -27,6 +27,7 @@
 // from (last offered item, C) through the keep words just written and mark
 // the chosen items, which the next stage then leaves out.
 #include <limits.h>
+#include <stdlib.h>
 
 #include "kernels.h"
 
@@ -34,7 +35,7 @@ namespace deft {
 
 namespace {
 
-constexpr int kGuardCells = 256;
+constexpr int kMaxGuardCells = 256;  // guard zone below the row, in cells (multiple of 64)
 
 template <int T>
 __device__ __forceinline__ void lds_sync()
@@ -82,6 +83,17 @@ __device__ __forceinline__ uint32_t shift_in_take(uint32_t bits, int cand, int o
 
 
 typedef __attribute__((address_space(3))) int32_t lds_i32;
+// Read-only inputs seen through the constant address space: a load at a uniform
+// index becomes a scalar load (its own counter, no wait behind keep-table stores).
+typedef const int32_t __attribute__((address_space(4))) const_i32;
+__device__ __forceinline__ const const_i32 *as_constant(const int32_t *p)
+{
+    // the pointer is the same in every lane of the instance; say so to the compiler
+    const uintptr_t v = (uintptr_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (const const_i32 *)(((uintptr_t)hi << 32) | lo);
+}
 __device__ __forceinline__ uint32_t lds_offset(int32_t *p)
 {
     return (uint32_t)(uintptr_t)(lds_i32 *)p;
@@ -121,7 +133,7 @@ __device__ __forceinline__ void write_addtid(int m0, int o0, int d0)
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 struct LdsLayout {
-    int32_t row_cells, n_pad, ints_per_inst;
+    int32_t guard_cells, row_cells, n_pad, ints_per_inst;
 };
 
 // All offered items of one stage, for a row of NB register slots per lane (NB is a
@@ -129,8 +141,9 @@ struct LdsLayout {
 // Slots 0 .. NB-1 cover cells 0 .. NB*T - 1 >= C; the cells above C are swept along and
 // never read back.
 template <int T, int NB, int NW, bool ADDTID>
-__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int tid, int nact,
-                                            const int4 *items, uint32_t *kp, int max_items)
+__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int guard_cells, int tid, int nact,
+                                            const int16_t *act, const const_i32 *W, const const_i32 *V,
+                                            uint32_t *kp, int max_items)
 {
     const int wave_first = tid & ~63;  // first lane of this wavefront within the instance
     int own[NB];
@@ -139,19 +152,16 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
         own[k] = 0;
         row[k * T + tid] = 0;
     }
-    global_sync<T>();  // zeroed row (LDS) and item list (global) visible to every lane
+    lds_sync<T>();  // zeroed row and item list visible to every lane
 
     const int m0w = uniform((int)row_off + wave_first * 4);
-    int4 cur = nact > 0 ? items[0] : make_int4(0, 1, 0, 0);
+    int tn = nact > 0 ? uniform(act[0]) : 0;
+    int wn = W[tn], vn = V[tn];
     for (int q = 0; q < nact; ++q) {
-        const int4 nxt = items[min(q + 1, nact - 1)];  // fetched while this item is swept
-        const int t = uniform(cur.x);
-        const int w = uniform(cur.y);
-        const int v = uniform(cur.z);
-        cur = nxt;
+        const int t = tn, w = wn, v = vn;
 
         int rd[NB];
-        if (w <= kGuardCells) {
+        if (w <= guard_cells) {
             // light item: every lane reads row[c - w]; c < w lands in the guard
             if constexpr (ADDTID) {
                 const int m0r = uniform((int)row_off + (wave_first - w) * 4);
@@ -163,7 +173,6 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
                 if constexpr (NB - R4 == 3) read_addtid3(m0r, 2 * T * 4, 1 * T * 4, 0, rd[2], rd[1], rd[0]);
                 if constexpr (NB - R4 == 2) read_addtid2(m0r, 1 * T * 4, 0, rd[1], rd[0]);
                 if constexpr (NB - R4 == 1) read_addtid1(m0r, 0, rd[0]);
-                wait_lds();
             } else {
                 const int32_t *src = row + (tid - w);
 #pragma unroll
@@ -176,7 +185,14 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 #pragma unroll
             for (int k = NB - 1; k >= 0; --k) rd[k] = row[max(idx + k * T, -1)];
         }
+        // next item: its index is read behind the row reads, its weight and value come
+        // by scalar loads that stay in flight while this item is swept
+        const int tn_raw = act[min(q + 1, nact - 1)];
+        if constexpr (ADDTID) wait_lds();  // the add-TID reads above are not tracked by the compiler
         lds_sync<T>();
+        tn = uniform(tn_raw);
+        wn = W[tn];
+        vn = V[tn];
 
         uint32_t bits[NW];
 #pragma unroll
@@ -200,21 +216,22 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 
 // Picks the sweep_stage instance for the stage's chunk count (1 .. N).
 template <int T, int G, int NW, bool ADDTID, int N>
-__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int tid, int nact,
-                                               const int4 *items, uint32_t *kp, int max_items)
+__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int guard_cells, int tid,
+                                               int nact,
+                                               const int16_t *act, const const_i32 *W, const const_i32 *V,
+                                               uint32_t *kp, int max_items)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID>(row, row_off, tid, nact, items, kp, max_items);
+        sweep_stage<T, N * G, NW, ADDTID>(row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
     } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, N - 1>(nchunk, row, row_off, tid, nact, items, kp, max_items);
+        sweep_dispatch<T, G, NW, ADDTID, N - 1>(nchunk, row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
     }
 }
 
 // WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
 template <int T, int K, int G, int WPE>
 __global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
-seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, int4 *items_all,
-               int max_items)
+seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, int max_items)
 {
     extern __shared__ __align__(16) int32_t lds_raw[];
     static_assert(K <= 64, "at most 64 segments per wavefront");
@@ -231,9 +248,10 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     if (inst >= a.batch) return;  // whole wavefront (T == 64) or never (grid == batch)
 
     int32_t *guard = lds_raw + (size_t)sub * lay.ints_per_inst;
-    int32_t *row = guard + kGuardCells;
+    int32_t *row = guard + lay.guard_cells;
     const uint32_t row_off = lds_offset(row);
-    int16_t *asg = reinterpret_cast<int16_t *>(row + lay.row_cells);
+    int16_t *act = reinterpret_cast<int16_t *>(row + lay.row_cells);  // offered items of the stage
+    int8_t *asg = reinterpret_cast<int8_t *>(act + lay.n_pad);       // knapsack id per item, -1 = unplaced
     int32_t *misc = reinterpret_cast<int32_t *>(asg + lay.n_pad);
     // misc: [0] fault flags, [1] offered-item count, [2..3] value sum, [4..5] fill-order seen mask
 
@@ -248,11 +266,11 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
     int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
     uint32_t *kp = keep + (size_t)inst * keep_words_per_inst;
-    int4 *items = items_all + (size_t)inst * max_items;  // offered items of the stage: (index, w, v, -)
+    const const_i32 *Wc = as_constant(W), *Vc = as_constant(V);
 
     // ---- per-instance validation -------------------------------------------
     if (tid < 6) misc[tid] = 0;
-    if (tid < kGuardCells) guard[tid] = INT_MIN;
+    for (int i = tid; i < lay.guard_cells; i += T) guard[i] = INT_MIN;
     for (int i = tid; i < lay.n_pad; i += T) asg[i] = -1;
     lds_sync<T>();
     {
@@ -318,7 +336,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 const int w = i < n ? W[i] : 0;
                 const bool f = i < n && asg[i] < 0 && w <= C;
                 const unsigned long long mask = __ballot(f);
-                if (f) items[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = make_int4(i, w, V[i], 0);
+                if (f) act[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = (int16_t)i;
                 cnt += __popcll(mask);
             }
             if (tid == 0) misc[1] = cnt;
@@ -327,7 +345,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
         lds_sync<T>();
         const int nact = min(uniform(misc[1]), max_items);
-        sweep_dispatch<T, G, NW, ADDTID, NCH>(nchunk, row, row_off, tid, nact, items, kp, max_items);
+        sweep_dispatch<T, G, NW, ADDTID, NCH>(nchunk, row, row_off, lay.guard_cells, tid, nact, act, Wc, Vc, kp,
+                                              max_items);
 
         const int value = uniform(row[C]);
 
@@ -346,17 +365,18 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             // Every index is range-checked before it is used; a violation (never expected)
             // marks the instance DEFT_ERR_DEVICE instead of touching memory.
             bool broken = false;
-            auto fetch = [&](int qq) {
+            auto fetch = [&](int qq) {  // lane L < 6 fetches (index, weight) of item qq - L
                 const bool have = L < 6 && qq - L >= 0;
-                int4 r = make_int4(0, 0, 0, 0);
+                int2 r = make_int2(0, 0);
                 if (have) {
-                    if (qq - L < max_items) r = items[qq - L]; else broken = true;
+                    const int t = qq - L < max_items ? (int)act[qq - L] : -1;
+                    if (t >= 0 && t < n) { r.x = t; r.y = W[t]; } else broken = true;
                 }
                 return r;
             };
             int c = C;
             int q = nact - 1;
-            int4 it = fetch(q);
+            int2 it = fetch(q);
             while (q >= 0) {
                 int wv[6], tv[6];
 #pragma unroll
@@ -365,7 +385,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                     wv[i] = __builtin_amdgcn_readlane(it.y, i);
                 }
                 const int qn = q - 6;
-                const int4 itn = fetch(qn);  // next round's items
+                const int2 itn = fetch(qn);  // next round's items
                 int cl = c, wd = wv[0], td = tv[0];
 #pragma unroll
                 for (int i = 0; i < 5; ++i) {
@@ -391,7 +411,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 for (int i = 0; i < 6; ++i) {
                     const int b = (int)((takes >> node) & 1ull);
                     if (b) {
-                        if (L == 0 && tv[i] >= 0 && tv[i] < lay.n_pad) asg[tv[i]] = (int16_t)j;
+                        if (L == 0 && tv[i] >= 0 && tv[i] < lay.n_pad) asg[tv[i]] = (int8_t)j;
                         c -= wv[i];
                     }
                     node = 2 * node + b;
@@ -431,12 +451,12 @@ const Variant kVariants[] = {
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 template <int T, int K, int G, int WPE>
-hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, int4 *items, hipStream_t st)
+hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, hipStream_t st)
 {
-    const LdsLayout lay{p.row_cells, p.n_pad, p.lds_bytes / p.inst_per_wg / 4};
+    const LdsLayout lay{p.guard_cells, p.row_cells, p.n_pad, p.lds_bytes / p.inst_per_wg / 4};
     const unsigned grid = (unsigned)((a.batch + p.inst_per_wg - 1) / p.inst_per_wg);
     hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
-                       a, lay, keep, p.keep_words_per_inst, items, p.max_items);
+                       a, lay, keep, p.keep_words_per_inst, p.max_items);
     return hipGetLastError();
 }
 
@@ -445,14 +465,19 @@ hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, i
 bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
                   SeqLdsPlan *plan)
 {
-    const int32_t n_pad = (max_items + 7) & ~7;  // int16 slots; keeps the ints after them 8-byte aligned
+    const int32_t n_pad = (max_items + 7) & ~7;  // item slots in LDS; keeps what follows 8-byte aligned
+    int guard = kMaxGuardCells;
+    if (const char *e = getenv("DEFT_GUARD_CELLS")) {  // tuning aid: 64, 128, 192 or 256
+        const int g = atoi(e);
+        if (g == 64 || g == 128 || g == 192 || g == 256) guard = g;
+    }
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         // register slots needed by lane 0, rounded up to whole chunks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
         if (slots > v.cells) continue;
         const int64_t row_cells = slots * v.threads;
-        const int64_t per_inst = (kGuardCells + row_cells) * 4 + (int64_t)n_pad * 2 + 8 * 4;
+        const int64_t per_inst = (guard + row_cells) * 4 + (int64_t)n_pad * 3 + 8 * 4;
         const int inst_per_wg = v.threads == 64 ? 4 : 1;
         const int64_t lds = per_inst * inst_per_wg;
         if (lds > lds_per_wg_bytes) continue;
@@ -460,6 +485,7 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, in
         plan->threads = v.threads;
         plan->cells_per_thread = v.cells;
         plan->keep_words = (v.cells + 31) / 32;
+        plan->guard_cells = guard;
         plan->row_cells = (int32_t)row_cells;
         plan->n_pad = n_pad;
         plan->lds_bytes = (int32_t)lds;
@@ -468,8 +494,7 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, in
         plan->wg_per_cu = 0;
         plan->keep_words_per_inst = (int64_t)max_items * plan->keep_words * v.threads;
         plan->max_items = max_items;
-        plan->items_offset = (plan->keep_words_per_inst * 4 * max_batch + 255) & ~(int64_t)255;
-        plan->scratch_bytes = plan->items_offset + (int64_t)max_batch * max_items * 16;
+        plan->scratch_bytes = plan->keep_words_per_inst * 4 * max_batch;
         return true;
     }
     return false;
@@ -490,14 +515,13 @@ hipError_t seq_lds_prepare(SeqLdsPlan *plan)
 hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
 {
     uint32_t *keep = static_cast<uint32_t *>(scratch);
-    int4 *items = reinterpret_cast<int4 *>(static_cast<char *>(scratch) + p.items_offset);
     switch (p.variant) {
-    case 0: return launch_one<64, 16, 4, 5>(p, a, keep, items, st);
-    case 1: return launch_one<256, 16, 4, 7>(p, a, keep, items, st);
-    case 2: return launch_one<256, 32, 4, 4>(p, a, keep, items, st);
-    case 3: return launch_one<256, 51, 3, 3>(p, a, keep, items, st);
-    case 4: return launch_one<512, 51, 3, 2>(p, a, keep, items, st);
-    case 5: return launch_one<1024, 40, 4, 4>(p, a, keep, items, st);
+    case 0: return launch_one<64, 16, 4, 5>(p, a, keep, st);
+    case 1: return launch_one<256, 16, 4, 7>(p, a, keep, st);
+    case 2: return launch_one<256, 32, 4, 4>(p, a, keep, st);
+    case 3: return launch_one<256, 51, 3, 3>(p, a, keep, st);
+    case 4: return launch_one<512, 51, 3, 2>(p, a, keep, st);
+    case 5: return launch_one<1024, 40, 4, 4>(p, a, keep, st);
     default: return hipErrorInvalidValue;
     }
 }
