@@ -15,6 +15,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -65,13 +67,14 @@ def main() -> int:
                     choices=["resnet101", "vgg19", "gpt2", "hetero", "tiny"])
     ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
+    ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
+    ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (instances are independent; sharding is by "
               "instance index and is not part of this build); use --gpus 1", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
     from paper_2503_16815_amd import binding
 
@@ -79,6 +82,13 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     calls, desc, algo = make_workload(args.workload, args.batch_scale)
+    if args.only_k:
+        calls = [kb for kb in calls if kb.meta.get("k") == args.only_k]
+        desc += f" [only k={args.only_k}]"
+    if args.max_stages:
+        for kb in calls:
+            kb.n_knapsacks[:] = np.minimum(kb.n_knapsacks, args.max_stages)
+        desc += f" [n_knapsacks clamped to {args.max_stages}]"
     seq = calls[0].mode == 0
     cap = max(int(kb.capacities.max()) for kb in calls)
     limits = dict(max_batch=max(kb.batch for kb in calls), max_items=max(kb.item_stride for kb in calls),

@@ -140,19 +140,22 @@ struct LdsLayout {
 // compile-time multiple of the chunk size, so the code is straight-line per item).
 // Slots 0 .. NB-1 cover cells 0 .. NB*T - 1 >= C; the cells above C are swept along and
 // never read back.
-template <int T, int NB, int NW, bool ADDTID>
+template <int T, int NB, int NW, bool ADDTID, bool VEQW>
 __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int guard_cells, int tid, int nact,
                                             const int16_t *act, const const_i32 *W, const const_i32 *V,
                                             uint32_t *kp, int max_items)
 {
     const int wave_first = tid & ~63;  // first lane of this wavefront within the instance
+    // VEQW (every value equals its weight, the paper's Problem 1): the row is kept as
+    // row[c] - c, which turns row[c-w] + w into a plain copy of the shifted operand and
+    // saves the add; comparisons and hence take bits are unchanged.
     int own[NB];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
-        own[k] = 0;
-        row[k * T + tid] = 0;
+        own[k] = VEQW ? -(k * T + tid) : 0;
+        row[k * T + tid] = own[k];
     }
-    lds_sync<T>();  // zeroed row and item list visible to every lane
+    lds_sync<T>();  // initial row and item list visible to every lane
 
     const int m0w = uniform((int)row_off + wave_first * 4);
     int tn = nact > 0 ? uniform(act[0]) : 0;
@@ -199,7 +202,7 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
         for (int x = 0; x < NW; ++x) bits[x] = 0;
 #pragma unroll
         for (int k = NB - 1; k >= 0; --k) {
-            const int cand = rd[k] + v;
+            const int cand = VEQW ? rd[k] : rd[k] + v;
             bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);  // slot k ends at bit k % 32
             own[k] = max(own[k], cand);
             if constexpr (ADDTID) write_addtid(m0w, k * T * 4, own[k]);
@@ -215,16 +218,16 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 }
 
 // Picks the sweep_stage instance for the stage's chunk count (1 .. N).
-template <int T, int G, int NW, bool ADDTID, int N>
+template <int T, int G, int NW, bool ADDTID, bool VEQW, int N>
 __device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int guard_cells, int tid,
                                                int nact,
                                                const int16_t *act, const const_i32 *W, const const_i32 *V,
                                                uint32_t *kp, int max_items)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID>(row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
+        sweep_stage<T, N * G, NW, ADDTID, VEQW>(row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
     } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, N - 1>(nchunk, row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
+        sweep_dispatch<T, G, NW, ADDTID, VEQW, N - 1>(nchunk, row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
     }
 }
 
@@ -253,7 +256,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     int16_t *act = reinterpret_cast<int16_t *>(row + lay.row_cells);  // offered items of the stage
     int8_t *asg = reinterpret_cast<int8_t *>(act + lay.n_pad);       // knapsack id per item, -1 = unplaced
     int32_t *misc = reinterpret_cast<int32_t *>(asg + lay.n_pad);
-    // misc: [0] fault flags, [1] offered-item count, [2..3] value sum, [4..5] fill-order seen mask
+    // misc: [0] fault flags (bit 2: some value differs from its weight), [1] offered-item count,
+    //       [2..3] value sum, [4..5] fill-order seen mask
 
     const int n = a.n_items[inst];
     const int m = a.n_knapsacks[inst];
@@ -283,6 +287,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             for (int i = tid; i < n; i += T) {
                 const int w = W[i], v = V[i];
                 if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
+                if (v != w) flags |= 4;
             }
             for (int j = tid; j < m; j += T) {
                 const int c = cap[j];
@@ -304,6 +309,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     }
     lds_sync<T>();
     int status = DEFT_OK;
+    const bool veqw = uniform(misc[0] & 4) == 0;
     {
         const uint32_t flags = (uint32_t)misc[0];
         const unsigned long long vs = *reinterpret_cast<unsigned long long *>(&misc[2]);
@@ -345,10 +351,14 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
         lds_sync<T>();
         const int nact = min(uniform(misc[1]), max_items);
-        sweep_dispatch<T, G, NW, ADDTID, NCH>(nchunk, row, row_off, lay.guard_cells, tid, nact, act, Wc, Vc, kp,
-                                              max_items);
+        if (veqw)
+            sweep_dispatch<T, G, NW, ADDTID, true, NCH>(nchunk, row, row_off, lay.guard_cells, tid, nact, act, Wc, Vc,
+                                                        kp, max_items);
+        else
+            sweep_dispatch<T, G, NW, ADDTID, false, NCH>(nchunk, row, row_off, lay.guard_cells, tid, nact, act, Wc,
+                                                         Vc, kp, max_items);
 
-        const int value = uniform(row[C]);
+        const int value = uniform(row[C]) + (veqw ? C : 0);
 
         // ---- traceback ------------------------------------------------------------
         // One wavefront walks the keep words back from (last offered item, C).  The
@@ -444,6 +454,7 @@ const Variant kVariants[] = {
     DEFT_VARIANT(256, 16, 4, 7),   // <= 4095
     DEFT_VARIANT(256, 32, 4, 4),   // <= 8191
     DEFT_VARIANT(256, 51, 3, 3),   // <= 13055
+    DEFT_VARIANT(512, 26, 2, 4),   // <= 13311
     DEFT_VARIANT(512, 51, 3, 2),   // <= 26111
     DEFT_VARIANT(1024, 40, 4, 4),  // <= 40959 (if LDS allows)
 };
@@ -471,7 +482,10 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, in
         const int g = atoi(e);
         if (g == 64 || g == 128 || g == 192 || g == 256) guard = g;
     }
+    int only = -1;
+    if (const char *e = getenv("DEFT_SEQ_VARIANT")) only = atoi(e);  // tuning aid: force a table entry
     for (int i = 0; i < kNumVariants; ++i) {
+        if (only >= 0 && i != only) continue;
         const Variant &v = kVariants[i];
         // register slots needed by lane 0, rounded up to whole chunks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
@@ -520,8 +534,9 @@ hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
     case 1: return launch_one<256, 16, 4, 7>(p, a, keep, st);
     case 2: return launch_one<256, 32, 4, 4>(p, a, keep, st);
     case 3: return launch_one<256, 51, 3, 3>(p, a, keep, st);
-    case 4: return launch_one<512, 51, 3, 2>(p, a, keep, st);
-    case 5: return launch_one<1024, 40, 4, 4>(p, a, keep, st);
+    case 4: return launch_one<512, 26, 2, 4>(p, a, keep, st);
+    case 5: return launch_one<512, 51, 3, 2>(p, a, keep, st);
+    case 6: return launch_one<1024, 40, 4, 4>(p, a, keep, st);
     default: return hipErrorInvalidValue;
     }
 }
