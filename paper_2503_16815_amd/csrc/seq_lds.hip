@@ -5,23 +5,25 @@
 // lanes.  Cell c of the row lives in lane (c mod T), register slot (c div T),
 // and a copy lives in LDS so that the shifted operand row[c - w] can be read
 // by whichever lane needs it.  Per offered item:
-//   phase 1  every lane reads row[c - w] for its cells          (LDS, 4 B/cell)
-//   barrier
-//   phase 2  cand = row[c - w] + v; take = cand > row[c];
-//            row[c] = max(row[c], cand) kept in registers and written back
-//            (LDS, 4 B/cell); take bits are shifted into one 32-bit word per
-//            32 register slots and stored to the keep table (HBM, 1/8 B/cell)
-//   barrier
+//   phase A  every lane reads row[c - w] for its cells (LDS, 4 B/cell) and, as
+//            the values arrive, computes cand = row[c - w] + v, take = cand >
+//            row[c], row[c] = max(row[c], cand) in registers; the reads run a
+//            fixed number of slots ahead of the arithmetic
+//   barrier  (every lane has read the old row)
+//   phase B  the new cells are written back (LDS, 4 B/cell); the take bits, one
+//            32-bit word per 32 register slots, go to the keep table (HBM,
+//            1/8 B/cell)
+//   barrier  (the new row is visible)
 // The textbook reverse sweep (c from C down to w) exists to read old values
-// only; reading everything before the barrier gives the same result.
-// Cells below w must not change.  A guard zone of 64..256 cells holding
+// only; reading everything before the first barrier gives the same result.
+// Cells below w must not change.  A guard zone of max(256, T) cells holding
 // INT_MIN (which can never win) sits below the row: for w <= guard size every
 // lane simply reads row[c - w], landing in the guard when c < w.  Heavier items
-// skip the chunks of segments that lie wholly below w and clamp the remaining
-// reads into the guard.  Segments above C are skipped per wavefront.
-// Where the row's byte offsets fit 16 bits the LDS traffic uses the
-// ds_{read,write}_addtid_b32 forms (address = M0 + immediate + 4 * lane), which
-// need no address register and no address transfer.
+// clamp each read index into the guard.
+// Where the row's byte offsets fit 16 bits the write-back uses
+// ds_write_addtid_b32 (address = M0 + immediate + 4 * lane), which ships no
+// address and runs at twice the rate of ds_write_b32; the reads are ordinary
+// loads, so the compiler tracks their completion itself.
 //
 // After the last item of a stage the same lanes trace the selection back
 // from (last offered item, C) through the keep words just written and mark
@@ -29,13 +31,16 @@
 #include <limits.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
+
 #include "kernels.h"
 
 namespace deft {
 
 namespace {
 
-constexpr int kMaxGuardCells = 256;  // guard zone below the row, in cells (multiple of 64)
+constexpr int kMinGuardCells = 256;  // guard zone below the row, in cells: max(this, T)
 
 template <int T>
 __device__ __forceinline__ void lds_sync()
@@ -99,37 +104,30 @@ __device__ __forceinline__ uint32_t lds_offset(int32_t *p)
     return (uint32_t)(uintptr_t)(lds_i32 *)p;
 }
 
-// LDS reads/writes addressed as M0 + OFF + 4 * lane.  M0 is set inside each asm
-// statement, followed by the one wait state the hardware needs between a scalar
-// write of M0 and an add-TID LDS access (the compiler's hazard pass does not look
-// inside asm).  The compiler does not track these accesses either, so every phase
-// ends with an explicit s_waitcnt lgkmcnt(0).
-__device__ __forceinline__ void read_addtid1(int m0, int o0, int &d0)
+// LDS write addressed as M0 + OFF + 4 * lane.  M0 is an operand the compiler
+// materialises and keeps across consecutive statements that use the same value.
+// The hardware needs one wait state between a scalar write of M0 and an add-TID
+// access, which the compiler's hazard pass does not know to apply to inline asm:
+// m0_settle() supplies it and must precede the first add-TID access of a run.
+// The compiler does not track these accesses either, so a run ends with an
+// explicit s_waitcnt lgkmcnt(0) before the barrier that publishes it.
+template <int OFF>
+__device__ __forceinline__ void write_addtid(int m0, int d)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%2" : "=v"(d0) : "s"(m0), "n"(o0) : "memory", "m0");
+    asm volatile("ds_write_addtid_b32 %0 offset:%2" ::"v"(d), "{m0}"(m0), "n"(OFF) : "memory");
 }
-__device__ __forceinline__ void read_addtid2(int m0, int o0, int o1, int &d0, int &d1)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%3\n\tds_read_addtid_b32 %1 offset:%4"
-                 : "=v"(d0), "=v"(d1) : "s"(m0), "n"(o0), "n"(o1) : "memory", "m0");
-}
-__device__ __forceinline__ void read_addtid3(int m0, int o0, int o1, int o2, int &d0, int &d1, int &d2)
-{
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%4\n\tds_read_addtid_b32 %1 offset:%5\n\t"
-                 "ds_read_addtid_b32 %2 offset:%6"
-                 : "=v"(d0), "=v"(d1), "=v"(d2) : "s"(m0), "n"(o0), "n"(o1), "n"(o2) : "memory", "m0");
-}
-__device__ __forceinline__ void read_addtid4(int m0, int o0, int o1, int o2, int o3, int &d0, int &d1, int &d2,
-                                             int &d3)
-{
-    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tds_read_addtid_b32 %0 offset:%5\n\tds_read_addtid_b32 %1 offset:%6\n\t"
-                 "ds_read_addtid_b32 %2 offset:%7\n\tds_read_addtid_b32 %3 offset:%8"
-                 : "=v"(d0), "=v"(d1), "=v"(d2), "=v"(d3) : "s"(m0), "n"(o0), "n"(o1), "n"(o2), "n"(o3) : "memory", "m0");
-}
-__device__ __forceinline__ void write_addtid(int m0, int o0, int d0)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tds_write_addtid_b32 %0 offset:%2" :: "v"(d0), "s"(m0), "n"(o0) : "memory", "m0");
-}
+__device__ __forceinline__ void m0_settle(int m0) { asm volatile("s_nop 0" ::"{m0}"(m0) : "memory"); }
+// Calls f(integral_constant<int, k>) for k = K0 down to 0 (compile-time indices for
+// the immediate offsets of the add-TID writes).
+template <int K0>
+struct SlotsDown {
+    template <class F>
+    static __device__ __forceinline__ void all(F &&f)
+    {
+        f(std::integral_constant<int, K0>{});
+        if constexpr (K0 > 0) SlotsDown<K0 - 1>::all(f);
+    }
+};
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 struct LdsLayout {
@@ -145,7 +143,8 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
                                             const int16_t *act, const const_i32 *W, const const_i32 *V,
                                             uint32_t *kp, int max_items)
 {
-    const int wave_first = tid & ~63;  // first lane of this wavefront within the instance
+    constexpr int D = NB < 14 ? NB : 14;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
+    const int wave_first = tid & ~63;     // first lane of this wavefront within the instance
     // VEQW (every value equals its weight, the paper's Problem 1): the row is kept as
     // row[c] - c, which turns row[c-w] + w into a plain copy of the shifted operand and
     // saves the add; comparisons and hence take bits are unchanged.
@@ -162,58 +161,61 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
     int wn = W[tn], vn = V[tn];
     for (int q = 0; q < nact; ++q) {
         const int t = tn, w = wn, v = vn;
-
+        uint32_t bits[NW];
+#pragma unroll
+        for (int x = 0; x < NW; ++x) bits[x] = 0;
         int rd[NB];
+        auto update = [&](int k) {
+            const int cand = VEQW ? rd[k] : rd[k] + v;
+            bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);  // slot k ends at bit k % 32
+            own[k] = max(own[k], cand);
+        };
+        // The order of phase A is pinned: D slots of reads up front, then two slots of
+        // arithmetic for every two further reads.
+        auto phase_a = [&](auto read) {
+#pragma unroll
+            for (int k = NB - 1; k >= NB - D; --k) rd[k] = read(k);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = NB - 1; k >= 0; k -= 2) {
+                update(k);
+                if (k >= 1) update(k - 1);
+                if (k - D >= 0) rd[k - D] = read(k - D);
+                if (k - D - 1 >= 0) rd[k - D - 1] = read(k - D - 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        const int idx = tid - w;
         if (w <= guard_cells) {
             // light item: every lane reads row[c - w]; c < w lands in the guard
-            if constexpr (ADDTID) {
-                const int m0r = uniform((int)row_off + (wave_first - w) * 4);
-                constexpr int R4 = NB / 4 * 4;
-#pragma unroll
-                for (int k = NB - 1; k >= NB - R4; k -= 4)
-                    read_addtid4(m0r, k * T * 4, (k - 1) * T * 4, (k - 2) * T * 4, (k - 3) * T * 4, rd[k], rd[k - 1],
-                                 rd[k - 2], rd[k - 3]);
-                if constexpr (NB - R4 == 3) read_addtid3(m0r, 2 * T * 4, 1 * T * 4, 0, rd[2], rd[1], rd[0]);
-                if constexpr (NB - R4 == 2) read_addtid2(m0r, 1 * T * 4, 0, rd[1], rd[0]);
-                if constexpr (NB - R4 == 1) read_addtid1(m0r, 0, rd[0]);
-            } else {
-                const int32_t *src = row + (tid - w);
-#pragma unroll
-                for (int k = NB - 1; k >= 0; --k) rd[k] = src[k * T];
-            }
+            const int32_t *src = row + idx;
+            phase_a([&](int k) { return src[k * T]; });
         } else {
             // heavy item (rare): each lane clamps its read index into the guard, so cells
             // below w read INT_MIN wherever they are
-            const int idx = tid - w;
-#pragma unroll
-            for (int k = NB - 1; k >= 0; --k) rd[k] = row[max(idx + k * T, -1)];
+            phase_a([&](int k) { return row[max(idx + k * T, -1)]; });
         }
         // next item: its index is read behind the row reads, its weight and value come
-        // by scalar loads that stay in flight while this item is swept
+        // by scalar loads that stay in flight while this item is written back
         const int tn_raw = act[min(q + 1, nact - 1)];
-        if constexpr (ADDTID) wait_lds();  // the add-TID reads above are not tracked by the compiler
-        lds_sync<T>();
+        lds_sync<T>();  // every lane has read the old row
         tn = uniform(tn_raw);
         wn = W[tn];
         vn = V[tn];
 
-        uint32_t bits[NW];
+        if constexpr (ADDTID) {
+            m0_settle(m0w);
+            SlotsDown<NB - 1>::all([&](auto kc) { write_addtid<kc.value * T * 4>(m0w, own[kc.value]); });
+        } else {
 #pragma unroll
-        for (int x = 0; x < NW; ++x) bits[x] = 0;
-#pragma unroll
-        for (int k = NB - 1; k >= 0; --k) {
-            const int cand = VEQW ? rd[k] : rd[k] + v;
-            bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);  // slot k ends at bit k % 32
-            own[k] = max(own[k], cand);
-            if constexpr (ADDTID) write_addtid(m0w, k * T * 4, own[k]);
-            else row[k * T + tid] = own[k];
+            for (int k = NB - 1; k >= 0; --k) row[k * T + tid] = own[k];
         }
-        if constexpr (ADDTID) wait_lds();
         if (t >= 0 && t < max_items) {  // always true for a well-formed item list
 #pragma unroll
             for (int x = 0; x < NW; ++x) kp[((size_t)t * NW + x) * T + tid] = bits[x];
         }
-        lds_sync<T>();
+        if constexpr (ADDTID) wait_lds();
+        lds_sync<T>();  // the new row is visible
     }
 }
 
@@ -477,16 +479,12 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, in
                   SeqLdsPlan *plan)
 {
     const int32_t n_pad = (max_items + 7) & ~7;  // item slots in LDS; keeps what follows 8-byte aligned
-    int guard = kMaxGuardCells;
-    if (const char *e = getenv("DEFT_GUARD_CELLS")) {  // tuning aid: 64, 128, 192 or 256
-        const int g = atoi(e);
-        if (g == 64 || g == 128 || g == 192 || g == 256) guard = g;
-    }
     int only = -1;
     if (const char *e = getenv("DEFT_SEQ_VARIANT")) only = atoi(e);  // tuning aid: force a table entry
     for (int i = 0; i < kNumVariants; ++i) {
         if (only >= 0 && i != only) continue;
         const Variant &v = kVariants[i];
+        const int guard = v.threads > kMinGuardCells ? v.threads : kMinGuardCells;
         // register slots needed by lane 0, rounded up to whole chunks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
         if (slots > v.cells) continue;
