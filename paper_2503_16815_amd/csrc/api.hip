@@ -41,7 +41,7 @@ struct deft_knapsack {
 
     int seq_path = 0;  // 0 none, 1 wave LDS, 2 workgroup LDS, 3 global rows
     SeqLdsPlan lds_plan{};
-    void *keep = nullptr;  // LDS path: keep table + offered-item lists
+    void *keep = nullptr;  // LDS path: keep table, then the offered-item lists
     SeqGlobalPlan glob_plan{};
     void *glob_scratch = nullptr;
 
@@ -126,7 +126,7 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
     if (want_seq) {
         const int lds_wg = (int)prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin
                                                                 : (int)prop.sharedMemPerBlock;
-        if (seq_lds_plan(cfg->max_capacity, cfg->max_items, cfg->max_batch, lds_wg, &h->lds_plan) &&
+        if (seq_lds_plan(cfg->max_capacity, cfg->max_items, cfg->max_knapsacks, cfg->max_batch, lds_wg, &h->lds_plan) &&
             seq_lds_prepare(&h->lds_plan) == hipSuccess) {
             h->seq_path = h->lds_plan.threads == 64 ? 1 : 2;
             st = alloc(&h->keep, h->lds_plan.scratch_bytes, &h->scratch_bytes);

@@ -27,21 +27,21 @@ struct SeqLdsPlan {
     int32_t threads;           // T
     int32_t cells_per_thread;  // K
     int32_t keep_words;        // 32-bit keep words per lane and item: ceil(K / 32)
-    int32_t guard_cells;       // INT_MIN cells below the row
+    int32_t guard_cells;       // cells below the row: 8 scratch words, then INT_MIN
     int32_t row_cells;         // LDS row length (multiple of 64, covers max_capacity)
-    int32_t n_pad;             // item slots in LDS (multiple of 4, >= max_items)
+    int32_t n_pad;             // entries per offered-item list (multiple of 8, >= max_items)
     int32_t lds_bytes;         // dynamic LDS per workgroup
     int32_t wg_threads;        // workgroup size
     int32_t inst_per_wg;       // instances per workgroup
-    int32_t wg_per_cu;         // co-resident workgroups (runtime's occupancy answer)
+    int32_t wg_per_cu;         // co-resident workgroups: the runtime's answer, capped by LDS granules
     int64_t keep_words_per_inst;  // max_items * keep_words * T
-    int32_t max_items;
-    int64_t scratch_bytes;     // keep table
+    int64_t keep_bytes;        // keep table of the whole batch
+    int64_t scratch_bytes;     // keep table + one offered-item list per instance and stage
 };
 
 // Picks the variant for the limits; returns false when no LDS variant fits.
-bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
-                  SeqLdsPlan *plan);
+bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks, int32_t max_batch,
+                  int32_t lds_per_wg_bytes, SeqLdsPlan *plan);
 // Sets the kernel's dynamic-LDS attribute and queries occupancy.
 hipError_t seq_lds_prepare(SeqLdsPlan *plan);
 hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,

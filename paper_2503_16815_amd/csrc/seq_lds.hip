@@ -59,18 +59,21 @@ __device__ __forceinline__ void lds_sync()
     }
 }
 
-// Makes the keep words written by all lanes of the instance visible to the
-// lanes that trace back (global memory, through L2; L1 is bypassed on read).
+// Makes what the lanes of the instance wrote to global memory (keep words, item
+// lists) visible to its other lanes.  All of them run on one compute unit, so
+// workgroup scope is enough: the stores have reached L2 when the wait ends, and the
+// readers go to L2 (scalar loads, and vector loads that bypass L1).  A wider scope
+// would write back and invalidate L2 at every call.
 template <int T>
 __device__ __forceinline__ void global_sync()
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     if constexpr (T == 64) {
         __builtin_amdgcn_wave_barrier();
     } else {
         __builtin_amdgcn_s_barrier();
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -88,16 +91,17 @@ __device__ __forceinline__ uint32_t shift_in_take(uint32_t bits, int cand, int o
 
 
 typedef __attribute__((address_space(3))) int32_t lds_i32;
-// Read-only inputs seen through the constant address space: a load at a uniform
-// index becomes a scalar load (its own counter, no wait behind keep-table stores).
-typedef const int32_t __attribute__((address_space(4))) const_i32;
-__device__ __forceinline__ const const_i32 *as_constant(const int32_t *p)
+// One offered item as the sweep and the traceback see it.
+struct __attribute__((aligned(16))) OfferedItem {
+    int32_t w, v, index, pad;
+};
+typedef const OfferedItem __attribute__((address_space(4))) const_item;
+__device__ __forceinline__ const const_item *as_constant(const OfferedItem *p)
 {
-    // the pointer is the same in every lane of the instance; say so to the compiler
     const uintptr_t v = (uintptr_t)p;
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    return (const const_i32 *)(((uintptr_t)hi << 32) | lo);
+    return (const const_item *)(((uintptr_t)hi << 32) | lo);
 }
 __device__ __forceinline__ uint32_t lds_offset(int32_t *p)
 {
@@ -130,18 +134,21 @@ struct SlotsDown {
 };
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
+// LDS of one instance: [8 ints of scratch][guard_cells - 8 ints of INT_MIN][row_cells].
+// The scratch words are the lowest cells of the guard zone; an item counts as light
+// only if it cannot reach them (w <= guard_cells - 8).
 struct LdsLayout {
-    int32_t guard_cells, row_cells, n_pad, ints_per_inst;
+    int32_t guard_cells, row_cells, ints_per_inst;
 };
+constexpr int kMiscInts = 8;
 
 // All offered items of one stage, for a row of NB register slots per lane (NB is a
 // compile-time multiple of the chunk size, so the code is straight-line per item).
 // Slots 0 .. NB-1 cover cells 0 .. NB*T - 1 >= C; the cells above C are swept along and
 // never read back.
 template <int T, int NB, int NW, bool ADDTID, bool VEQW>
-__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int guard_cells, int tid, int nact,
-                                            const int16_t *act, const const_i32 *W, const const_i32 *V,
-                                            uint32_t *kp, int max_items)
+__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
+                                            const const_item *lst, uint32_t *kp)
 {
     constexpr int D = NB < 14 ? NB : 14;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
     const int wave_first = tid & ~63;     // first lane of this wavefront within the instance
@@ -157,10 +164,11 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
     lds_sync<T>();  // initial row and item list visible to every lane
 
     const int m0w = uniform((int)row_off + wave_first * 4);
-    int tn = nact > 0 ? uniform(act[0]) : 0;
-    int wn = W[tn], vn = V[tn];
+    // The item list is read by scalar loads (their own counter: no wait behind the
+    // keep-table stores), one item ahead.
+    int wn = lst[0].w, vn = lst[0].v;
     for (int q = 0; q < nact; ++q) {
-        const int t = tn, w = wn, v = vn;
+        const int w = wn, v = vn;
         uint32_t bits[NW];
 #pragma unroll
         for (int x = 0; x < NW; ++x) bits[x] = 0;
@@ -186,7 +194,7 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             }
         };
         const int idx = tid - w;
-        if (w <= guard_cells) {
+        if (w <= light_max) {
             // light item: every lane reads row[c - w]; c < w lands in the guard
             const int32_t *src = row + idx;
             phase_a([&](int k) { return src[k * T]; });
@@ -195,13 +203,11 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             // below w read INT_MIN wherever they are
             phase_a([&](int k) { return row[max(idx + k * T, -1)]; });
         }
-        // next item: its index is read behind the row reads, its weight and value come
-        // by scalar loads that stay in flight while this item is written back
-        const int tn_raw = act[min(q + 1, nact - 1)];
         lds_sync<T>();  // every lane has read the old row
-        tn = uniform(tn_raw);
-        wn = W[tn];
-        vn = V[tn];
+        // next item: the scalar loads stay in flight while this one is written back
+        const int qn = min(q + 1, nact - 1);
+        wn = lst[qn].w;
+        vn = lst[qn].v;
 
         if constexpr (ADDTID) {
             m0_settle(m0w);
@@ -210,10 +216,8 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 #pragma unroll
             for (int k = NB - 1; k >= 0; --k) row[k * T + tid] = own[k];
         }
-        if (t >= 0 && t < max_items) {  // always true for a well-formed item list
 #pragma unroll
-            for (int x = 0; x < NW; ++x) kp[((size_t)t * NW + x) * T + tid] = bits[x];
-        }
+        for (int x = 0; x < NW; ++x) kp[((size_t)q * NW + x) * T + tid] = bits[x];  // row q: the q-th offered item
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
     }
@@ -221,22 +225,21 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 
 // Picks the sweep_stage instance for the stage's chunk count (1 .. N).
 template <int T, int G, int NW, bool ADDTID, bool VEQW, int N>
-__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int guard_cells, int tid,
-                                               int nact,
-                                               const int16_t *act, const const_i32 *W, const const_i32 *V,
-                                               uint32_t *kp, int max_items)
+__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
+                                               int nact, const const_item *lst, uint32_t *kp)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID, VEQW>(row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
+        sweep_stage<T, N * G, NW, ADDTID, VEQW>(row, row_off, light_max, tid, nact, lst, kp);
     } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, VEQW, N - 1>(nchunk, row, row_off, guard_cells, tid, nact, act, W, V, kp, max_items);
+        sweep_dispatch<T, G, NW, ADDTID, VEQW, N - 1>(nchunk, row, row_off, light_max, tid, nact, lst, kp);
     }
 }
 
 // WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
 template <int T, int K, int G, int WPE>
 __global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
-seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, int max_items)
+seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, OfferedItem *lists,
+               int list_stride)
 {
     extern __shared__ __align__(16) int32_t lds_raw[];
     static_assert(K <= 64, "at most 64 segments per wavefront");
@@ -252,12 +255,9 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     const int inst = (T == 64) ? (int)blockIdx.x * 4 + sub : (int)blockIdx.x;
     if (inst >= a.batch) return;  // whole wavefront (T == 64) or never (grid == batch)
 
-    int32_t *guard = lds_raw + (size_t)sub * lay.ints_per_inst;
-    int32_t *row = guard + lay.guard_cells;
+    int32_t *misc = lds_raw + (size_t)sub * lay.ints_per_inst;
+    int32_t *row = misc + lay.guard_cells;
     const uint32_t row_off = lds_offset(row);
-    int16_t *act = reinterpret_cast<int16_t *>(row + lay.row_cells);  // offered items of the stage
-    int8_t *asg = reinterpret_cast<int8_t *>(act + lay.n_pad);       // knapsack id per item, -1 = unplaced
-    int32_t *misc = reinterpret_cast<int32_t *>(asg + lay.n_pad);
     // misc: [0] fault flags (bit 2: some value differs from its weight), [1] offered-item count,
     //       [2..3] value sum, [4..5] fill-order seen mask
 
@@ -272,12 +272,13 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
     int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
     uint32_t *kp = keep + (size_t)inst * keep_words_per_inst;
-    const const_i32 *Wc = as_constant(W), *Vc = as_constant(V);
+    // one item list per stage: a list is written once and only then read through the
+    // scalar cache, so no stage can see another stage's entries there
+    OfferedItem *inst_lists = lists + (size_t)inst * a.knap_stride * list_stride;
 
     // ---- per-instance validation -------------------------------------------
-    if (tid < 6) misc[tid] = 0;
-    for (int i = tid; i < lay.guard_cells; i += T) guard[i] = INT_MIN;
-    for (int i = tid; i < lay.n_pad; i += T) asg[i] = -1;
+    if (tid < kMiscInts) misc[tid] = 0;
+    for (int i = kMiscInts + tid; i < lay.guard_cells; i += T) misc[i] = INT_MIN;
     lds_sync<T>();
     {
         uint32_t flags = 0;
@@ -324,17 +325,20 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         for (int j = 0; j < a.knap_stride; ++j) { out_kv[j] = 0; out_kl[j] = 0; }
         a.status[inst] = status;
     }
+    for (int i = tid; i < a.item_stride; i += T) out_asg[i] = -1;
     if (status != DEFT_OK) {
-        for (int i = tid; i < a.item_stride; i += T) out_asg[i] = -1;
         if (tid == 0) a.total_value[inst] = 0;
         return;
     }
 
     // ---- stages ----------------------------------------------------------------
+    // Items already placed: bit (i / 64) of lane (i % 64) of the first wavefront.
+    unsigned long long placed = 0;
     long long total = 0;
     for (int s = 0; s < m; ++s) {
         const int j = uniform(ord ? ord[s] : s);
         const int C = uniform(cap[j]);
+        OfferedItem *list = inst_lists + (size_t)s * list_stride;
 
         // offered items: not yet placed and able to fit at all, ascending index
         if (tid < 64) {
@@ -342,23 +346,29 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             for (int i0 = 0; i0 < n; i0 += 64) {
                 const int i = i0 + tid;
                 const int w = i < n ? W[i] : 0;
-                const bool f = i < n && asg[i] < 0 && w <= C;
+                const int v = i < n ? V[i] : 0;
+                const bool f = i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C;
                 const unsigned long long mask = __ballot(f);
-                if (f) act[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = (int16_t)i;
+                if (f) {
+                    OfferedItem e;
+                    e.w = w; e.v = v; e.index = i; e.pad = 0;
+                    list[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = e;
+                }
                 cnt += __popcll(mask);
             }
             if (tid == 0) misc[1] = cnt;
         }
 
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
-        lds_sync<T>();
-        const int nact = min(uniform(misc[1]), max_items);
+        global_sync<T>();  // the list (global memory) and the count (LDS) are visible
+        const int nact = min(uniform(misc[1]), list_stride);
+        const const_item *lst = as_constant(list);
         if (veqw)
-            sweep_dispatch<T, G, NW, ADDTID, true, NCH>(nchunk, row, row_off, lay.guard_cells, tid, nact, act, Wc, Vc,
-                                                        kp, max_items);
+            sweep_dispatch<T, G, NW, ADDTID, true, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid, nact,
+                                                        lst, kp);
         else
-            sweep_dispatch<T, G, NW, ADDTID, false, NCH>(nchunk, row, row_off, lay.guard_cells, tid, nact, act, Wc,
-                                                         Vc, kp, max_items);
+            sweep_dispatch<T, G, NW, ADDTID, false, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid, nact,
+                                                         lst, kp);
 
         const int value = uniform(row[C]) + (veqw ? C : 0);
 
@@ -377,17 +387,18 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             // Every index is range-checked before it is used; a violation (never expected)
             // marks the instance DEFT_ERR_DEVICE instead of touching memory.
             bool broken = false;
-            auto fetch = [&](int qq) {  // lane L < 6 fetches (index, weight) of item qq - L
+            auto fetch = [&](int qq) {  // lane L < 6 fetches (index, weight) of offered item qq - L
                 const bool have = L < 6 && qq - L >= 0;
                 int2 r = make_int2(0, 0);
                 if (have) {
-                    const int t = qq - L < max_items ? (int)act[qq - L] : -1;
-                    if (t >= 0 && t < n) { r.x = t; r.y = W[t]; } else broken = true;
+                    const OfferedItem e = list[qq - L];
+                    if (e.index >= 0 && e.index < n) { r.x = e.index; r.y = e.w; } else broken = true;
                 }
                 return r;
             };
             int c = C;
             int q = nact - 1;
+            unsigned long long chosen = 0;  // items this stage places, laid out like `placed`
             int2 it = fetch(q);
             while (q >= 0) {
                 int wv[6], tv[6];
@@ -398,20 +409,21 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 }
                 const int qn = q - 6;
                 const int2 itn = fetch(qn);  // next round's items
-                int cl = c, wd = wv[0], td = tv[0];
+                int cl = c, wd = wv[0];
 #pragma unroll
                 for (int i = 0; i < 5; ++i) {
                     if (i < d && ((p >> (d - 1 - i)) & 1)) cl -= wv[i];
-                    if (d == i + 1) { wd = wv[i + 1]; td = tv[i + 1]; }
+                    if (d == i + 1) wd = wv[i + 1];
                 }
                 uint32_t bit = 0;
-                // lane L tests item q-d; items past the head of the list (q-d < 0) carry w = 0
-                // and are excluded here, so cl never leaves [-5*C, C]
+                // lane L tests offered item q-d; items past the head of the list (q-d < 0) carry
+                // w = 0 and are excluded here, so cl never leaves [-5*C, C]
                 if (L >= 1 && q - d >= 0 && cl >= 0 && wd <= cl) {
                     const int k = cl >> LOG_T, lane = cl & (T - 1);
-                    if (td >= 0 && td < max_items && k < K && cl <= C) {
-                        const uint32_t word = __hip_atomic_load(&kp[((size_t)td * NW + (k >> 5)) * T + lane],
-                                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (k < K && cl <= C) {
+                        const uint32_t word =
+                            __hip_atomic_load(&kp[((size_t)(q - d) * NW + (k >> 5)) * T + lane], __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
                         bit = (word >> (k & 31)) & 1u;
                     } else {
                         broken = true;
@@ -423,13 +435,20 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 for (int i = 0; i < 6; ++i) {
                     const int b = (int)((takes >> node) & 1ull);
                     if (b) {
-                        if (L == 0 && tv[i] >= 0 && tv[i] < lay.n_pad) asg[tv[i]] = (int8_t)j;
+                        const int t = tv[i];  // uniform
+                        if (L == (t & 63)) chosen |= 1ull << (t >> 6);
                         c -= wv[i];
                     }
                     node = 2 * node + b;
                 }
                 q = qn;
                 it = itn;
+            }
+            placed |= chosen;
+            while (chosen) {  // outside the walk: no store sits in its chain of loads
+                const int b = __builtin_ctzll(chosen);
+                chosen &= chosen - 1;
+                out_asg[b * 64 + L] = j;
             }
             if (L == 0) {
                 out_kv[j] = value;
@@ -441,7 +460,6 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         lds_sync<T>();
     }
 
-    for (int i = tid; i < a.item_stride; i += T) out_asg[i] = asg[i];
     if (tid == 0) a.total_value[inst] = total;
 }
 
@@ -464,21 +482,28 @@ const Variant kVariants[] = {
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 template <int T, int K, int G, int WPE>
-hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, uint32_t *keep, hipStream_t st)
+hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
 {
-    const LdsLayout lay{p.guard_cells, p.row_cells, p.n_pad, p.lds_bytes / p.inst_per_wg / 4};
+    const LdsLayout lay{p.guard_cells, p.row_cells, p.lds_bytes / p.inst_per_wg / 4};
     const unsigned grid = (unsigned)((a.batch + p.inst_per_wg - 1) / p.inst_per_wg);
+    uint32_t *keep = static_cast<uint32_t *>(scratch);
+    OfferedItem *lists = reinterpret_cast<OfferedItem *>(static_cast<char *>(scratch) + p.keep_bytes);
     hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
-                       a, lay, keep, p.keep_words_per_inst, p.max_items);
+                       a, lay, keep, p.keep_words_per_inst, lists, p.n_pad);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
-                  SeqLdsPlan *plan)
+// LDS is handed out in granules of 1280 bytes, 128 of them per compute unit (measured:
+// three 53760-byte workgroups run together on a CU, three 54016-byte ones do not, whatever
+// the occupancy query says).
+constexpr int kLdsGranule = 1280, kLdsGranulesPerCu = 128;
+
+bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks, int32_t max_batch,
+                  int32_t lds_per_wg_bytes, SeqLdsPlan *plan)
 {
-    const int32_t n_pad = (max_items + 7) & ~7;  // item slots in LDS; keeps what follows 8-byte aligned
+    const int32_t n_pad = (max_items + 7) & ~7;  // list entries per stage (whole 64-byte lines)
     int only = -1;
     if (const char *e = getenv("DEFT_SEQ_VARIANT")) only = atoi(e);  // tuning aid: force a table entry
     for (int i = 0; i < kNumVariants; ++i) {
@@ -489,7 +514,7 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, in
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
         if (slots > v.cells) continue;
         const int64_t row_cells = slots * v.threads;
-        const int64_t per_inst = (guard + row_cells) * 4 + (int64_t)n_pad * 3 + 8 * 4;
+        const int64_t per_inst = (guard + row_cells) * 4;
         const int inst_per_wg = v.threads == 64 ? 4 : 1;
         const int64_t lds = per_inst * inst_per_wg;
         if (lds > lds_per_wg_bytes) continue;
@@ -505,8 +530,8 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, in
         plan->inst_per_wg = inst_per_wg;
         plan->wg_per_cu = 0;
         plan->keep_words_per_inst = (int64_t)max_items * plan->keep_words * v.threads;
-        plan->max_items = max_items;
-        plan->scratch_bytes = plan->keep_words_per_inst * 4 * max_batch;
+        plan->keep_bytes = plan->keep_words_per_inst * 4 * max_batch;
+        plan->scratch_bytes = plan->keep_bytes + (int64_t)max_batch * max_knapsacks * n_pad * (int64_t)sizeof(OfferedItem);
         return true;
     }
     return false;
@@ -520,21 +545,21 @@ hipError_t seq_lds_prepare(SeqLdsPlan *plan)
     int nb = 0;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, plan->wg_threads, (size_t)plan->lds_bytes);
     if (e != hipSuccess) return e;
-    plan->wg_per_cu = nb;
-    return nb > 0 ? hipSuccess : hipErrorInvalidConfiguration;
+    const int by_lds = kLdsGranulesPerCu / ((plan->lds_bytes + kLdsGranule - 1) / kLdsGranule);
+    plan->wg_per_cu = nb < by_lds ? nb : by_lds;
+    return plan->wg_per_cu > 0 ? hipSuccess : hipErrorInvalidConfiguration;
 }
 
 hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
 {
-    uint32_t *keep = static_cast<uint32_t *>(scratch);
     switch (p.variant) {
-    case 0: return launch_one<64, 16, 4, 5>(p, a, keep, st);
-    case 1: return launch_one<256, 16, 4, 7>(p, a, keep, st);
-    case 2: return launch_one<256, 32, 4, 4>(p, a, keep, st);
-    case 3: return launch_one<256, 51, 3, 3>(p, a, keep, st);
-    case 4: return launch_one<512, 26, 2, 4>(p, a, keep, st);
-    case 5: return launch_one<512, 51, 3, 2>(p, a, keep, st);
-    case 6: return launch_one<1024, 40, 4, 4>(p, a, keep, st);
+    case 0: return launch_one<64, 16, 4, 5>(p, a, scratch, st);
+    case 1: return launch_one<256, 16, 4, 7>(p, a, scratch, st);
+    case 2: return launch_one<256, 32, 4, 4>(p, a, scratch, st);
+    case 3: return launch_one<256, 51, 3, 3>(p, a, scratch, st);
+    case 4: return launch_one<512, 26, 2, 4>(p, a, scratch, st);
+    case 5: return launch_one<512, 51, 3, 2>(p, a, scratch, st);
+    case 6: return launch_one<1024, 40, 4, 4>(p, a, scratch, st);
     default: return hipErrorInvalidValue;
     }
 }
