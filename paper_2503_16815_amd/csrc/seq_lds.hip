@@ -16,7 +16,7 @@
 //   barrier  (the new row is visible)
 // The textbook reverse sweep (c from C down to w) exists to read old values
 // only; reading everything before the first barrier gives the same result.
-// Cells below w must not change.  A guard zone of max(256, T) cells holding
+// Cells below w must not change.  A guard zone of 128 or 256 cells holding
 // INT_MIN (which can never win) sits below the row: for w <= guard size every
 // lane simply reads row[c - w], landing in the guard when c < w.  Heavier items
 // clamp each read index into the guard.
@@ -40,7 +40,6 @@ namespace deft {
 
 namespace {
 
-constexpr int kMinGuardCells = 256;  // guard zone below the row, in cells: max(this, T)
 
 template <int T>
 __device__ __forceinline__ void lds_sync()
@@ -465,18 +464,18 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
 
 struct Variant {
     int threads, cells, chunk;
+    int guard;  // cells below the row (8 scratch words + INT_MIN); items up to guard - 8 take the light path
     const void *fn;
 };
 
-#define DEFT_VARIANT(T, K, G, WPE) { T, K, G, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, G, WPE>) }
+#define DEFT_VARIANT(T, K, G, WPE, GUARD) { T, K, G, GUARD, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, G, WPE>) }
 const Variant kVariants[] = {
-    DEFT_VARIANT(64, 16, 4, 5),    // capacity <= 1023: one wavefront per instance, four per workgroup
-    DEFT_VARIANT(256, 16, 4, 7),   // <= 4095
-    DEFT_VARIANT(256, 32, 4, 4),   // <= 8191
-    DEFT_VARIANT(256, 51, 3, 3),   // <= 13055
-    DEFT_VARIANT(512, 26, 2, 4),   // <= 13311
-    DEFT_VARIANT(512, 51, 3, 2),   // <= 26111
-    DEFT_VARIANT(1024, 40, 4, 4),  // <= 40959 (if LDS allows)
+    DEFT_VARIANT(64, 16, 4, 5, 256),    // capacity <= 1023: one wavefront per instance, four per workgroup
+    DEFT_VARIANT(256, 16, 4, 7, 256),   // <= 4095
+    DEFT_VARIANT(256, 32, 4, 4, 256),   // <= 8191
+    DEFT_VARIANT(512, 26, 1, 6, 128),   // <= 13311: with the 128-cell guard three workgroups share a CU's LDS
+    DEFT_VARIANT(512, 51, 3, 2, 256),   // <= 26111
+    DEFT_VARIANT(1024, 40, 4, 4, 256),  // <= 40959 (if LDS allows)
 };
 #undef DEFT_VARIANT
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -509,7 +508,7 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
     for (int i = 0; i < kNumVariants; ++i) {
         if (only >= 0 && i != only) continue;
         const Variant &v = kVariants[i];
-        const int guard = v.threads > kMinGuardCells ? v.threads : kMinGuardCells;
+        const int guard = v.guard;
         // register slots needed by lane 0, rounded up to whole chunks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
         if (slots > v.cells) continue;
@@ -556,10 +555,9 @@ hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
     case 0: return launch_one<64, 16, 4, 5>(p, a, scratch, st);
     case 1: return launch_one<256, 16, 4, 7>(p, a, scratch, st);
     case 2: return launch_one<256, 32, 4, 4>(p, a, scratch, st);
-    case 3: return launch_one<256, 51, 3, 3>(p, a, scratch, st);
-    case 4: return launch_one<512, 26, 2, 4>(p, a, scratch, st);
-    case 5: return launch_one<512, 51, 3, 2>(p, a, scratch, st);
-    case 6: return launch_one<1024, 40, 4, 4>(p, a, scratch, st);
+    case 3: return launch_one<512, 26, 1, 6>(p, a, scratch, st);
+    case 4: return launch_one<512, 51, 3, 2>(p, a, scratch, st);
+    case 5: return launch_one<1024, 40, 4, 4>(p, a, scratch, st);
     default: return hipErrorInvalidValue;
     }
 }
