@@ -30,16 +30,26 @@ PEAK_INT_LANE_OPS = N_CU * 64 * CLOCK_HZ                              # 39.3e12 
 PEAK_HBM_GBS = 8000.0
 
 
-def make_workload(name: str, batch_scale: float):
+def make_workload(name: str, batch_scale: float, per_k_calls: bool):
     from paper_2503_16815_amd import workloads as W
     sc = lambda b: max(1, int(round(b * batch_scale)))
     if name == "resnet101":
-        calls = [W.resnet101_shaped(k=k, batch=sc(1024)) for k in (1, 2, 3, 4)]
-        desc = f"ResNet-101-shaped: 4 calls (k=1..4, m=2k), each batch {sc(1024)}, n=314, windows 11800/5900 +-10%, v=w"
+        if per_k_calls:
+            calls = [W.resnet101_shaped(k=k, batch=sc(1024)) for k in (1, 2, 3, 4)]
+            how = f"4 calls (k=1..4, m=2k), each batch {sc(1024)}"
+        else:
+            calls = [W.resnet101_sweep(batch=sc(1024))]
+            how = f"one call of {4 * sc(1024)} candidate schedules = {sc(1024)} perturbed profiles x k=1..4 (m=2k)"
+        desc = f"ResNet-101-shaped: {how}, n=314, windows 11800/5900 +-10%, v=w"
         algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
     elif name == "vgg19":
-        calls = [W.vgg19_shaped(k=k, batch=sc(4096)) for k in (1, 2, 3, 4)]
-        desc = f"VGG-19-shaped: 4 calls (k=1..4, m=2k), each batch {sc(4096)}, n=38, windows 9300/3700, v=w"
+        if per_k_calls:
+            calls = [W.vgg19_shaped(k=k, batch=sc(4096)) for k in (1, 2, 3, 4)]
+            how = f"4 calls (k=1..4, m=2k), each batch {sc(4096)}"
+        else:
+            calls = [W.vgg19_sweep(batch=sc(4096))]
+            how = f"one call of {4 * sc(4096)} candidate schedules = {sc(4096)} profiles x k=1..4 (m=2k)"
+        desc = f"VGG-19-shaped: {how}, n=38, windows 9300/3700, v=w"
         algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
     elif name == "gpt2":
         calls = [W.gpt2_shaped(batch=sc(256))]
@@ -67,6 +77,9 @@ def main() -> int:
                     choices=["resnet101", "vgg19", "gpt2", "hetero", "tiny"])
     ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
+    ap.add_argument("--per-k-calls", action="store_true",
+                    help="ResNet/VGG shapes: one call per k (4 calls of 1024 / 4096 instances) instead of one call "
+                         "holding the whole sweep over k")
     ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
     ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()
@@ -81,7 +94,7 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
-    calls, desc, algo = make_workload(args.workload, args.batch_scale)
+    calls, desc, algo = make_workload(args.workload, args.batch_scale, args.per_k_calls or bool(args.only_k))
     if args.only_k:
         calls = [kb for kb in calls if kb.meta.get("k") == args.only_k]
         desc += f" [only k={args.only_k}]"

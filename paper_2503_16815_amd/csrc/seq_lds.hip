@@ -88,19 +88,35 @@ __device__ __forceinline__ uint32_t shift_in_take(uint32_t bits, int cand, int o
     return out;
 }
 
-
 typedef __attribute__((address_space(3))) int32_t lds_i32;
 // One offered item as the sweep and the traceback see it.
 struct __attribute__((aligned(16))) OfferedItem {
     int32_t w, v, index, pad;
 };
-typedef const OfferedItem __attribute__((address_space(4))) const_item;
-__device__ __forceinline__ const const_item *as_constant(const OfferedItem *p)
+// Reads the first or second half of a list entry from L2, past the vector L1.  The
+// lists are written and read inside one launch, and the scalar cache is not a way
+// to read them: it can still hold a line from an earlier launch.
+__device__ __forceinline__ int2 load_item_wv(const OfferedItem *e)
+{
+    const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(e), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return make_int2((int)(uint32_t)u, (int)(uint32_t)(u >> 32));
+}
+__device__ __forceinline__ int load_item_index(const OfferedItem *e)
+{
+    return __hip_atomic_load(&e->index, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The same pointer in every lane of the wavefront: says so to the compiler, which then
+// keeps it in scalar registers and addresses memory as scalar base + lane offset.
+template <class P>
+__device__ __forceinline__ P *uniform_ptr(P *p)
 {
     const uintptr_t v = (uintptr_t)p;
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    return (const const_item *)(((uintptr_t)hi << 32) | lo);
+    // rebuilt as a global-memory pointer, so that accesses stay global_* instructions
+    typedef P __attribute__((address_space(1))) GlobalP;
+    return (P *)(GlobalP *)(((uintptr_t)hi << 32) | lo);
 }
 __device__ __forceinline__ uint32_t lds_offset(int32_t *p)
 {
@@ -147,27 +163,36 @@ constexpr int kMiscInts = 8;
 // never read back.
 template <int T, int NB, int NW, bool ADDTID, bool VEQW>
 __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
-                                            const const_item *lst, uint32_t *kp)
+                                            const OfferedItem *list, uint32_t *kp, unsigned long long &nzm)
 {
-    constexpr int D = NB < 14 ? NB : 14;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
+    constexpr int D = NB < 12 ? NB : 12;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
     const int wave_first = tid & ~63;     // first lane of this wavefront within the instance
     // VEQW (every value equals its weight, the paper's Problem 1): the row is kept as
     // row[c] - c, which turns row[c-w] + w into a plain copy of the shifted operand and
     // saves the add; comparisons and hence take bits are unchanged.
+    // Each wavefront holds 64 list entries in two registers (lane l: entry 64 c + l) and
+    // fetches the next 64 while it works through these, so an item's weight and value are
+    // two lane reads and the sweep waits on vector memory once per 64 items.
+    const int lane = tid & 63;
+    auto load_chunk = [&](int first) {
+        return first + lane < nact ? load_item_wv(list + first + lane) : make_int2(0, 0);
+    };
+    int2 cur = load_chunk(0);
     int own[NB];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
         own[k] = VEQW ? -(k * T + tid) : 0;
         row[k * T + tid] = own[k];
     }
-    lds_sync<T>();  // initial row and item list visible to every lane
+    lds_sync<T>();  // initial row visible to every lane
 
     const int m0w = uniform((int)row_off + wave_first * 4);
-    // The item list is read by scalar loads (their own counter: no wait behind the
-    // keep-table stores), one item ahead.
-    int wn = lst[0].w, vn = lst[0].v;
-    for (int q = 0; q < nact; ++q) {
-        const int w = wn, v = vn;
+    for (int q0 = 0; q0 < nact; q0 += 64) {
+    const int2 nxt = load_chunk(q0 + 64);
+    const int q1 = min(q0 + 64, nact);
+    for (int q = q0; q < q1; ++q) {
+        const int w = __builtin_amdgcn_readlane(cur.x, q & 63);
+        const int v = VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63);
         uint32_t bits[NW];
 #pragma unroll
         for (int x = 0; x < NW; ++x) bits[x] = 0;
@@ -193,7 +218,7 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             }
         };
         const int idx = tid - w;
-        if (w <= light_max) {
+        if (__builtin_expect(w <= light_max, 1)) {
             // light item: every lane reads row[c - w]; c < w lands in the guard
             const int32_t *src = row + idx;
             phase_a([&](int k) { return src[k * T]; });
@@ -203,10 +228,6 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             phase_a([&](int k) { return row[max(idx + k * T, -1)]; });
         }
         lds_sync<T>();  // every lane has read the old row
-        // next item: the scalar loads stay in flight while this one is written back
-        const int qn = min(q + 1, nact - 1);
-        wn = lst[qn].w;
-        vn = lst[qn].v;
 
         if constexpr (ADDTID) {
             m0_settle(m0w);
@@ -215,22 +236,35 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 #pragma unroll
             for (int k = NB - 1; k >= 0; --k) row[k * T + tid] = own[k];
         }
+        // Row q of the keep table belongs to the q-th offered item.  A wavefront whose 64
+        // lanes took nothing writes nothing and notes that in nzm: bit (q % 64) of lane
+        // (q / 64) says whether this wavefront's part of row q exists.
+        uint32_t any_bits = bits[0];
 #pragma unroll
-        for (int x = 0; x < NW; ++x) kp[((size_t)q * NW + x) * T + tid] = bits[x];  // row q: the q-th offered item
+        for (int x = 1; x < NW; ++x) any_bits |= bits[x];
+        const bool nz = __builtin_amdgcn_ballot_w64(any_bits != 0) != 0ull;
+        if (nz) {
+#pragma unroll
+            for (int x = 0; x < NW; ++x) kp[((size_t)q * NW + x) * T + tid] = bits[x];
+        }
+        if ((tid & 63) == (q >> 6)) nzm |= (unsigned long long)nz << (q & 63);
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
+    }
+    cur = nxt;
     }
 }
 
 // Picks the sweep_stage instance for the stage's chunk count (1 .. N).
 template <int T, int G, int NW, bool ADDTID, bool VEQW, int N>
 __device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
-                                               int nact, const const_item *lst, uint32_t *kp)
+                                               int nact, const OfferedItem *list, uint32_t *kp,
+                                               unsigned long long &nzm)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID, VEQW>(row, row_off, light_max, tid, nact, lst, kp);
+        sweep_stage<T, N * G, NW, ADDTID, VEQW>(row, row_off, light_max, tid, nact, list, kp, nzm);
     } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, VEQW, N - 1>(nchunk, row, row_off, light_max, tid, nact, lst, kp);
+        sweep_dispatch<T, G, NW, ADDTID, VEQW, N - 1>(nchunk, row, row_off, light_max, tid, nact, list, kp, nzm);
     }
 }
 
@@ -270,10 +304,9 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     int32_t *out_asg = a.assignment + (size_t)inst * a.item_stride;
     int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
     int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
-    uint32_t *kp = keep + (size_t)inst * keep_words_per_inst;
-    // one item list per stage: a list is written once and only then read through the
-    // scalar cache, so no stage can see another stage's entries there
-    OfferedItem *inst_lists = lists + (size_t)inst * a.knap_stride * list_stride;
+    uint32_t *kp = uniform_ptr(keep + (size_t)inst * keep_words_per_inst);
+    // one item list per stage
+    OfferedItem *inst_lists = uniform_ptr(lists + (size_t)inst * a.knap_stride * list_stride);
 
     // ---- per-instance validation -------------------------------------------
     if (tid < kMiscInts) misc[tid] = 0;
@@ -361,24 +394,37 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
         global_sync<T>();  // the list (global memory) and the count (LDS) are visible
         const int nact = min(uniform(misc[1]), list_stride);
-        const const_item *lst = as_constant(list);
+        unsigned long long nzm = 0;
         if (veqw)
             sweep_dispatch<T, G, NW, ADDTID, true, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid, nact,
-                                                        lst, kp);
+                                                        list, kp, nzm);
         else
             sweep_dispatch<T, G, NW, ADDTID, false, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid, nact,
-                                                         lst, kp);
+                                                         list, kp, nzm);
 
         const int value = uniform(row[C]) + (veqw ? C : 0);
 
         // ---- traceback ------------------------------------------------------------
+        // The row is dead now; its LDS holds what the walk needs: weight and index of
+        // every offered item and, per wavefront, which keep-row parts exist.
+        lds_sync<T>();  // every lane has read row[C]
+        int32_t *tb_w = row, *tb_index = row + list_stride;
+        unsigned long long *tb_nz = reinterpret_cast<unsigned long long *>(row + 2 * list_stride);
+        for (int i = tid; i < nact; i += T) {
+            tb_w[i] = load_item_wv(list + i).x;
+            tb_index[i] = load_item_index(list + i);
+        }
+        tb_nz[tid] = nzm;  // wavefront x, lane l: rows 64 l .. 64 l + 63
+        global_sync<T>();  // keep words (global memory) and the staged data (LDS) are visible
+
         // One wavefront walks the keep words back from (last offered item, C).  The
         // walk is a chain of dependent loads, so six steps are taken per memory round
         // trip: lane L in [2^d, 2^(d+1)) assumes the decisions spelled by the bits of
         // L below its leading one for the items q .. q-d+1 (most significant first)
         // and fetches the keep bit of item q-d at the capacity those decisions leave;
-        // a ballot then gives all 63 answers and the true path is read off it.
-        global_sync<T>();
+        // a ballot then gives all 63 answers and the true path is read off it.  A lane
+        // whose keep-row part was never written knows its answer (not taken) without a
+        // load, so rounds through all-zero rows cost no memory round trip.
         if (tid < 64) {
             const int L = tid;
             const int d = 31 - __clz(L | 1);
@@ -386,28 +432,25 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             // Every index is range-checked before it is used; a violation (never expected)
             // marks the instance DEFT_ERR_DEVICE instead of touching memory.
             bool broken = false;
-            auto fetch = [&](int qq) {  // lane L < 6 fetches (index, weight) of offered item qq - L
-                const bool have = L < 6 && qq - L >= 0;
-                int2 r = make_int2(0, 0);
-                if (have) {
-                    const OfferedItem e = list[qq - L];
-                    if (e.index >= 0 && e.index < n) { r.x = e.index; r.y = e.w; } else broken = true;
-                }
-                return r;
-            };
             int c = C;
             int q = nact - 1;
             unsigned long long chosen = 0;  // items this stage places, laid out like `placed`
-            int2 it = fetch(q);
             while (q >= 0) {
                 int wv[6], tv[6];
+                {
+                    const bool have = L < 6 && q - L >= 0;
+                    int w_l = 0, t_l = 0;
+                    if (have) {
+                        w_l = tb_w[q - L];
+                        t_l = tb_index[q - L];
+                        if (t_l < 0 || t_l >= n) { broken = true; t_l = 0; }
+                    }
 #pragma unroll
-                for (int i = 0; i < 6; ++i) {
-                    tv[i] = __builtin_amdgcn_readlane(it.x, i);
-                    wv[i] = __builtin_amdgcn_readlane(it.y, i);
+                    for (int i = 0; i < 6; ++i) {
+                        tv[i] = __builtin_amdgcn_readlane(t_l, i);
+                        wv[i] = __builtin_amdgcn_readlane(w_l, i);
+                    }
                 }
-                const int qn = q - 6;
-                const int2 itn = fetch(qn);  // next round's items
                 int cl = c, wd = wv[0];
 #pragma unroll
                 for (int i = 0; i < 5; ++i) {
@@ -418,12 +461,14 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 // lane L tests offered item q-d; items past the head of the list (q-d < 0) carry
                 // w = 0 and are excluded here, so cl never leaves [-5*C, C]
                 if (L >= 1 && q - d >= 0 && cl >= 0 && wd <= cl) {
-                    const int k = cl >> LOG_T, lane = cl & (T - 1);
+                    const int k = cl >> LOG_T, lane = cl & (T - 1), qd = q - d;
                     if (k < K && cl <= C) {
-                        const uint32_t word =
-                            __hip_atomic_load(&kp[((size_t)(q - d) * NW + (k >> 5)) * T + lane], __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-                        bit = (word >> (k & 31)) & 1u;
+                        const unsigned long long nzw = tb_nz[(lane >> 6) * 64 + (qd >> 6)];
+                        if ((nzw >> (qd & 63)) & 1ull) {
+                            const uint32_t word = __hip_atomic_load(&kp[((size_t)qd * NW + (k >> 5)) * T + lane],
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            bit = (word >> (k & 31)) & 1u;
+                        }
                     } else {
                         broken = true;
                     }
@@ -440,8 +485,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                     }
                     node = 2 * node + b;
                 }
-                q = qn;
-                it = itn;
+                q -= 6;
             }
             placed |= chosen;
             while (chosen) {  // outside the walk: no store sits in its chain of loads
@@ -513,6 +557,9 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
         if (slots > v.cells) continue;
         const int64_t row_cells = slots * v.threads;
+        // after a stage's sweep the row's LDS stages the walk's data: two ints per list
+        // entry and one 64-bit word per lane
+        if (row_cells < 2 * (int64_t)n_pad + 2 * v.threads) continue;
         const int64_t per_inst = (guard + row_cells) * 4;
         const int inst_per_wg = v.threads == 64 ? 4 : 1;
         const int64_t lds = per_inst * inst_per_wg;

@@ -153,6 +153,42 @@ def vgg19_shaped(k: int = 1, batch: int = 4096, n: int = 38,
     return _sequential(f"vgg19_k{k}", w, w.copy(), cap, meta={"seed": seed, "k": k})
 
 
+def concat(batches, name: str) -> KnapsackBatch:
+    """One call holding the instances of several sequential batches with the same
+    item count; shorter capacity rows are padded with unused (zero) knapsacks."""
+    ks = max(kb.knap_stride for kb in batches)
+
+    def pad(a: np.ndarray) -> np.ndarray:
+        out = np.zeros((a.shape[0], ks), dtype=np.int32)
+        out[:, :a.shape[1]] = a
+        return out
+
+    assert all(kb.mode == MODE_SEQUENTIAL and kb.fill_order is None and
+               kb.item_stride == batches[0].item_stride for kb in batches)
+    return KnapsackBatch(
+        name=name, mode=MODE_SEQUENTIAL, batch=sum(kb.batch for kb in batches),
+        item_stride=batches[0].item_stride, knap_stride=ks,
+        n_items=_i32(np.concatenate([kb.n_items for kb in batches])),
+        n_knapsacks=_i32(np.concatenate([kb.n_knapsacks for kb in batches])),
+        weights=_i32(np.concatenate([kb.weights for kb in batches])),
+        values=_i32(np.concatenate([kb.values for kb in batches])),
+        capacities=_i32(np.concatenate([pad(kb.capacities) for kb in batches])),
+        meta={"parts": [kb.name for kb in batches]})
+
+
+def resnet101_sweep(batch: int = 1024, ks=(4, 3, 2, 1)) -> KnapsackBatch:
+    """The ResNet-101-shaped candidate set as one call: `batch` perturbed profiles,
+    each with the window pair repeated k times for every k in `ks` (Section III.A:
+    the delayed-update frequency decides how many windows serve one iteration's
+    communication).  Longest instances (largest k) come first."""
+    return concat([resnet101_shaped(k=k, batch=batch) for k in ks], "resnet101_sweep")
+
+
+def vgg19_sweep(batch: int = 4096, ks=(4, 3, 2, 1)) -> KnapsackBatch:
+    """The VGG-19-shaped candidate set as one call (see resnet101_sweep)."""
+    return concat([vgg19_shaped(k=k, batch=batch) for k in ks], "vgg19_sweep")
+
+
 def gpt2_shaped(batch: int = 256, n: int = 148, seed: int = SEED_GPT2) -> KnapsackBatch:
     """GPT-2 shape (Table I, 1 us units): total comm 546400, windows 381000 /
     169000; value = weight x U[1,4] priority."""
