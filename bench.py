@@ -80,6 +80,9 @@ def main() -> int:
     ap.add_argument("--per-k-calls", action="store_true",
                     help="ResNet/VGG shapes: one call per k (4 calls of 1024 / 4096 instances) instead of one call "
                          "holding the whole sweep over k")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel, so that a counter profile of this "
+                         "command holds a row of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
     ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()
@@ -145,6 +148,14 @@ def main() -> int:
             for db in dbs:
                 h.solve_batch(db, stream)
 
+        if args.calibrate_copy:
+            src = torch.empty(1 << 28, dtype=torch.int32, device=dev)
+            src.fill_(1)
+            dst = torch.empty_like(src)
+            torch.cuda.synchronize(dev)
+            dst.copy_(src)            # the calibration row: reads 1 GiB, writes 1 GiB
+            torch.cuda.synchronize(dev)
+            del src, dst
         for _ in range(args.warmup):
             step()
         stream.synchronize()
@@ -175,9 +186,20 @@ def main() -> int:
     algo_bytes_total = cells_step * args.steps * algo["bytes_per_cell"]
     achieved_gbs = algo_bytes_total / sweep_s / 1e9 if sweep_s > 0 else 0.0
     peak = PEAK_LDS_GBS if algo["bound"] == "lds" else PEAK_HBM_GBS
+    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter passes
+    # (FETCH_SIZE and WRITE_SIZE scaled by a copy of known size); only for the unmodified workload.
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", f"seq_lds_kernel_{args.workload}_traffic.txt")
+    plain = args.batch_scale == 1.0 and not (args.per_k_calls or args.only_k or args.max_stages)
+    if plain and os.path.exists(tf):
+        try:
+            with open(tf) as f:
+                traffic = float(json.load(f)["hbm_bytes_per_launch"])
+        except (ValueError, KeyError):
+            traffic = None
     roofline = dict(
         bound=algo["bound"], achieved=achieved_gbs, peak=peak, unit="GB/s", frac=achieved_gbs / peak,
-        traffic=None,
+        traffic=traffic,
         kernel="seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep" if seq else "jt_sweep"),
         bytes_per_cell=algo["bytes_per_cell"], launches=launches,
         avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),

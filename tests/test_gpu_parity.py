@@ -150,3 +150,27 @@ def test_repeat_runs_are_bit_identical(binding, oracle):
                 first = cur
             else:
                 assert all(torch.equal(a, b) for a, b in zip(first, cur))
+
+
+def test_one_handle_reused_across_layouts(binding, oracle):
+    """Calls with different knapsack strides and item counts reuse one handle's
+    scratch at shifting offsets; every repeat must still match the oracle (nothing
+    written by an earlier launch may be served again from a cache)."""
+    import torch
+    calls = [W.vgg19_shaped(k=k, batch=512) for k in (1, 2, 3, 4)]
+    calls.append(W.random_sequential(991, batch=300, n_max=30, m_max=5, w_hi=900, v_hi=50, cap_hi=9000))
+    refs = [oracle.solve_batch(kb, nthreads=16) for kb in calls]
+    with binding.DeftKnapsack(max_batch=512, max_items=38, max_knapsacks=8, max_capacity=9300) as h:
+        dbs = [h.upload(kb) for kb in calls]
+        for rep in range(4):
+            outs = [h.solve_batch(db) for db in dbs]
+            torch.cuda.synchronize()
+            for kb, out, ref in zip(calls, outs, refs):
+                assert_same(kb, out, ref)
+
+
+def test_full_size_sweeps(binding, oracle):
+    """The two LDS-path workloads at the sizes and in the launch shape bench.py times:
+    every output of every instance against the oracle."""
+    run(binding, oracle, W.resnet101_sweep())
+    run(binding, oracle, W.vgg19_sweep())
