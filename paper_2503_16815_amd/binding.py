@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdeft_knapsack.so")
+LIB_PATH = os.environ.get("DEFT_KNAPSACK_LIB") or os.path.join(_HERE, "libdeft_knapsack.so")
 
 DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, DEFT_ERR_DEVICE = range(6)
 DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2 = 0, 1

@@ -139,8 +139,15 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
     }
     if (st == DEFT_OK && want_joint) {
         h->joint_path = 1;
-        joint_plan(cfg->max_c1, cfg->max_c2, cfg->max_items, cfg->max_batch, &h->joint_plan);
-        st = alloc(&h->joint_scratch, h->joint_plan.scratch_bytes, &h->scratch_bytes);
+        const int lds_wg = (int)prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin
+                                                                : (int)prop.sharedMemPerBlock;
+        joint_plan(cfg->max_c1, cfg->max_c2, cfg->max_items, cfg->max_batch, lds_wg, &h->joint_plan);
+        if (joint_prepare(h->joint_plan) != hipSuccess) {
+            (void)hipGetLastError();
+            st = DEFT_ERR_DEVICE;
+        } else {
+            st = alloc(&h->joint_scratch, h->joint_plan.scratch_bytes, &h->scratch_bytes);
+        }
     }
     if (st != DEFT_OK) {
         free_handle(h);

@@ -1,11 +1,22 @@
-// Joint two-link solve (Sec. III.C, Problem 2 with one weight per link) with
-// the (C1+1) x (C2+1) table in global memory.  Item q reads table q & 1 and
-// writes the other:
+// Joint two-link solve (Sec. III.C, Problem 2 with one weight per link).  The
+// (C1+1) x (C2+1) table does not fit LDS, so it lives in global memory (two
+// copies, item q reads copy q & 1 and writes the other) and streams through an
+// LDS window once per item:
 //   new[a][b] = max(old[a][b], old[a - w0][b] + v, old[a][b - w1] + v)
 // tested in that order, each replacing the incumbent only when strictly
-// greater.  The 2-bit choice is stored as two bit planes (took link 0 / took
-// link 1), one 64-bit ballot word per 64 consecutive b.  The first item reads
-// zeros instead of a table.  One launch per item rank up to item_stride.
+// greater.  One workgroup owns an instance for all its items.  It walks the
+// rows in ascending blocks; each old row is fetched from global memory exactly
+// once, as the block's own rows, into a ring of LDS rows, where it stays until
+// the rows w0 above it have used it as their shifted operand; the b-shifted
+// operand comes from the same LDS row.  Per cell: 4 B read + 4 B written +
+// 1/4 B of choice bits to HBM, 4 B written + 12 B read in LDS.
+// The 2-bit choice is stored as two bit planes (took link 0 / took link 1),
+// one 64-bit ballot word per 64 consecutive b.  The first item reads zeros
+// instead of a table.
+#include <limits.h>
+
+#include <type_traits>
+
 #include "instance_check.h"
 
 namespace deft {
@@ -13,7 +24,6 @@ namespace deft {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kTasksPerWave = 8;   // (row, 64-column segment) pairs per wavefront
 
 struct InstState {
     int32_t status, n, c1, c2;
@@ -54,44 +64,204 @@ __global__ void __launch_bounds__(kThreads) jt_init(BatchArgs a, InstState *stat
     }
 }
 
-__global__ void __launch_bounds__(kThreads)
-jt_sweep(BatchArgs a, int q, const InstState *__restrict__ state, int32_t *tab, uint64_t *choice, int rows,
-         int pitch, int max_items, int wgs_per_inst)
+constexpr int kSweepThreads = 1024;  // one workgroup per instance
+constexpr int kSweepWaves = kSweepThreads / 64;
+constexpr int kLoadWaves = 2;        // wavefronts that only move old rows from global memory into LDS
+constexpr int kComputeWaves = kSweepWaves - kLoadWaves;
+
+// Block hand-over barriers.  A loading wavefront arrives when its LDS-direct loads have
+// landed (they count as vector memory); a computing wavefront arrives when its LDS reads
+// have, while its table stores stay in flight (they are awaited once, at the end of the
+// item).  Written as asm because the compiler, seeing LDS-direct loads in the kernel, puts
+// a wait for all vector memory in front of every barrier it knows about.
+__device__ __forceinline__ void barrier_after_loads()
 {
-    const int inst = blockIdx.x / wgs_per_inst, wg = blockIdx.x % wgs_per_inst;
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+__device__ __forceinline__ void barrier_after_lds_reads()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+typedef __attribute__((address_space(3))) int32_t lds_i32;
+typedef const __attribute__((address_space(1))) int32_t global_ci32;
+
+// Roles: the first kLoadWaves wavefronts copy the next block's old rows from global
+// memory straight into the LDS ring (no registers in between, so dozens of 256-byte
+// loads are in flight per wavefront); the others compute the current block from the ring
+// and store the new rows and the choice bits, and never wait on memory.  One barrier per
+// block hands the freshly loaded block over.
+// A compute task is one row x 256 columns: lane l covers columns tile*256 + 64 j + l,
+// j = 0..3, so every global and LDS access of a wavefront is 64 consecutive words and the
+// ballot over j is the choice word of segment tile*4 + j.
+__global__ void __launch_bounds__(kSweepThreads)
+jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uint64_t *choice, int rows, int pitch,
+             int max_items, int ring_rows, int lds_pitch)
+{
+    extern __shared__ __align__(16) int32_t ring[];  // [ring_rows][lds_pitch], row a lives in slot a % ring_rows
+    const int inst = blockIdx.x;
     const InstState st = state[inst];
-    if (q >= st.n) return;
+    if (st.status != DEFT_OK || st.n <= 0) return;
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const bool loader = wave < kLoadWaves;
     const int segs = pitch / 64;
-    const int w0 = a.weights[(size_t)inst * 2 * a.item_stride + q];
-    const int w1 = a.weights[(size_t)inst * 2 * a.item_stride + a.item_stride + q];
-    const int v = a.values[(size_t)inst * a.item_stride + q];
+    const int ncol = st.c2 + 1, nrow = st.c1 + 1;
+    const int nseg = (ncol + 63) / 64, ntile = (ncol + 255) / 256;
     const size_t tsz = (size_t)rows * pitch;
-    const int32_t *__restrict__ src = tab + ((size_t)inst * 2 + (q & 1)) * tsz;
-    int32_t *__restrict__ dst = tab + ((size_t)inst * 2 + ((q & 1) ^ 1)) * tsz;
-    uint64_t *ch = choice + ((size_t)inst * max_items + q) * ((size_t)rows * segs * 2);
-    const bool first = q == 0;
-    const int task0 = (wg * (kThreads / 64) + (threadIdx.x >> 6)) * kTasksPerWave;
-#pragma unroll 2
-    for (int i = 0; i < kTasksPerWave; ++i) {
-        const int task = task0 + i;
-        const int ar = task / segs, sg = task % segs;
-        if (ar > st.c1 || sg * 64 > st.c2) continue;
-        const int b = sg * 64 + lane;
-        const size_t at = (size_t)ar * pitch + b;
-        int best = first ? 0 : src[at];
-        bool t0 = false, t1 = false;
-        if (ar >= w0) {
-            const int cand = (first ? 0 : src[at - (size_t)w0 * pitch]) + v;
-            if (cand > best) { best = cand; t0 = true; }
+    const int32_t *W0 = a.weights + (size_t)inst * 2 * a.item_stride;
+    const int32_t *W1 = W0 + a.item_stride;
+    const int32_t *V = a.values + (size_t)inst * a.item_stride;
+
+    // the first item sees an all-zero table: the ring is cleared once and not loaded
+    for (int i = threadIdx.x; i < ring_rows * lds_pitch; i += kSweepThreads) ring[i] = 0;
+    __syncthreads();
+
+    for (int q = 0; q < st.n; ++q) {
+        const int w0 = W0[q], w1 = W1[q], v = V[q];
+        const int32_t *__restrict__ src = tab + ((size_t)inst * 2 + (q & 1)) * tsz;
+        int32_t *__restrict__ dst = tab + ((size_t)inst * 2 + ((q & 1) ^ 1)) * tsz;
+        uint64_t *ch = choice + ((size_t)inst * max_items + q) * ((size_t)rows * segs * 2);
+        const bool first = q == 0;
+        // The ring holds the block being computed, the next block being loaded and the w0
+        // rows below the current block: 2 R + w0 <= ring_rows.  Heavier items read their
+        // row-shifted operand from global memory instead.
+        const bool shifted_in_ring = 2 + w0 <= ring_rows;
+        const int R = max(1, (shifted_in_ring ? ring_rows - w0 : ring_rows) / 2);
+
+        // rows [lo, lo + R) of the old table -> ring; slot_lo = lo % ring_rows.  The
+        // (row, segment) pairs are dealt round-robin to the loading wavefronts.
+        auto load_rows = [&](int lo, int slot_lo) {
+            if (first) return;
+            const int nr = min(R, nrow - lo);
+            int r = 0, part = wave;  // part: 256 columns, 16 bytes per lane
+            while (true) {
+                while (part >= ntile) { part -= ntile; ++r; }
+                if (r >= nr) break;
+                int slot = slot_lo + r;
+                if (slot >= ring_rows) slot -= ring_rows;
+                const int col = part * 256 + lane * 4;
+                // a lane's four columns may run past the instance's last column, never past the
+                // row pitch of the table or of the ring (both are multiples of four)
+                if (col < ncol) {
+                    __builtin_amdgcn_global_load_lds((global_ci32 *)(src + (size_t)(lo + r) * pitch + col),
+                                                     (lds_i32 *)(ring + (size_t)slot * lds_pitch + part * 256), 16, 0, 0);
+                }
+                part += kLoadWaves;
+            }
+        };
+
+        if (loader) {
+            load_rows(0, 0);
+            barrier_after_loads();
+        } else {
+            barrier_after_lds_reads();
         }
-        if (b >= w1) {
-            const int cand = (first ? 0 : src[at - w1]) + v;
-            if (cand > best) { best = cand; t0 = false; t1 = true; }
+        int slot_a0 = 0;  // a0 % ring_rows
+        for (int a0 = 0; a0 < nrow; a0 += R) {
+            int slot_next = slot_a0 + R;
+            if (slot_next >= ring_rows) slot_next -= ring_rows;
+            if (loader) {
+                if (a0 + R < nrow) load_rows(a0 + R, slot_next);
+                barrier_after_loads();  // the next block is in the ring
+            } else {
+                // One task.  IN_RING: the row-shifted operand comes from the ring; otherwise
+                // (items heavier than the ring allows) from global memory, which makes every
+                // task wait on vector memory: kept apart so that the common path never does.
+                // MASK_B: some column of the tile lies below w1 and must not take link 1.
+                // The first item needs no special case: the ring holds zeros while it runs.
+                // HAS0: the row has a row-shifted operand (ar >= w0).  FULL: all four 64-column
+                // segments of the tile exist and no column needs clamping (straight-line code).
+                auto task = [&](auto in_ring_tag, auto mask_b_tag, auto has0_tag, auto full_tag, int ar, int slot,
+                                int tile) {
+                    constexpr bool IN_RING = decltype(in_ring_tag)::value;
+                    constexpr bool MASK_B = decltype(mask_b_tag)::value;
+                    constexpr bool has0 = decltype(has0_tag)::value;
+                    constexpr bool FULL = decltype(full_tag)::value;
+                    const int32_t *own_row = ring + (size_t)slot * lds_pitch;
+                    int sh_slot = slot - w0;  // only used when w0 < ring_rows
+                    if (sh_slot < 0) sh_slot += ring_rows;
+                    const int32_t *sh_row = ring + (size_t)(IN_RING ? sh_slot : 0) * lds_pitch;
+                    const int col0 = tile * 256 + lane;
+                    const int nj = FULL ? 4 : min(4, (ncol - tile * 256 + 63) >> 6);  // segments of the tile that exist
+                    int32_t *out = dst + (size_t)ar * pitch + col0;
+                    int cen[4], sh[4], bs[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (j < nj) {
+                            const int col = FULL ? col0 + j * 64 : min(col0 + j * 64, ncol - 1);
+                            const int idx = col - w1;
+                            cen[j] = own_row[col];
+                            bs[j] = own_row[MASK_B ? max(idx, 0) : idx];
+                            if (has0) {
+                                if (IN_RING) sh[j] = sh_row[col];
+                                else sh[j] = first ? 0 : src[(size_t)(ar - w0) * pitch + col];
+                            }
+                        }
+                    }
+                    unsigned long long m0[4], m1[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        m0[j] = 0;
+                        m1[j] = 0;
+                        if (j < nj) {
+                            const int col = col0 + j * 64;
+                            int best = cen[j];
+                            if (has0) {
+                                const int cand0 = sh[j] + v;
+                                m0[j] = __ballot(cand0 > best);
+                                best = max(best, cand0);
+                            }
+                            int cand1 = bs[j] + v;
+                            if (MASK_B) cand1 = col < w1 ? INT_MIN : cand1;
+                            m1[j] = __ballot(cand1 > best);
+                            best = max(best, cand1);
+                            m0[j] &= ~m1[j];
+                            if (FULL || col < ncol) out[j * 64] = best;
+                        }
+                    }
+                    // lanes 0..7 store the eight ballot words of the tile's four segments (bits of
+                    // columns past the instance's last one are never looked at)
+                    const int j = lane >> 1;
+                    if (lane < 8 && j < nj) {
+                        unsigned long long wsel = 0;
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj)
+                            if (jj == j) wsel = (lane & 1) ? m1[jj] : m0[jj];
+                        ch[((size_t)ar * segs + tile * 4 + j) * 2 + (lane & 1)] = wsel;
+                    }
+                };
+                const int nr = min(R, nrow - a0);
+                int r = 0, tile = wave - kLoadWaves;
+                while (true) {
+                    while (tile >= ntile) { tile -= ntile; ++r; }
+                    if (r >= nr) break;
+                    int slot = slot_a0 + r;
+                    if (slot >= ring_rows) slot -= ring_rows;
+                    const bool mask_b = tile * 256 < w1, has0 = a0 + r >= w0, full = tile * 256 + 256 <= ncol;
+                    const std::true_type yes{};
+                    const std::false_type no{};
+                    const int ar = a0 + r;
+                    if (!shifted_in_ring || !full) {  // rare shapes: one general instance each
+                        if (!shifted_in_ring) {
+                            if (has0) task(no, yes, yes, no, ar, slot, tile); else task(no, yes, no, no, ar, slot, tile);
+                        } else {
+                            if (has0) task(yes, yes, yes, no, ar, slot, tile); else task(yes, yes, no, no, ar, slot, tile);
+                        }
+                    } else if (has0) {
+                        if (mask_b) task(yes, yes, yes, yes, ar, slot, tile); else task(yes, no, yes, yes, ar, slot, tile);
+                    } else {
+                        if (mask_b) task(yes, yes, no, yes, ar, slot, tile); else task(yes, no, no, yes, ar, slot, tile);
+                    }
+                    tile += kComputeWaves;
+                }
+                barrier_after_lds_reads();  // this block's slots may be reused
+            }
+            slot_a0 = slot_next;
         }
-        dst[at] = best;
-        const unsigned long long m0 = __ballot(t0), m1 = __ballot(t1);
-        if (lane < 2) ch[((size_t)ar * segs + sg) * 2 + lane] = lane ? m1 : m0;
+        // the next item reads what this one wrote (other wavefronts' rows included)
+        __threadfence_block();
+        __syncthreads();
     }
 }
 
@@ -133,10 +303,18 @@ jt_traceback(BatchArgs a, const InstState *__restrict__ state, const int32_t *ta
 
 }  // namespace
 
-void joint_plan(int32_t max_c1, int32_t max_c2, int32_t max_items, int32_t max_batch, JointPlan *p)
+void joint_plan(int32_t max_c1, int32_t max_c2, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
+                JointPlan *p)
 {
     p->rows = max_c1 + 1;
     p->pitch = (max_c2 + 1 + 63) / 64 * 64;
+    p->lds_pitch = (max_c2 + 1 + 3) / 4 * 4;  // rows stay 16-byte aligned for the 16-byte LDS-direct loads
+    // as many LDS rows as fit, but no more than the table has (plus one block)
+    int64_t ring = (int64_t)lds_per_wg_bytes / ((int64_t)p->lds_pitch * 4);
+    if (ring > p->rows) ring = p->rows;
+    if (ring < 2) ring = 2;
+    p->ring_rows = (int32_t)ring;
+    p->lds_bytes = (int32_t)(ring * p->lds_pitch * 4);
     p->max_items = max_items;
     p->max_batch = max_batch;
     p->scratch_bytes = (int64_t)(align256((size_t)max_batch * 2 * p->rows * p->pitch * 4) +
@@ -144,19 +322,20 @@ void joint_plan(int32_t max_c1, int32_t max_c2, int32_t max_items, int32_t max_b
                                  align256((size_t)max_batch * sizeof(InstState)));
 }
 
+hipError_t joint_prepare(const JointPlan &p)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&jt_sweep_all),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
+}
+
 hipError_t joint_launch(const JointPlan &p, const BatchArgs &a, void *scratch, hipStream_t st, Profiler *prof)
 {
     const Scratch s = carve(p, scratch);
     hipLaunchKernelGGL(jt_init, dim3(a.batch), dim3(kThreads), 0, st, a, s.state);
-    const int tasks = p.rows * (p.pitch / 64);
-    const int per_wg = kTasksPerWave * (kThreads / 64);
-    const int wgs = (tasks + per_wg - 1) / per_wg;
-    for (int q = 0; q < a.item_stride; ++q) {
-        if (prof) prof->sweep_begin(st);
-        hipLaunchKernelGGL(jt_sweep, dim3((unsigned)wgs * (unsigned)a.batch), dim3(kThreads), 0, st, a, q, s.state,
-                           s.tab, s.choice, p.rows, p.pitch, p.max_items, wgs);
-        if (prof) prof->sweep_end(st);
-    }
+    if (prof) prof->sweep_begin(st);
+    hipLaunchKernelGGL(jt_sweep_all, dim3((unsigned)a.batch), dim3(kSweepThreads), (size_t)p.lds_bytes, st, a, s.state,
+                       s.tab, s.choice, p.rows, p.pitch, p.max_items, p.ring_rows, p.lds_pitch);
+    if (prof) prof->sweep_end(st);
     hipLaunchKernelGGL(jt_traceback, dim3((a.batch + 63) / 64), dim3(64), 0, st, a, s.state, s.tab, s.choice,
                        p.rows, p.pitch, p.max_items);
     return hipGetLastError();

@@ -90,10 +90,15 @@ hipError_t seq_global_launch(const SeqGlobalPlan &plan, const BatchArgs &args, v
 struct JointPlan {
     int32_t pitch;             // int32 cells per table row (multiple of 64)
     int32_t rows;              // max_c1 + 1
+    int32_t lds_pitch;         // int32 cells per LDS row: max_c2 + 1
+    int32_t ring_rows;         // old rows resident in LDS
+    int32_t lds_bytes;         // dynamic LDS of the sweep kernel
     int32_t max_items, max_batch;
     int64_t scratch_bytes;
 };
-void joint_plan(int32_t max_c1, int32_t max_c2, int32_t max_items, int32_t max_batch, JointPlan *plan);
+void joint_plan(int32_t max_c1, int32_t max_c2, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
+                JointPlan *plan);
+hipError_t joint_prepare(const JointPlan &plan);
 hipError_t joint_launch(const JointPlan &plan, const BatchArgs &args, void *scratch, hipStream_t stream,
                         Profiler *prof);
 
