@@ -200,7 +200,7 @@ def main() -> int:
     roofline = dict(
         bound=algo["bound"], achieved=achieved_gbs, peak=peak, unit="GB/s", frac=achieved_gbs / peak,
         traffic=traffic,
-        kernel="seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep" if seq else "jt_sweep_all"),
+        kernel="seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep_all" if seq else "jt_sweep_all"),
         bytes_per_cell=algo["bytes_per_cell"], launches=launches,
         avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
         algorithmic_bytes_per_launch=algo_bytes_total / max(launches, 1),

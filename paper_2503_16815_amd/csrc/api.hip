@@ -133,8 +133,14 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
         } else {
             (void)hipGetLastError();
             h->seq_path = 3;
-            seq_global_plan(cfg->max_capacity, cfg->max_items, cfg->max_batch, &h->glob_plan);
-            st = alloc(&h->glob_scratch, h->glob_plan.scratch_bytes, &h->scratch_bytes);
+            seq_global_plan(cfg->max_capacity, cfg->max_items, cfg->max_batch, lds_wg, h->compute_units,
+                            &h->glob_plan);
+            if (seq_global_prepare(h->glob_plan) != hipSuccess) {
+                (void)hipGetLastError();
+                st = DEFT_ERR_DEVICE;
+            } else {
+                st = alloc(&h->glob_scratch, h->glob_plan.scratch_bytes, &h->scratch_bytes);
+            }
         }
     }
     if (st == DEFT_OK && want_joint) {

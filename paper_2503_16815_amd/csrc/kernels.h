@@ -80,9 +80,14 @@ struct SeqGlobalPlan {
     int32_t row_len;           // int32 cells per row buffer (multiple of the tile)
     int32_t keep_words;        // 64-bit keep words per item
     int32_t max_items, max_batch;
+    int32_t ring_segs;         // persistent sweep: 256-cell segments of the old row resident in LDS
+    int32_t lds_bytes;         // its dynamic LDS
+    int32_t persistent_min_batch;  // batches at least this large take the persistent sweep
     int64_t scratch_bytes;     // rows + keep + offered-item lists + per-instance state
 };
-void seq_global_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, SeqGlobalPlan *plan);
+void seq_global_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
+                     int32_t compute_units, SeqGlobalPlan *plan);
+hipError_t seq_global_prepare(const SeqGlobalPlan &plan);
 hipError_t seq_global_launch(const SeqGlobalPlan &plan, const BatchArgs &args, void *scratch,
                              hipStream_t stream, Profiler *prof);
 

@@ -78,6 +78,18 @@ def test_global_row_path_large_capacity(binding, oracle):
     run(binding, oracle, kt, max_capacity=50000)
 
 
+def test_global_row_path_persistent_sweep(binding, oracle):
+    """Batches of at least half the compute units take the one-workgroup-per-instance
+    sweep (row streamed through an LDS ring): light items, items heavier than the
+    ring can hold (shifted operand from global memory), ragged n/m, tie-heavy data."""
+    kb = W.random_sequential(3101, batch=140, n_max=14, m_max=3, w_hi=60000, v_hi=5000, cap_hi=90000)
+    run(binding, oracle, kb, max_capacity=90000)
+    kl = W.random_sequential(3102, batch=130, n_max=24, m_max=2, w_hi=3000, v_hi=50, cap_hi=60000)
+    run(binding, oracle, kl, max_capacity=60000)
+    kt = W.random_sequential(3103, batch=129, n_max=30, m_max=2, w_hi=2500, v_hi=9, cap_hi=45000, ties=True)
+    run(binding, oracle, kt, max_capacity=45000)
+
+
 def test_joint_two_link(binding, oracle):
     run(binding, oracle, W.random_joint(4001, batch=21, n_max=30, w_hi=40, v_hi=1000, c1_hi=150, c2_hi=200))
     run(binding, oracle, W.hetero_joint(batch=6, n=40, c1=200, c2=129))
@@ -174,3 +186,10 @@ def test_full_size_sweeps(binding, oracle):
     every output of every instance against the oracle."""
     run(binding, oracle, W.resnet101_sweep())
     run(binding, oracle, W.vgg19_sweep())
+
+
+def test_full_size_gpt2_and_two_link(binding, oracle):
+    """The GPT-2-shaped batch (rows in global memory, persistent sweep) and the two-link
+    batch at full size: every output of every instance against the oracle."""
+    run(binding, oracle, W.gpt2_shaped())
+    run(binding, oracle, W.hetero_joint())
