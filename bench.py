@@ -189,7 +189,8 @@ def main() -> int:
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter passes
     # (FETCH_SIZE and WRITE_SIZE scaled by a copy of known size); only for the unmodified workload.
     traffic = None
-    tf = os.path.join(ROOT, "profiles", f"seq_lds_kernel_{args.workload}_traffic.txt")
+    kernel = "seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep_all" if seq else "jt_sweep_all")
+    tf = os.path.join(ROOT, "profiles", f"{kernel}_{args.workload}_traffic.txt")
     plain = args.batch_scale == 1.0 and not (args.per_k_calls or args.only_k or args.max_stages)
     if plain and os.path.exists(tf):
         try:
@@ -200,7 +201,7 @@ def main() -> int:
     roofline = dict(
         bound=algo["bound"], achieved=achieved_gbs, peak=peak, unit="GB/s", frac=achieved_gbs / peak,
         traffic=traffic,
-        kernel="seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep_all" if seq else "jt_sweep_all"),
+        kernel=kernel,
         bytes_per_cell=algo["bytes_per_cell"], launches=launches,
         avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
         algorithmic_bytes_per_launch=algo_bytes_total / max(launches, 1),
