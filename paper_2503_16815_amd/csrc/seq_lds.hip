@@ -517,6 +517,7 @@ const Variant kVariants[] = {
     DEFT_VARIANT(64, 16, 4, 5, 256),    // capacity <= 1023: one wavefront per instance, four per workgroup
     DEFT_VARIANT(256, 16, 4, 7, 256),   // <= 4095
     DEFT_VARIANT(256, 32, 4, 4, 256),   // <= 8191
+    DEFT_VARIANT(512, 20, 1, 8, 128),   // <= 10239: four workgroups per CU when the row stays under 40 KB
     DEFT_VARIANT(512, 26, 1, 6, 128),   // <= 13311: with the 128-cell guard three workgroups share a CU's LDS
     DEFT_VARIANT(512, 51, 3, 2, 256),   // <= 26111
     DEFT_VARIANT(1024, 40, 4, 4, 256),  // <= 40959 (if LDS allows)
@@ -602,9 +603,10 @@ hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
     case 0: return launch_one<64, 16, 4, 5>(p, a, scratch, st);
     case 1: return launch_one<256, 16, 4, 7>(p, a, scratch, st);
     case 2: return launch_one<256, 32, 4, 4>(p, a, scratch, st);
-    case 3: return launch_one<512, 26, 1, 6>(p, a, scratch, st);
-    case 4: return launch_one<512, 51, 3, 2>(p, a, scratch, st);
-    case 5: return launch_one<1024, 40, 4, 4>(p, a, scratch, st);
+    case 3: return launch_one<512, 20, 1, 8>(p, a, scratch, st);
+    case 4: return launch_one<512, 26, 1, 6>(p, a, scratch, st);
+    case 5: return launch_one<512, 51, 3, 2>(p, a, scratch, st);
+    case 6: return launch_one<1024, 40, 4, 4>(p, a, scratch, st);
     default: return hipErrorInvalidValue;
     }
 }
