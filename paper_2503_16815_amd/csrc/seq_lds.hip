@@ -187,12 +187,11 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
     lds_sync<T>();  // initial row visible to every lane
 
     const int m0w = uniform((int)row_off + wave_first * 4);
-    for (int q0 = 0; q0 < nact; q0 += 64) {
-    const int2 nxt = load_chunk(q0 + 64);
-    const int q1 = min(q0 + 64, nact);
-    for (int q = q0; q < q1; ++q) {
-        const int w = __builtin_amdgcn_readlane(cur.x, q & 63);
-        const int v = VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63);
+    // One item.  HEAVY is a compile-time flag and the two kinds run in separate loops
+    // below, so that the loop over the (common) light items has a single body and the
+    // compiler keeps every cell in one register across iterations.
+    auto item = [&](auto heavy_tag, int q, int w, int v) {
+        constexpr bool HEAVY = decltype(heavy_tag)::value;
         uint32_t bits[NW];
 #pragma unroll
         for (int x = 0; x < NW; ++x) bits[x] = 0;
@@ -202,30 +201,24 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);  // slot k ends at bit k % 32
             own[k] = max(own[k], cand);
         };
+        const int idx = tid - w;
+        const int32_t *src = row + idx;
+        // light item: every lane reads row[c - w]; c < w lands in the guard.  Heavy item
+        // (rare): each lane clamps its read index into the guard, so cells below w read
+        // INT_MIN wherever they are.
+        auto read = [&](int k) { return HEAVY ? row[max(idx + k * T, -1)] : src[k * T]; };
         // The order of phase A is pinned: D slots of reads up front, then two slots of
         // arithmetic for every two further reads.
-        auto phase_a = [&](auto read) {
 #pragma unroll
-            for (int k = NB - 1; k >= NB - D; --k) rd[k] = read(k);
+        for (int k = NB - 1; k >= NB - D; --k) rd[k] = read(k);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = NB - 1; k >= 0; k -= 2) {
+            update(k);
+            if (k >= 1) update(k - 1);
+            if (k - D >= 0) rd[k - D] = read(k - D);
+            if (k - D - 1 >= 0) rd[k - D - 1] = read(k - D - 1);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int k = NB - 1; k >= 0; k -= 2) {
-                update(k);
-                if (k >= 1) update(k - 1);
-                if (k - D >= 0) rd[k - D] = read(k - D);
-                if (k - D - 1 >= 0) rd[k - D - 1] = read(k - D - 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        };
-        const int idx = tid - w;
-        if (__builtin_expect(w <= light_max, 1)) {
-            // light item: every lane reads row[c - w]; c < w lands in the guard
-            const int32_t *src = row + idx;
-            phase_a([&](int k) { return src[k * T]; });
-        } else {
-            // heavy item (rare): each lane clamps its read index into the guard, so cells
-            // below w read INT_MIN wherever they are
-            phase_a([&](int k) { return row[max(idx + k * T, -1)]; });
         }
         lds_sync<T>();  // every lane has read the old row
 
@@ -250,8 +243,25 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
         if ((tid & 63) == (q >> 6)) nzm |= (unsigned long long)nz << (q & 63);
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
-    }
-    cur = nxt;
+    };
+
+    for (int q0 = 0; q0 < nact; q0 += 64) {
+        const int2 nxt = load_chunk(q0 + 64);
+        const int q1 = min(q0 + 64, nact);
+        int q = q0;
+        while (q < q1) {
+            int w = __builtin_amdgcn_readlane(cur.x, q & 63);
+            while (w <= light_max) {  // run of light items
+                item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
+                if (++q >= q1) break;
+                w = __builtin_amdgcn_readlane(cur.x, q & 63);
+            }
+            if (q < q1) {  // one heavy item
+                item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
+                ++q;
+            }
+        }
+        cur = nxt;
     }
 }
 
