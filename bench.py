@@ -206,6 +206,12 @@ def main() -> int:
     launches = int(prof.sweep_launches)
     sweep_s = float(prof.sweep_ms) * 1e-3
     algo_bytes_total = cells_step * args.steps * algo["bytes_per_cell"]
+    if seq and info.seq_path == 3 and int(prof.streamed_row_cells) > 0:
+        # rows in global memory: a pass over a row (4 B read + 4 B written per cell) may serve two
+        # items; the library counts the row cells it read and wrote, the keep stream is 1/8 B per
+        # cell-update
+        algo_bytes_total = int(prof.streamed_row_cells) * 4.0 + cells_step * args.steps / 8.0
+        algo = dict(algo, bytes_per_cell=algo_bytes_total / (cells_step * args.steps))
     achieved_gbs = algo_bytes_total / sweep_s / 1e9 if sweep_s > 0 else 0.0
     peak = PEAK_LDS_GBS if algo["bound"] == "lds" else PEAK_HBM_GBS
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter passes

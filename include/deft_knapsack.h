@@ -155,6 +155,10 @@ typedef struct {
     float sweep_ms;        /* summed duration of the DP sweep kernel launches              */
     int32_t sweep_launches;
     float other_ms;        /* total_ms - sweep_ms: set-up, traceback, launch gaps          */
+    int64_t streamed_row_cells; /* sequential mode with rows in global memory, persistent
+                              sweep: row cells read from plus row cells written to global
+                              memory by the sweeps, summed over instances and stages (a
+                              pass over a row may serve two items); 0 on the other paths   */
 } deft_knapsack_profile_t;
 
 /* Turn HIP-event timing of solve calls on (1) or off (0); off by default.

@@ -44,6 +44,7 @@ struct deft_knapsack {
     void *keep = nullptr;  // LDS path: keep table, then the offered-item lists
     SeqGlobalPlan glob_plan{};
     void *glob_scratch = nullptr;
+    unsigned long long *glob_streamed = nullptr;  // device counter read by get_profile
 
     int joint_path = 0;
     JointPlan joint_plan{};
@@ -61,6 +62,7 @@ void free_handle(deft_knapsack *h)
     DeviceGuard g(h->cfg.device);
     if (h->keep) (void)hipFree(h->keep);
     if (h->glob_scratch) (void)hipFree(h->glob_scratch);
+    if (h->glob_streamed) (void)hipFree(h->glob_streamed);
     if (h->joint_scratch) (void)hipFree(h->joint_scratch);
     h->prof.destroy();
     delete h;
@@ -140,6 +142,15 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
                 st = DEFT_ERR_DEVICE;
             } else {
                 st = alloc(&h->glob_scratch, h->glob_plan.scratch_bytes, &h->scratch_bytes);
+                if (st == DEFT_OK) {
+                    void *c = nullptr;
+                    st = alloc(&c, 8, &h->scratch_bytes);
+                    h->glob_streamed = static_cast<unsigned long long *>(c);
+                    if (st == DEFT_OK && hipMemset(c, 0, 8) != hipSuccess) {
+                        (void)hipGetLastError();
+                        st = DEFT_ERR_DEVICE;
+                    }
+                }
             }
         }
     }
@@ -208,7 +219,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     hipError_t e = hipSuccess;
     if (b->mode == DEFT_MODE_SEQUENTIAL) {
         if (h->seq_path == 3) {
-            e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof);
+            e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof, h->glob_streamed);
         } else {
             if (prof) prof->sweep_begin(st);
             e = seq_lds_launch(h->lds_plan, a, h->keep, st);
@@ -252,6 +263,13 @@ extern "C" deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t
     if (!h) return DEFT_ERR_INVALID_ARG;
     h->profiling = enable != 0;
     h->prof.reset();
+    if (h->glob_streamed) {
+        DeviceGuard g(h->cfg.device);
+        if (!g.ok || hipMemset(h->glob_streamed, 0, 8) != hipSuccess) {
+            (void)hipGetLastError();
+            return DEFT_ERR_DEVICE;
+        }
+    }
     return DEFT_OK;
 }
 
@@ -260,7 +278,18 @@ extern "C" deft_status_t deft_knapsack_get_profile(deft_knapsack_t *h, deft_knap
     if (!h || !out || !h->profiling) return DEFT_ERR_INVALID_ARG;
     DeviceGuard g(h->cfg.device);
     if (!g.ok) return DEFT_ERR_DEVICE;
-    return h->prof.read(out);
+    deft_status_t rc = h->prof.read(out);   // waits for the last profiled call
+    out->streamed_row_cells = 0;
+    if (rc == DEFT_OK && h->glob_streamed) {
+        unsigned long long v = 0;
+        if (hipMemcpy(&v, h->glob_streamed, 8, hipMemcpyDeviceToHost) != hipSuccess ||
+            hipMemset(h->glob_streamed, 0, 8) != hipSuccess) {
+            (void)hipGetLastError();
+            return DEFT_ERR_DEVICE;
+        }
+        out->streamed_row_cells = (int64_t)v;
+    }
+    return rc;
 }
 
 extern "C" const char *deft_knapsack_status_string(int32_t s)

@@ -88,8 +88,9 @@ struct SeqGlobalPlan {
 void seq_global_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
                      int32_t compute_units, SeqGlobalPlan *plan);
 hipError_t seq_global_prepare(const SeqGlobalPlan &plan);
+// `streamed_cells` (device, may be null): the persistent sweep adds the row cells it fetched.
 hipError_t seq_global_launch(const SeqGlobalPlan &plan, const BatchArgs &args, void *scratch,
-                             hipStream_t stream, Profiler *prof);
+                             hipStream_t stream, Profiler *prof, unsigned long long *streamed_cells);
 
 // ---- joint two-link mode, table in global memory (joint2.hip) -----------------
 struct JointPlan {

@@ -35,6 +35,8 @@ constexpr int kTileCells = kWaveCells * (kThreads / 64);
 struct InstState {
     int32_t status, n_act, knap, cap;
     int64_t total;
+    int32_t buf;   // row buffer holding the stage's final row; -1: the parity of n_act says
+    int32_t pad;
 };
 
 struct Scratch {
@@ -81,7 +83,7 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
     InstState *st = &state[inst];
     const int m = a.n_knapsacks[inst];
     if (st->status != DEFT_OK || s >= m) {
-        if (lane == 0) st->n_act = 0, st->knap = -1;
+        if (lane == 0) st->n_act = 0, st->knap = -1, st->buf = -1;
         return;
     }
     const int n = a.n_items[inst];
@@ -98,7 +100,7 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
         if (f) list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = i;
         cnt += __popcll(mask);
     }
-    if (lane == 0) { st->n_act = cnt; st->knap = j; st->cap = C; }
+    if (lane == 0) { st->n_act = cnt; st->knap = j; st->cap = C; st->buf = -1; }
 }
 
 // Offered item q of every instance: one pass over the row.
@@ -153,15 +155,26 @@ __device__ __forceinline__ void barrier_after_loads() { asm volatile("s_waitcnt 
 __device__ __forceinline__ void barrier_after_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // All offered items of one stage, one workgroup per instance.  The row is walked in
-// ascending blocks of R segments (256 cells each).  Segment g lives in ring slot
-// g % ring_segs; the ring holds the block being computed, the block being loaded and the
-// cells up to w below the current block: 2 R + ceil(w / 256) + 1 <= ring_segs.  Heavier
-// items read their shifted operand from global memory (separate instantiation).
+// ascending blocks of R segments (256 cells each); a ring of LDS segments holds the part
+// of the old row the block needs (segment g in slot g % ring size), so that every old cell
+// is fetched from global memory once and both operands of a cell come from LDS.
+//
+// Two kinds of pass over the row:
+//  * one item: old row in buffer `cur`, new row into the other buffer.  The ring holds the
+//    block being computed, the block being loaded and the cells up to w below:
+//    2 R + ceil(w / 256) + 1 <= ring_segs.  Items too heavy for that read their shifted
+//    operand from global memory (separate instantiation).
+//  * two items A, B (temporal blocking): the row after A exists only in LDS.  Ring 0 holds
+//    the old row (2 R + sA segments), ring 1 the row after A (R + sB + 1 segments),
+//    sA/B = ceil(wA/B / 256) + 1; per block, phase 1 computes A's block from ring 0 into
+//    ring 1, phase 2 computes B's block from ring 1 and stores it - into the buffer being
+//    read, behind the loads - so a cell-update costs half the HBM traffic.
 // A compute task is one segment: lane l covers cells seg*256 + 64 j + l, j = 0..3, so the
 // v_cmp masks are the keep words of the segment.
 __global__ void __launch_bounds__(kAllThreads)
-sg_sweep_all(BatchArgs a, const InstState *__restrict__ state, const int32_t *__restrict__ act, int32_t *rows,
-             uint64_t *keep, int row_len, int keep_words, int max_items, int ring_segs)
+sg_sweep_all(BatchArgs a, InstState *__restrict__ state, const int32_t *__restrict__ act, int32_t *rows,
+             uint64_t *keep, int row_len, int keep_words, int max_items, int ring_segs,
+             unsigned long long *streamed_cells)
 {
     extern __shared__ __align__(16) int32_t ring[];  // [ring_segs][256]
     const int inst = blockIdx.x;
@@ -172,136 +185,210 @@ sg_sweep_all(BatchArgs a, const InstState *__restrict__ state, const int32_t *__
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const bool loader = wave < kAllLoadWaves;
     const int nseg = C / kSegCells + 1;  // segments holding cells 0 .. C (all inside row_len)
-    const int ring_cells = ring_segs * kSegCells;
     const int32_t *W = a.weights + (size_t)inst * a.item_stride;
     const int32_t *V = a.values + (size_t)inst * a.item_stride;
     const int32_t *list = act + (size_t)inst * max_items;
+    int32_t *const buf0 = rows + (size_t)inst * 2 * row_len;
+    const std::true_type yes{};
+    const std::false_type no{};
 
     // the first offered item sees an all-zero row: the ring is cleared once and not loaded
-    for (int i = threadIdx.x; i < ring_cells; i += kAllThreads) ring[i] = 0;
+    for (int i = threadIdx.x; i < ring_segs * kSegCells; i += kAllThreads) ring[i] = 0;
     __syncthreads();
 
-    for (int q = 0; q < st.n_act; ++q) {
-        const int t = list[q];
-        const int w = W[t], v = V[t];
-        const int32_t *__restrict__ src = rows + ((size_t)inst * 2 + (q & 1)) * row_len;
-        int32_t *__restrict__ dst = rows + ((size_t)inst * 2 + ((q & 1) ^ 1)) * row_len;
-        uint64_t *kw = keep + ((size_t)inst * max_items + t) * keep_words;
-        const bool first = q == 0;
-        const int wsegs = (w + kSegCells - 1) / kSegCells + 1;  // segments the shifted operand reaches back
-        const bool shifted_in_ring = wsegs + 2 <= ring_segs;
-        const int R = max(1, (shifted_in_ring ? ring_segs - wsegs : ring_segs) / 2);
+    // segments [lo, lo + n) of `src` -> ring slots slot_lo .. of a ring of rn segments at rbase
+    auto load_segs = [&](const int32_t *src, int lo, int n, int rbase, int rn, int slot_lo) {
+        for (int g = wave; g < n; g += kAllLoadWaves) {
+            int slot = slot_lo + g;
+            if (slot >= rn) slot -= rn;
+            __builtin_amdgcn_global_load_lds((global_ci32 *)(src + (size_t)(lo + g) * kSegCells + lane * 4),
+                                             (lds_i32 *)(ring + (size_t)(rbase + slot) * kSegCells), 16, 0, 0);
+        }
+    };
 
-        // segments [lo, lo + R) of the old row -> ring; slot_lo = lo % ring_segs
-        auto load_segs = [&](int lo, int slot_lo) {
-            if (first) return;
-            const int ns = min(R, nseg - lo);
-            for (int g = wave; g < ns; g += kAllLoadWaves) {
-                int slot = slot_lo + g;
-                if (slot >= ring_segs) slot -= ring_segs;
-                __builtin_amdgcn_global_load_lds((global_ci32 *)(src + (size_t)(lo + g) * kSegCells + lane * 4),
-                                                 (lds_i32 *)(ring + (size_t)slot * kSegCells), 16, 0, 0);
-            }
-        };
-
-        // One task = one segment.  IN_RING: the shifted operand comes from the ring.
-        // KIND 0: the whole segment lies at or above w; 1: w falls inside it (cells below w
-        // keep their value); 2: the whole segment lies below w (copied through).
-        auto task = [&](auto in_ring_tag, auto kind_tag, int seg, int slot) {
-            constexpr bool IN_RING = decltype(in_ring_tag)::value;
-            constexpr int KIND = decltype(kind_tag)::value;
-            const int32_t *own = ring + (size_t)slot * kSegCells + lane;
-            const int c0 = seg * kSegCells + lane;
-            int cen[4], sh[4];
+    // One task = one segment `seg`, held in slot `slot` of the source ring (rn segments at
+    // segment offset rbase).  IN_RING: the shifted operand comes from the ring, else from
+    // `src` in global memory.  KIND 0: the whole segment lies at or above w; 1: w falls
+    // inside it (cells below w keep their value); 2: the whole segment lies below w (copied
+    // through).  TO_LDS: the new cells go to slot `oslot` of the ring at obase, else to `dst`.
+    auto task = [&](auto in_ring_tag, auto kind_tag, auto to_lds_tag, int rbase, int rn, int w, int v, int seg,
+                    int slot, const int32_t *src, bool first, int32_t *dst, int obase, int oslot, uint64_t *kw) {
+        constexpr bool IN_RING = decltype(in_ring_tag)::value;
+        constexpr int KIND = decltype(kind_tag)::value;
+        constexpr bool TO_LDS = decltype(to_lds_tag)::value;
+        const int32_t *rg = ring + (size_t)rbase * kSegCells;
+        const int rcells = rn * kSegCells;
+        const int32_t *own = rg + (size_t)slot * kSegCells + lane;
+        const int c0 = seg * kSegCells + lane;
+        int cen[4], sh[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) cen[j] = own[j * 64];
-            if (KIND != 2) {
-                if (IN_RING) {
-                    // ring position of the segment's first cell minus w, brought into [0, ring_cells)
-                    int base = slot * kSegCells - w;
-                    base += base < 0 ? ring_cells : 0;
-                    if (base + kSegCells <= ring_cells) {
-                        // the 256 shifted cells are contiguous in the ring: immediate offsets
-                        const int32_t *shp = ring + base + lane;
+        for (int j = 0; j < 4; ++j) cen[j] = own[j * 64];
+        if (KIND != 2) {
+            if (IN_RING) {
+                // ring position of the segment's first cell minus w, brought into [0, rcells)
+                int base = slot * kSegCells - w;
+                base += base < 0 ? rcells : 0;
+                if (base + kSegCells <= rcells) {
+                    // the 256 shifted cells are contiguous in the ring: immediate offsets
+                    const int32_t *shp = rg + base + lane;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) sh[j] = shp[j * 64];
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            unsigned o = (unsigned)(base + lane + j * 64);
-                            o = min(o, o - (unsigned)ring_cells);  // wraps past the ring's end
-                            sh[j] = ring[o];
-                        }
-                    }
+                    for (int j = 0; j < 4; ++j) sh[j] = shp[j * 64];
                 } else {
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const int c = c0 + j * 64;
-                        sh[j] = (c >= w && !first) ? src[c - w] : 0;
+                        unsigned o = (unsigned)(base + lane + j * 64);
+                        o = min(o, o - (unsigned)rcells);  // wraps past the ring's end
+                        sh[j] = rg[o];
                     }
                 }
-            }
-            unsigned long long m[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int best = cen[j];
-                m[j] = 0;
-                if (KIND != 2) {
-                    int cand = sh[j] + v;
-                    if (KIND == 1 || !IN_RING) cand = c0 + j * 64 < w ? INT_MIN : cand;
-                    m[j] = __ballot(cand > best);
-                    best = max(best, cand);
-                }
-                dst[(size_t)c0 + j * 64] = best;
-            }
-            if (lane < 4) {
-                unsigned long long wsel = 0;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    if (jj == lane) wsel = m[jj];
-                kw[seg * 4 + lane] = wsel;
-            }
-        };
-
-        if (loader) {
-            load_segs(0, 0);
-            barrier_after_loads();
-        } else {
-            barrier_after_lds_reads();
-        }
-        int slot_lo = 0;  // lo % ring_segs
-        for (int lo = 0; lo < nseg; lo += R) {
-            int slot_next = slot_lo + R;
-            if (slot_next >= ring_segs) slot_next -= ring_segs;
-            if (loader) {
-                if (lo + R < nseg) load_segs(lo + R, slot_next);
-                barrier_after_loads();  // the next block is in the ring
             } else {
-                const int ns = min(R, nseg - lo);
-                const std::true_type yes{};
-                const std::false_type no{};
-                for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
-                    const int seg = lo + g;
-                    int slot = slot_lo + g;
-                    if (slot >= ring_segs) slot -= ring_segs;
-                    const int c_first = seg * kSegCells;
-                    if (c_first >= w) {
-                        if (shifted_in_ring) task(yes, std::integral_constant<int, 0>{}, seg, slot);
-                        else task(no, std::integral_constant<int, 0>{}, seg, slot);
-                    } else if (c_first + kSegCells > w) {
-                        if (shifted_in_ring) task(yes, std::integral_constant<int, 1>{}, seg, slot);
-                        else task(no, std::integral_constant<int, 1>{}, seg, slot);
-                    } else {
-                        task(yes, std::integral_constant<int, 2>{}, seg, slot);
-                    }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = c0 + j * 64;
+                    sh[j] = (c >= w && !first) ? src[c - w] : 0;
                 }
-                barrier_after_lds_reads();  // this block's slots may be reused
             }
-            slot_lo = slot_next;
         }
-        // the next item reads what this one wrote (other wavefronts' cells included)
+        unsigned long long m[4];
+        int32_t *lds_out = ring + (size_t)(obase + oslot) * kSegCells + lane;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int best = cen[j];
+            m[j] = 0;
+            if (KIND != 2) {
+                int cand = sh[j] + v;
+                if (KIND == 1 || !IN_RING) cand = c0 + j * 64 < w ? INT_MIN : cand;
+                m[j] = __ballot(cand > best);
+                best = max(best, cand);
+            }
+            if (TO_LDS) lds_out[j * 64] = best;
+            else dst[(size_t)c0 + j * 64] = best;
+        }
+        if (lane < 4) {
+            unsigned long long wsel = 0;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                if (jj == lane) wsel = m[jj];
+            kw[seg * 4 + lane] = wsel;
+        }
+    };
+    // picks the KIND for the segment
+    auto run_task = [&](auto in_ring_tag, auto to_lds_tag, int rbase, int rn, int w, int v, int seg, int slot,
+                        const int32_t *src, bool first, int32_t *dst, int obase, int oslot, uint64_t *kw) {
+        const int c_first = seg * kSegCells;
+        if (c_first >= w)
+            task(in_ring_tag, std::integral_constant<int, 0>{}, to_lds_tag, rbase, rn, w, v, seg, slot, src, first, dst,
+                 obase, oslot, kw);
+        else if (c_first + kSegCells > w)
+            task(in_ring_tag, std::integral_constant<int, 1>{}, to_lds_tag, rbase, rn, w, v, seg, slot, src, first, dst,
+                 obase, oslot, kw);
+        else
+            task(yes, std::integral_constant<int, 2>{}, to_lds_tag, rbase, rn, w, v, seg, slot, src, first, dst, obase,
+                 oslot, kw);
+    };
+
+    int cur = 0;  // buffer holding the row before item q (all zeros for q == 0, wherever it is)
+    int q = 0;
+    int row_transfers = 0;  // rows read from plus rows written to global memory
+    while (q < st.n_act) {
+        const int tA = list[q];
+        const int wA = W[tA], vA = V[tA];
+        const int sA = (wA + kSegCells - 1) / kSegCells + 1;  // segments the shifted operand reaches back
+        const bool first = q == 0;
+        row_transfers += first ? 1 : 2;  // every pass writes the row, all but the stage's first read it
+        int32_t *src = buf0 + (size_t)cur * row_len;
+        uint64_t *kwA = keep + ((size_t)inst * max_items + tA) * keep_words;
+        // try to take the next item along
+        int tB = 0, wB = 0, vB = 0, sB = 0, Rp = 0;
+        if (q + 1 < st.n_act) {
+            tB = list[q + 1];
+            wB = W[tB];
+            vB = V[tB];
+            sB = (wB + kSegCells - 1) / kSegCells + 1;
+            Rp = (ring_segs - 1 - sA - sB) / 3;
+        }
+        if (Rp >= 8) {
+            // ---- two items per pass -------------------------------------------------
+            const int R = Rp, n0 = 2 * R + sA, n1 = R + sB + 1;  // n0 + n1 <= ring_segs
+            uint64_t *kwB = keep + ((size_t)inst * max_items + tB) * keep_words;
+            if (loader) {
+                if (!first) load_segs(src, 0, min(R, nseg), 0, n0, 0);
+                barrier_after_loads();
+            } else {
+                barrier_after_lds_reads();
+            }
+            int slot0 = 0, slot1 = 0;  // lo % n0, lo % n1
+            for (int lo = 0; lo < nseg; lo += R) {
+                int slot0_next = slot0 + R, slot1_next = slot1 + R;
+                if (slot0_next >= n0) slot0_next -= n0;
+                if (slot1_next >= n1) slot1_next -= n1;
+                const int ns = min(R, nseg - lo);
+                if (loader) {
+                    if (!first && lo + R < nseg) load_segs(src, lo + R, min(R, nseg - lo - R), 0, n0, slot0_next);
+                    barrier_after_lds_reads();  // (phase 1 of this block is in ring 1)
+                    barrier_after_loads();      // the next block of the old row is in ring 0
+                } else {
+                    for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
+                        int s0 = slot0 + g, s1 = slot1 + g;
+                        if (s0 >= n0) s0 -= n0;
+                        if (s1 >= n1) s1 -= n1;
+                        run_task(yes, yes, 0, n0, wA, vA, lo + g, s0, src, first, src, n0, s1, kwA);
+                    }
+                    barrier_after_lds_reads();  // the block of the row after A is complete in ring 1
+                    for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
+                        int s1 = slot1 + g;
+                        if (s1 >= n1) s1 -= n1;
+                        run_task(yes, no, n0, n1, wB, vB, lo + g, s1, src, false, src, 0, 0, kwB);
+                    }
+                    barrier_after_lds_reads();  // ring slots may be reused
+                }
+                slot0 = slot0_next;
+                slot1 = slot1_next;
+            }
+            q += 2;  // the new row replaced the old one in buffer `cur`
+        } else {
+            // ---- one item per pass --------------------------------------------------
+            int32_t *dst = buf0 + (size_t)(cur ^ 1) * row_len;
+            const bool shifted_in_ring = sA + 2 <= ring_segs;
+            const int R = max(1, (shifted_in_ring ? ring_segs - sA : ring_segs) / 2);
+            if (loader) {
+                if (!first) load_segs(src, 0, min(R, nseg), 0, ring_segs, 0);
+                barrier_after_loads();
+            } else {
+                barrier_after_lds_reads();
+            }
+            int slot_lo = 0;  // lo % ring_segs
+            for (int lo = 0; lo < nseg; lo += R) {
+                int slot_next = slot_lo + R;
+                if (slot_next >= ring_segs) slot_next -= ring_segs;
+                if (loader) {
+                    if (!first && lo + R < nseg)
+                        load_segs(src, lo + R, min(R, nseg - lo - R), 0, ring_segs, slot_next);
+                    barrier_after_loads();  // the next block is in the ring
+                } else {
+                    const int ns = min(R, nseg - lo);
+                    for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
+                        int slot = slot_lo + g;
+                        if (slot >= ring_segs) slot -= ring_segs;
+                        if (shifted_in_ring)
+                            run_task(yes, no, 0, ring_segs, wA, vA, lo + g, slot, src, first, dst, 0, 0, kwA);
+                        else
+                            run_task(no, no, 0, ring_segs, wA, vA, lo + g, slot, src, first, dst, 0, 0, kwA);
+                    }
+                    barrier_after_lds_reads();  // this block's slots may be reused
+                }
+                slot_lo = slot_next;
+            }
+            cur ^= 1;
+            q += 1;
+        }
+        // the next pass reads what this one wrote (other wavefronts' cells included)
         __threadfence_block();
         __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        state[inst].buf = cur;
+        if (streamed_cells) atomicAdd(streamed_cells, (unsigned long long)row_transfers * nseg * kSegCells);
     }
 }
 
@@ -318,7 +405,7 @@ sg_traceback(BatchArgs a, InstState *state, const int32_t *__restrict__ act, con
     const int32_t *W = a.weights + (size_t)inst * a.item_stride;
     const int32_t *list = act + (size_t)inst * max_items;
     int value = 0;
-    if (nact > 0) value = rows[((size_t)inst * 2 + (nact & 1)) * row_len + C];
+    if (nact > 0) value = rows[((size_t)inst * 2 + (st->buf >= 0 ? st->buf : (nact & 1))) * row_len + C];
     int c = C;
     for (int q = nact - 1; q >= 0; --q) {
         const int t = list[q];
@@ -366,7 +453,7 @@ hipError_t seq_global_prepare(const SeqGlobalPlan &p)
 }
 
 hipError_t seq_global_launch(const SeqGlobalPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
-                             Profiler *prof)
+                             Profiler *prof, unsigned long long *streamed_cells)
 {
     const Scratch s = carve(p, scratch, p.max_batch);
     hipLaunchKernelGGL(sg_init, dim3(a.batch), dim3(kThreads), 0, st, a, s.state);
@@ -377,7 +464,8 @@ hipError_t seq_global_launch(const SeqGlobalPlan &p, const BatchArgs &a, void *s
         if (a.batch >= p.persistent_min_batch) {
             if (prof) prof->sweep_begin(st);
             hipLaunchKernelGGL(sg_sweep_all, dim3((unsigned)a.batch), dim3(kAllThreads), (size_t)p.lds_bytes, st, a,
-                               s.state, s.act, s.rows, s.keep, p.row_len, p.keep_words, p.max_items, p.ring_segs);
+                               s.state, s.act, s.rows, s.keep, p.row_len, p.keep_words, p.max_items, p.ring_segs,
+                               prof ? streamed_cells : nullptr);
             if (prof) prof->sweep_end(st);
         } else {
             for (int q = 0; q < a.item_stride; ++q) {
