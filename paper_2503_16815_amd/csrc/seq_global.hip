@@ -143,6 +143,8 @@ constexpr int kAllWaves = kAllThreads / 64;
 constexpr int kAllLoadWaves = 2;    // wavefronts that only move old cells from global memory into LDS
 constexpr int kAllComputeWaves = kAllWaves - kAllLoadWaves;
 constexpr int kSegCells = 256;      // one task / one 16-byte-per-lane LDS-direct load
+constexpr int kMaxItemsPerPass = 3; // temporal blocking depth of the persistent sweep
+constexpr int kMinBlockSegs = 14;   // smallest block worth an extra level: one task per computing wavefront
 
 typedef __attribute__((address_space(3))) int32_t lds_i32;
 typedef const __attribute__((address_space(1))) int32_t global_ci32;
@@ -164,11 +166,11 @@ __device__ __forceinline__ void barrier_after_lds_reads() { asm volatile("s_wait
 //    block being computed, the block being loaded and the cells up to w below:
 //    2 R + ceil(w / 256) + 1 <= ring_segs.  Items too heavy for that read their shifted
 //    operand from global memory (separate instantiation).
-//  * two items A, B (temporal blocking): the row after A exists only in LDS.  Ring 0 holds
-//    the old row (2 R + sA segments), ring 1 the row after A (R + sB + 1 segments),
-//    sA/B = ceil(wA/B / 256) + 1; per block, phase 1 computes A's block from ring 0 into
-//    ring 1, phase 2 computes B's block from ring 1 and stores it - into the buffer being
-//    read, behind the loads - so a cell-update costs half the HBM traffic.
+//  * g = 2 or 3 items (temporal blocking): the rows between the items exist only in LDS.
+//    Ring 0 holds the old row (2 R + s0 segments), ring l the row after item l - 1
+//    (R + sl + 1 segments), sl = ceil(wl / 256) + 1; per block, level l computes item l's
+//    block from ring l into ring l + 1, and the last level stores it - into the buffer
+//    being read, behind the loads - so a cell-update costs 1/g of the HBM traffic.
 // A compute task is one segment: lane l covers cells seg*256 + 64 j + l, j = 0..3, so the
 // v_cmp masks are the keep words of the segment.
 __global__ void __launch_bounds__(kAllThreads)
@@ -291,89 +293,122 @@ sg_sweep_all(BatchArgs a, InstState *__restrict__ state, const int32_t *__restri
     int q = 0;
     int row_transfers = 0;  // rows read from plus rows written to global memory
     while (q < st.n_act) {
-        const int tA = list[q];
-        const int wA = W[tA], vA = V[tA];
-        const int sA = (wA + kSegCells - 1) / kSegCells + 1;  // segments the shifted operand reaches back
         const bool first = q == 0;
         row_transfers += first ? 1 : 2;  // every pass writes the row, all but the stage's first read it
         int32_t *src = buf0 + (size_t)cur * row_len;
-        uint64_t *kwA = keep + ((size_t)inst * max_items + tA) * keep_words;
-        // try to take the next item along
-        int tB = 0, wB = 0, vB = 0, sB = 0, Rp = 0;
-        if (q + 1 < st.n_act) {
-            tB = list[q + 1];
-            wB = W[tB];
-            vB = V[tB];
-            sB = (wB + kSegCells - 1) / kSegCells + 1;
-            Rp = (ring_segs - 1 - sA - sB) / 3;
+        // the next up to kMaxItemsPerPass items: weight, value, reach in segments, keep row
+        int w[kMaxItemsPerPass], v[kMaxItemsPerPass], sg[kMaxItemsPerPass];
+        uint64_t *kw[kMaxItemsPerPass];
+#pragma unroll
+        for (int l = 0; l < kMaxItemsPerPass; ++l) {
+            const int t = list[min(q + l, st.n_act - 1)];
+            w[l] = W[t];
+            v[l] = V[t];
+            sg[l] = (w[l] + kSegCells - 1) / kSegCells + 1;  // segments the shifted operand reaches back
+            kw[l] = keep + ((size_t)inst * max_items + t) * keep_words;
         }
-        if (Rp >= 8) {
-            // ---- two items per pass -------------------------------------------------
-            const int R = Rp, n0 = 2 * R + sA, n1 = R + sB + 1;  // n0 + n1 <= ring_segs
-            uint64_t *kwB = keep + ((size_t)inst * max_items + tB) * keep_words;
+        // as many items per pass as leave blocks of at least kMinBlockSegs segments:
+        // (g + 1) R + sum of reaches + (g - 1) <= ring_segs
+        int g = 1, R = 0;
+        {
+            int reach = sg[0];
+#pragma unroll
+            for (int l = 1; l < kMaxItemsPerPass; ++l) {
+                reach += sg[l];
+                const int r = (ring_segs - l - reach) / (l + 2);
+                if (q + l < st.n_act && r >= kMinBlockSegs) { g = l + 1; R = r; }
+            }
+        }
+        if (g >= 2) {
+            // ---- g items per pass: ring 0 holds the old row (2 R + reach of item 0), ring l
+            // the row after item l - 1 (R + reach of item l + 1); level l reads ring l and
+            // writes ring l + 1, the last level stores to the buffer being read ------------
+            int rbase[kMaxItemsPerPass], rn[kMaxItemsPerPass], slot[kMaxItemsPerPass];
+            {
+                int at = 0;
+#pragma unroll
+                for (int l = 0; l < kMaxItemsPerPass; ++l) {
+                    rbase[l] = at;
+                    rn[l] = l == 0 ? 2 * R + sg[0] : R + sg[l] + 1;
+                    at += rn[l];
+                    slot[l] = 0;  // lo % rn[l]
+                }
+            }
             if (loader) {
-                if (!first) load_segs(src, 0, min(R, nseg), 0, n0, 0);
+                if (!first) load_segs(src, 0, min(R, nseg), 0, rn[0], 0);
                 barrier_after_loads();
             } else {
                 barrier_after_lds_reads();
             }
-            int slot0 = 0, slot1 = 0;  // lo % n0, lo % n1
             for (int lo = 0; lo < nseg; lo += R) {
-                int slot0_next = slot0 + R, slot1_next = slot1 + R;
-                if (slot0_next >= n0) slot0_next -= n0;
-                if (slot1_next >= n1) slot1_next -= n1;
+                int slot_next[kMaxItemsPerPass];
+#pragma unroll
+                for (int l = 0; l < kMaxItemsPerPass; ++l) {
+                    slot_next[l] = slot[l] + R;
+                    if (slot_next[l] >= rn[l]) slot_next[l] -= rn[l];
+                }
                 const int ns = min(R, nseg - lo);
                 if (loader) {
-                    if (!first && lo + R < nseg) load_segs(src, lo + R, min(R, nseg - lo - R), 0, n0, slot0_next);
-                    barrier_after_lds_reads();  // (phase 1 of this block is in ring 1)
-                    barrier_after_loads();      // the next block of the old row is in ring 0
+                    if (!first && lo + R < nseg) load_segs(src, lo + R, min(R, nseg - lo - R), 0, rn[0], slot_next[0]);
+                    for (int l = 0; l + 1 < g; ++l) barrier_after_lds_reads();  // (levels of this block)
+                    barrier_after_loads();  // the next block of the old row is in ring 0
                 } else {
-                    for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
-                        int s0 = slot0 + g, s1 = slot1 + g;
-                        if (s0 >= n0) s0 -= n0;
-                        if (s1 >= n1) s1 -= n1;
-                        run_task(yes, yes, 0, n0, wA, vA, lo + g, s0, src, first, src, n0, s1, kwA);
+#pragma unroll
+                    for (int l = 0; l < kMaxItemsPerPass; ++l) {
+                        if (l < g) {
+                            const bool last = l + 1 == g;
+                            for (int i = wave - kAllLoadWaves; i < ns; i += kAllComputeWaves) {
+                                int s_in = slot[l] + i;
+                                if (s_in >= rn[l]) s_in -= rn[l];
+                                if (last) {
+                                    run_task(yes, no, rbase[l], rn[l], w[l], v[l], lo + i, s_in, src, first && l == 0, src, 0,
+                                             0, kw[l]);
+                                } else {
+                                    int s_out = slot[l + 1 < kMaxItemsPerPass ? l + 1 : l] + i;
+                                    const int rn_out = rn[l + 1 < kMaxItemsPerPass ? l + 1 : l];
+                                    if (s_out >= rn_out) s_out -= rn_out;
+                                    run_task(yes, yes, rbase[l], rn[l], w[l], v[l], lo + i, s_in, src, first && l == 0, src,
+                                             rbase[l + 1 < kMaxItemsPerPass ? l + 1 : l], s_out, kw[l]);
+                                }
+                            }
+                            barrier_after_lds_reads();  // level l of the block is complete
+                        }
                     }
-                    barrier_after_lds_reads();  // the block of the row after A is complete in ring 1
-                    for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
-                        int s1 = slot1 + g;
-                        if (s1 >= n1) s1 -= n1;
-                        run_task(yes, no, n0, n1, wB, vB, lo + g, s1, src, false, src, 0, 0, kwB);
-                    }
-                    barrier_after_lds_reads();  // ring slots may be reused
                 }
-                slot0 = slot0_next;
-                slot1 = slot1_next;
+#pragma unroll
+                for (int l = 0; l < kMaxItemsPerPass; ++l) slot[l] = slot_next[l];
             }
-            q += 2;  // the new row replaced the old one in buffer `cur`
+            q += g;  // the new row replaced the old one in buffer `cur`
         } else {
             // ---- one item per pass --------------------------------------------------
             int32_t *dst = buf0 + (size_t)(cur ^ 1) * row_len;
+            const int wA = w[0], vA = v[0], sA = sg[0];
+            uint64_t *kwA = kw[0];
             const bool shifted_in_ring = sA + 2 <= ring_segs;
-            const int R = max(1, (shifted_in_ring ? ring_segs - sA : ring_segs) / 2);
+            const int R1 = max(1, (shifted_in_ring ? ring_segs - sA : ring_segs) / 2);
             if (loader) {
-                if (!first) load_segs(src, 0, min(R, nseg), 0, ring_segs, 0);
+                if (!first) load_segs(src, 0, min(R1, nseg), 0, ring_segs, 0);
                 barrier_after_loads();
             } else {
                 barrier_after_lds_reads();
             }
             int slot_lo = 0;  // lo % ring_segs
-            for (int lo = 0; lo < nseg; lo += R) {
-                int slot_next = slot_lo + R;
+            for (int lo = 0; lo < nseg; lo += R1) {
+                int slot_next = slot_lo + R1;
                 if (slot_next >= ring_segs) slot_next -= ring_segs;
                 if (loader) {
-                    if (!first && lo + R < nseg)
-                        load_segs(src, lo + R, min(R, nseg - lo - R), 0, ring_segs, slot_next);
+                    if (!first && lo + R1 < nseg)
+                        load_segs(src, lo + R1, min(R1, nseg - lo - R1), 0, ring_segs, slot_next);
                     barrier_after_loads();  // the next block is in the ring
                 } else {
-                    const int ns = min(R, nseg - lo);
-                    for (int g = wave - kAllLoadWaves; g < ns; g += kAllComputeWaves) {
-                        int slot = slot_lo + g;
-                        if (slot >= ring_segs) slot -= ring_segs;
+                    const int ns = min(R1, nseg - lo);
+                    for (int i = wave - kAllLoadWaves; i < ns; i += kAllComputeWaves) {
+                        int sl = slot_lo + i;
+                        if (sl >= ring_segs) sl -= ring_segs;
                         if (shifted_in_ring)
-                            run_task(yes, no, 0, ring_segs, wA, vA, lo + g, slot, src, first, dst, 0, 0, kwA);
+                            run_task(yes, no, 0, ring_segs, wA, vA, lo + i, sl, src, first, dst, 0, 0, kwA);
                         else
-                            run_task(no, no, 0, ring_segs, wA, vA, lo + g, slot, src, first, dst, 0, 0, kwA);
+                            run_task(no, no, 0, ring_segs, wA, vA, lo + i, sl, src, first, dst, 0, 0, kwA);
                     }
                     barrier_after_lds_reads();  // this block's slots may be reused
                 }
