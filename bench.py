@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel, so that a counter profile of this "
                          "command holds a row of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--no-per-k", action="store_true",
+                    help="skip the extra timing of the one-call-per-k reading (profiling runs: keeps the kernel "
+                         "statistics to the headline launches)")
     ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
     ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()
@@ -174,7 +177,7 @@ def main() -> int:
         # The same candidate set as one call per k (the other way to read "a batch of 1024
         # profiles, k = 1..4"): timed beside the headline so that both readings are on record.
         per_k = None
-        if args.workload in ("resnet101", "vgg19") and len(calls) == 1 and plain_run:
+        if args.workload in ("resnet101", "vgg19") and len(calls) == 1 and plain_run and not args.no_per_k:
             from paper_2503_16815_amd import workloads as W
             gen, b0 = (W.resnet101_shaped, 1024) if args.workload == "resnet101" else (W.vgg19_shaped, 4096)
             kdbs = [h.upload(gen(k=k, batch=b0)) for k in (1, 2, 3, 4)]
