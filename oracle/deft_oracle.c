@@ -18,6 +18,10 @@
  *   - Section III.C, Problem 2: two knapsacks (links), each item in at most
  *     one; generalised to a separate weight per link (the paper's single c_j
  *     with a capacity scaled by mu is the case w1 == w2).
+ *   - Section III.B, Algorithm 1 (RecursiveKnapsack): the knapsack over the whole
+ *     list with the remaining time, against the same procedure on the list
+ *     without its last item and with that item's time taken off the remaining
+ *     time; the shallower answer wins only if its sum is strictly greater.
  *
  * Conventions the paper leaves open, fixed here:
  *   - an item is taken at capacity c only if it strictly improves the value;
@@ -233,11 +237,90 @@ int deft_oracle_joint2(int32_t n, int32_t item_stride, const int32_t *w1, const 
     return ST_OK;
 }
 
+/*
+ * Algorithm 1 (RecursiveKnapsack) for one instance, written as the recursion it is.
+ * Items 0 .. n-1 are the list C_1 .. C_N in generation order; drop[i] is the time taken
+ * off the remaining time when item i (the last of the current list) is left out of the
+ * list.  A list solved with a negative remaining time schedules nothing.
+ * Outputs: assign[i] = 0 for scheduled items else -1; knap_value[0] / knap_load[0] =
+ * value and weight scheduled; knap_value[1] = number of items dropped from the end of
+ * the list at the level whose answer was returned (n if nothing is scheduled at any
+ * level), knap_load[1] = the remaining time of that level (0 if none).
+ */
+typedef struct { int64_t value, load, remain; int len; uint8_t *chosen; } rec_result_t;
+
+static int recursive_knapsack(int len, const int32_t *w, const int32_t *v, const int32_t *drop,
+                              int64_t remain, rec_result_t *out, int64_t *touched, int64_t *table)
+{
+    if (len == 0) {                              /* CommTimeList is empty: return the empty order */
+        out->value = 0; out->load = 0; out->remain = 0; out->len = 0;
+        return ST_OK;
+    }
+    /* order1 = NaiveKnapsack(CommTimeList, remainTime) */
+    rec_result_t one = { 0, 0, remain, len, NULL };
+    one.chosen = (uint8_t *)calloc((size_t)len, 1);
+    if (!one.chosen) return ST_OOM;
+    if (remain >= 0) {
+        int rc = single_stage(len, w, v, (int32_t)remain, &one.value, &one.load, one.chosen, touched, table);
+        if (rc != ST_OK) { free(one.chosen); return rc; }
+    }
+    /* order2 = RecursiveKnapsack(CommTimeList - C_N, remainTime - T_{N-1}) */
+    rec_result_t two = { 0, 0, 0, 0, NULL };
+    two.chosen = out->chosen;                    /* the deeper levels write into the caller's buffer */
+    int rc = recursive_knapsack(len - 1, w, v, drop, remain - drop[len - 1], &two, touched, table);
+    if (rc != ST_OK) { free(one.chosen); return rc; }
+    if (one.value > two.value) {                 /* sum(order1) > sum(order2): return order1 */
+        memcpy(out->chosen, one.chosen, (size_t)len);
+        out->value = one.value; out->load = one.load; out->remain = remain; out->len = len;
+    } else {                                     /* else return order2 (already in out->chosen) */
+        out->value = two.value; out->load = two.load; out->remain = two.remain; out->len = two.len;
+    }
+    free(one.chosen);
+    return ST_OK;
+}
+
+int deft_oracle_recursive(int32_t n, int32_t item_stride, const int32_t *w, const int32_t *v,
+                          const int32_t *drop, int32_t m, int32_t knap_stride, const int32_t *cap,
+                          int32_t cap_limit, int64_t *total, int32_t *knap_value, int32_t *knap_load,
+                          int32_t *assign, int64_t *touched_cells, int64_t *table_cells)
+{
+    int64_t touched = 0, table = 0;
+    clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+    if (touched_cells) *touched_cells = 0;
+    if (table_cells) *table_cells = 0;
+    if (n < 0 || n > item_stride || m != 1 || knap_stride < 2) return ST_INVALID;
+    for (int i = 0; i < n; ++i)
+        if (w[i] < 1 || v[i] < 0 || drop[i] < 0) return ST_INVALID;
+    if (cap[0] < 0) return ST_INVALID;
+    if (cap_limit >= 0 && cap[0] > cap_limit) return ST_LIMIT;
+    int64_t vsum = 0;
+    for (int i = 0; i < n; ++i) vsum += v[i];
+    if (vsum >= VALUE_SUM_LIMIT) return ST_OVERFLOW;
+
+    rec_result_t res = { 0, 0, 0, 0, NULL };
+    res.chosen = (uint8_t *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!res.chosen) return ST_OOM;
+    int rc = recursive_knapsack(n, w, v, drop, cap[0], &res, &touched, &table);
+    if (rc != ST_OK) { free(res.chosen); return rc; }
+    if (res.value == 0) res.len = 0;             /* nothing scheduled at any level: the empty order */
+    for (int i = 0; i < res.len; ++i)
+        if (res.chosen[i]) assign[i] = 0;
+    knap_value[0] = (int32_t)res.value;
+    knap_load[0] = (int32_t)res.load;
+    knap_value[1] = n - res.len;
+    knap_load[1] = res.len > 0 ? (int32_t)res.remain : 0;
+    *total = res.value;
+    if (touched_cells) *touched_cells = touched;
+    if (table_cells) *table_cells = table;
+    free(res.chosen);
+    return ST_OK;
+}
+
 /* ---- batch driver: instances split statically over nthreads ------------- */
 
 typedef struct {
     int32_t mode, batch, item_stride, knap_stride;
-    const int32_t *n_items, *n_knapsacks, *weights, *values, *capacities, *fill_order;
+    const int32_t *n_items, *n_knapsacks, *weights, *values, *capacities, *fill_order, *drop_time;
     int32_t cap_limit, c1_limit, c2_limit;
     int64_t *total;
     int32_t *knap_value, *knap_load, *assign, *status;
@@ -258,6 +341,12 @@ static void solve_one(const batch_args_t *a, int b)
                                     a->fill_order ? a->fill_order + b * ks : NULL, a->cap_limit,
                                     a->total + b, a->knap_value + b * ks, a->knap_load + b * ks,
                                     a->assign + b * is, &touched, &table);
+    } else if (a->mode == 2) {
+        st = deft_oracle_recursive(a->n_items[b], a->item_stride, a->weights + b * is, a->values + b * is,
+                                   a->drop_time + b * is, a->n_knapsacks[b], a->knap_stride,
+                                   a->capacities + b * ks, a->cap_limit, a->total + b,
+                                   a->knap_value + b * ks, a->knap_load + b * ks, a->assign + b * is,
+                                   &touched, &table);
     } else {
         st = deft_oracle_joint2(a->n_items[b], a->item_stride, a->weights + b * 2 * is,
                                 a->weights + b * 2 * is + is, a->values + b * is,
@@ -282,14 +371,16 @@ int deft_oracle_solve_batch(int32_t mode, int32_t batch, int32_t item_stride, in
                             const int32_t *n_items, const int32_t *n_knapsacks,
                             const int32_t *weights, const int32_t *values,
                             const int32_t *capacities, const int32_t *fill_order,
+                            const int32_t *drop_time,
                             int32_t cap_limit, int32_t c1_limit, int32_t c2_limit,
                             int64_t *total, int32_t *knap_value, int32_t *knap_load,
                             int32_t *assign, int32_t *status, int64_t *touched, int64_t *table,
                             int32_t nthreads)
 {
-    if ((mode != 0 && mode != 1) || batch < 0 || item_stride < 0 || knap_stride < 0) return -1;
+    if (mode < 0 || mode > 2 || (mode == 2 && !drop_time) || batch < 0 || item_stride < 0 || knap_stride < 0)
+        return -1;
     batch_args_t a = { mode, batch, item_stride, knap_stride, n_items, n_knapsacks, weights,
-                       values, capacities, fill_order, cap_limit, c1_limit, c2_limit, total,
+                       values, capacities, fill_order, drop_time, cap_limit, c1_limit, c2_limit, total,
                        knap_value, knap_load, assign, status, touched, table };
     if (nthreads < 1) nthreads = 1;
     if (nthreads > batch) nthreads = batch > 0 ? batch : 1;

@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
 benchmark's cpu_baseline leg, never by the HIP product path.  It takes plain
 numpy arrays (any object with the fields of a solver call: mode, batch,
 item_stride, knap_stride, n_items, n_knapsacks, weights, values, capacities,
-fill_order) and imports nothing from the HIP package.
+fill_order, and drop_time for the recursive mode) and imports nothing from the HIP package.
 """
 from __future__ import annotations
 
@@ -41,7 +41,7 @@ def _load():
         p64 = ctypes.POINTER(ctypes.c_int64)
         i32 = ctypes.c_int32
         lib.deft_oracle_solve_batch.restype = ctypes.c_int
-        lib.deft_oracle_solve_batch.argtypes = [i32, i32, i32, i32, p32, p32, p32, p32, p32, p32,
+        lib.deft_oracle_solve_batch.argtypes = [i32, i32, i32, i32, p32, p32, p32, p32, p32, p32, p32,
                                                 i32, i32, i32, p64, p32, p32, p32, p32, p64, p64, i32]
         _lib = lib
     return _lib
@@ -75,9 +75,11 @@ def solve_batch(kb, cap_limit: int = -1, c1_limit: int = -1, c2_limit: int = -1,
     n_items, n_knap = c(kb.n_items), c(kb.n_knapsacks)
     w, v, cap = c(kb.weights), c(kb.values), c(kb.capacities)
     fo = None if kb.fill_order is None else c(kb.fill_order)
+    dt = None if getattr(kb, "drop_time", None) is None else c(kb.drop_time)
+    assert kb.mode != 2 or (dt is not None and dt.shape == (B, IS))
     assert n_items.shape == (B,) and n_knap.shape == (B,)
     assert v.shape == (B, IS) and cap.shape == (B, KS)
-    assert w.shape == ((B, IS) if kb.mode == 0 else (B, 2, IS))
+    assert w.shape == ((B, 2, IS) if kb.mode == 1 else (B, IS))
     total = np.zeros(B, np.int64)
     kv = np.zeros((B, KS), np.int32)
     kl = np.zeros((B, KS), np.int32)
@@ -87,7 +89,7 @@ def solve_batch(kb, cap_limit: int = -1, c1_limit: int = -1, c2_limit: int = -1,
     table = np.zeros(B, np.int64)
     used = lib.deft_oracle_solve_batch(
         kb.mode, B, IS, KS, _p32(n_items), _p32(n_knap), _p32(w), _p32(v), _p32(cap),
-        None if fo is None else _p32(fo), cap_limit, c1_limit, c2_limit,
+        None if fo is None else _p32(fo), None if dt is None else _p32(dt), cap_limit, c1_limit, c2_limit,
         _p64(total), _p32(kv), _p32(kl), _p32(asg), _p32(st), _p64(touched), _p64(table), nthreads)
     if used < 0:
         raise ValueError("oracle: bad batch arguments")

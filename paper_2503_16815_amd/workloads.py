@@ -32,6 +32,7 @@ import numpy as np
 
 MODE_SEQUENTIAL = 0
 MODE_JOINT2 = 1
+MODE_RECURSIVE = 2
 
 SEED_TINY = 1001
 SEED_RESNET = 1002
@@ -61,6 +62,7 @@ class KnapsackBatch:
     capacities: np.ndarray
     fill_order: Optional[np.ndarray] = None
     meta: dict = field(default_factory=dict)
+    drop_time: Optional[np.ndarray] = None   # [batch, item_stride], recursive mode only
 
     def slice(self, lo: int, hi: int) -> "KnapsackBatch":
         fo = None if self.fill_order is None else np.ascontiguousarray(self.fill_order[lo:hi])
@@ -72,7 +74,8 @@ class KnapsackBatch:
             weights=np.ascontiguousarray(self.weights[lo:hi]),
             values=np.ascontiguousarray(self.values[lo:hi]),
             capacities=np.ascontiguousarray(self.capacities[lo:hi]),
-            fill_order=fo, meta=dict(self.meta))
+            fill_order=fo, meta=dict(self.meta),
+            drop_time=None if self.drop_time is None else np.ascontiguousarray(self.drop_time[lo:hi]))
 
     def max_capacity(self) -> int:
         return int(self.capacities.max()) if self.capacities.size else 0
@@ -249,3 +252,41 @@ def random_joint(seed: int, batch: int, n_max: int, w_hi: int, v_hi: int, c1_hi:
         name=f"random_joint_{seed}", mode=MODE_JOINT2, batch=batch, item_stride=n_max, knap_stride=2,
         n_items=_i32(n_items), n_knapsacks=_i32(np.full(batch, 2)), weights=_i32(w), values=_i32(v),
         capacities=_i32(cap), meta={"seed": seed})
+
+
+def random_recursive(seed: int, batch: int, n_max: int, w_hi: int, v_hi: int, cap_hi: int, t_hi: int,
+                     ragged: bool = True, ties: bool = False) -> KnapsackBatch:
+    """Batches for Algorithm 1 (Section III.B): items in generation order, one remaining
+    time per instance, and per item the time that leaving it out of the list takes off
+    the remaining time (drawn in [0, t_hi]).  knap_stride is 2: slot 1 of the outputs
+    reports the level whose answer was returned."""
+    r = _rng(seed)
+    n_items = r.integers(0, n_max + 1, size=batch) if ragged else np.full(batch, n_max)
+    w = r.integers(1, w_hi + 1, size=(batch, n_max))
+    v = w.copy() if ties else r.integers(0, v_hi + 1, size=(batch, n_max))
+    cap = np.zeros((batch, 2), dtype=np.int64)
+    cap[:, 0] = r.integers(0, cap_hi + 1, size=batch)
+    drop = r.integers(0, t_hi + 1, size=(batch, n_max))
+    return KnapsackBatch(
+        name=f"random_recursive_{seed}", mode=MODE_RECURSIVE, batch=batch, item_stride=n_max, knap_stride=2,
+        n_items=_i32(n_items), n_knapsacks=_i32(np.full(batch, 1)), weights=_i32(w), values=_i32(v),
+        capacities=_i32(cap), meta={"seed": seed}, drop_time=_i32(drop))
+
+
+def backward_stage_shaped(batch: int = 1024, n: int = 314, seed: int = SEED_RESNET + 50) -> KnapsackBatch:
+    """ResNet-101-shaped backward stage for Algorithm 1 (Cases 3 and 4): the buckets of
+    the running iteration appear one after the other while the backward pass computes, so
+    scheduling only the first N - d of them may start d bucket computations later: items
+    = bucket communication times (as resnet101_shaped), remaining time = the backward
+    window, and leaving out bucket i costs its share of the backward computation time
+    (proportional to its size, summing to the window)."""
+    r = _rng(seed)
+    x = r.lognormal(mean=0.0, sigma=1.2, size=(batch, n))
+    w = _rescale_to_sum(x, 24200.0)
+    cap = np.zeros((batch, 2), dtype=np.int64)
+    cap[:, 0] = np.rint(11800.0 * r.uniform(0.9, 1.1, size=batch)).astype(np.int64)
+    drop = np.maximum(0, np.rint(x / x.sum(axis=1, keepdims=True) * cap[:, :1])).astype(np.int64)
+    return KnapsackBatch(
+        name="backward_stage", mode=MODE_RECURSIVE, batch=batch, item_stride=n, knap_stride=2,
+        n_items=_i32(np.full(batch, n)), n_knapsacks=_i32(np.full(batch, 1)), weights=_i32(w), values=_i32(w.copy()),
+        capacities=_i32(cap), meta={"seed": seed}, drop_time=_i32(drop))

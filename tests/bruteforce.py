@@ -75,3 +75,27 @@ def best_two_link(w1, w2, v, c1, c2):
         assign.append(num % 3 - 1)
         num //= 3
     return best, assign
+
+
+def recursive_prefixes(w, v, drop, remain):
+    """Algorithm 1 by its meaning rather than its recursion: level d (d = 0 .. n) keeps
+    the first n - d items and has remain - sum of drop over the d items left out; each
+    level is solved by enumeration; the answer is the best level, and among equal levels
+    the one with the most items left out (the recursion only prefers the shallower
+    answer when it is strictly better).  Nothing scheduled anywhere -> level n.
+    Returns (value, load, level, level's remaining time, assignment 0 / -1)."""
+    n = len(w)
+    best = (0, 0, n, 0, [-1] * n)
+    rem = int(remain) - int(sum(drop))
+    for d in range(n, -1, -1):           # deepest first; shallower must be strictly better
+        if d < n:
+            rem += int(drop[n - 1 - d])  # level d leaves out items n-d .. n-1 only
+        k = n - d
+        if k == 0 or rem < 0:
+            continue
+        val, mask = best_subset(w[:k], v[:k], rem)
+        if val > best[0]:
+            asg = [0 if (mask >> t) & 1 else -1 for t in range(k)] + [-1] * d
+            load = sum(int(w[t]) for t in range(k) if (mask >> t) & 1)
+            best = (val, load, d, rem, asg)
+    return best
