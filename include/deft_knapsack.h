@@ -35,7 +35,8 @@ typedef enum {
 
 enum {
     DEFT_MODE_SEQUENTIAL = 0, /* m knapsacks filled one after the other (Sec. III.B)       */
-    DEFT_MODE_JOINT2 = 1      /* two links, one joint 2-D DP (Sec. III.C, Problem 2)       */
+    DEFT_MODE_JOINT2 = 1,     /* two links, one joint 2-D DP (Sec. III.C, Problem 2)       */
+    DEFT_MODE_RECURSIVE = 2   /* one window, the list shortened from its end (Algorithm 1) */
 };
 
 /* Limits fixed at create time; they size the scratch memory and select the
@@ -81,6 +82,22 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *   the incumbent only when strictly greater; traced back from the last item.
  *   n_knapsacks must be 2.
  *
+ * DEFT_MODE_RECURSIVE (Sec. III.B, Algorithm 1, RecursiveKnapsack):
+ *   Items are the list in generation order, capacities[b][0] is the remaining time R.
+ *   Level d (d = 0 .. n) keeps the first n - d items and has R minus the drop_time of the
+ *   d items left off; a level whose remaining time is negative schedules nothing.  Each
+ *   level is solved exactly as a SEQUENTIAL stage (same tie rule); the answer is the
+ *   level with the greatest value, and among equal levels the one with the most items
+ *   left off (the recursion prefers the shorter list unless the longer one is strictly
+ *   better).  All levels come out of one DP sweep: the row after item i is level
+ *   n - 1 - i's row.  n_knapsacks must be 1 and knap_stride >= 2:
+ *     knap_value[0], knap_load[0]  value and weight scheduled; total_value = knap_value[0]
+ *     knap_value[1]                d of the level returned (n if nothing is scheduled)
+ *     knap_load[1]                 that level's remaining time (0 if nothing is scheduled)
+ *     assignment                   0 for scheduled items, else -1
+ *   fill_order is ignored.  Only handles whose max_capacity fits the LDS-resident row
+ *   (seq_path 1 or 2) serve this mode; others return LIMIT from the call.
+ *
  * Layout (row-major, device memory):
  *   n_items     [batch]                      0 <= n_items[b] <= item_stride
  *   n_knapsacks [batch]                      0 <= n_knapsacks[b] <= knap_stride
@@ -89,6 +106,7 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *   values      [batch][item_stride]         each >= 0, sum per instance < 2^31
  *   capacities  [batch][knap_stride]         indexed by knapsack id, each >= 0
  *   fill_order  [batch][knap_stride] or NULL a permutation of 0..n_knapsacks[b]-1
+ *   drop_time   RECURSIVE [batch][item_stride] each >= 0 (unused, may be NULL, otherwise)
  * Outputs (every slot of every row is written):
  *   total_value [batch] int64                sum of knap_value
  *   knap_value  [batch][knap_stride]         value placed in knapsack j (unused slots 0)
@@ -96,7 +114,8 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *   assignment  [batch][item_stride]         knapsack id, or -1 (also for slots >= n_items)
  *   status      [batch]                      deft_status_t of the instance
  * A faulted instance (status != DEFT_OK: bad n/m, w < 1, v < 0, capacity < 0,
- * fill_order not a permutation -> INVALID_ARG; capacity above the create-time
+ * fill_order not a permutation, drop_time < 0, RECURSIVE with n_knapsacks != 1
+ * -> INVALID_ARG; capacity above the create-time
  * limit -> LIMIT; value sum >= 2^31 -> OVERFLOW; in that precedence) gets
  * total_value 0, knap_value/knap_load 0 and assignment -1; other instances are
  * unaffected.
@@ -105,7 +124,7 @@ typedef struct {
     int32_t mode;        /* DEFT_MODE_*                                                    */
     int32_t batch;       /* 0 .. max_batch (0 is a no-op)                                  */
     int32_t item_stride; /* 1 .. max_items                                                 */
-    int32_t knap_stride; /* 1 .. max_knapsacks (>= 2 for JOINT2)                           */
+    int32_t knap_stride; /* 1 .. max_knapsacks (>= 2 for JOINT2 and RECURSIVE)             */
     const int32_t *n_items;
     const int32_t *n_knapsacks;
     const int32_t *weights;
@@ -118,6 +137,7 @@ typedef struct {
     int32_t *assignment;
     int32_t *status;
     void *stream; /* hipStream_t; NULL = the default stream */
+    const int32_t *drop_time; /* RECURSIVE mode only */
 } deft_knapsack_batch_t;
 
 /*

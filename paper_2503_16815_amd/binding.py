@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DEFT_KNAPSACK_LIB") or os.path.join(_HERE, "libdeft_knapsack.so")
 
 DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, DEFT_ERR_DEVICE = range(6)
-DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2 = 0, 1
+DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2, DEFT_MODE_RECURSIVE = 0, 1, 2
 
 EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_destroy",
            "deft_knapsack_get_info", "deft_knapsack_set_profiling", "deft_knapsack_get_profile",
@@ -37,7 +37,7 @@ class deft_knapsack_batch_t(ctypes.Structure):
                 ("values", ctypes.c_void_p), ("capacities", ctypes.c_void_p), ("fill_order", ctypes.c_void_p),
                 ("total_value", ctypes.c_void_p), ("knap_value", ctypes.c_void_p),
                 ("knap_load", ctypes.c_void_p), ("assignment", ctypes.c_void_p), ("status", ctypes.c_void_p),
-                ("stream", ctypes.c_void_p)]
+                ("stream", ctypes.c_void_p), ("drop_time", ctypes.c_void_p)]
 
 
 class deft_knapsack_info_t(ctypes.Structure):
@@ -119,6 +119,8 @@ class DeviceBatch:
         self.values = _dev_i32(kb.values, device)
         self.capacities = _dev_i32(kb.capacities, device)
         self.fill_order = None if kb.fill_order is None else _dev_i32(kb.fill_order, device)
+        drop = getattr(kb, "drop_time", None)
+        self.drop_time = None if drop is None else _dev_i32(drop, device)
         B, IS, KS = self.batch, self.item_stride, self.knap_stride
         self.out = SolveOutputs(
             total_value=torch.empty(B, dtype=torch.int64, device=device),
@@ -134,7 +136,7 @@ class DeviceBatch:
             self.mode, self.batch, self.item_stride, self.knap_stride,
             p(self.n_items), p(self.n_knapsacks), p(self.weights), p(self.values), p(self.capacities),
             p(self.fill_order), p(o.total_value), p(o.knap_value), p(o.knap_load), p(o.assignment),
-            p(o.status), ctypes.c_void_p(stream_handle))
+            p(o.status), ctypes.c_void_p(stream_handle), p(self.drop_time))
 
 
 class DeftKnapsack:
@@ -200,7 +202,7 @@ class DeftKnapsack:
 
 def solve(kb, device: int = 0, **limits) -> SolveOutputs:
     """Convenience: create a handle sized for `kb`, solve, synchronise, destroy."""
-    seq = kb.mode == DEFT_MODE_SEQUENTIAL
+    seq = kb.mode != DEFT_MODE_JOINT2
     cap = int(kb.capacities.max()) if kb.capacities.size else 1
     args = dict(max_batch=max(1, kb.batch), max_items=kb.item_stride, max_knapsacks=kb.knap_stride,
                 max_capacity=max(1, cap) if seq else 0,

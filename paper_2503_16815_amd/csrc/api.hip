@@ -129,7 +129,7 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
         const int lds_wg = (int)prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin
                                                                 : (int)prop.sharedMemPerBlock;
         if (seq_lds_plan(cfg->max_capacity, cfg->max_items, cfg->max_knapsacks, cfg->max_batch, lds_wg, &h->lds_plan) &&
-            seq_lds_prepare(&h->lds_plan) == hipSuccess) {
+            seq_lds_prepare(&h->lds_plan) == hipSuccess && seq_lds_rec_prepare(h->lds_plan) == hipSuccess) {
             h->seq_path = h->lds_plan.threads == 64 ? 1 : 2;
             st = alloc(&h->keep, h->lds_plan.scratch_bytes, &h->scratch_bytes);
         } else {
@@ -177,9 +177,11 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
 extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *b)
 {
     if (!h || !b) return DEFT_ERR_INVALID_ARG;
-    if (b->mode != DEFT_MODE_SEQUENTIAL && b->mode != DEFT_MODE_JOINT2) return DEFT_ERR_INVALID_ARG;
+    if (b->mode != DEFT_MODE_SEQUENTIAL && b->mode != DEFT_MODE_JOINT2 && b->mode != DEFT_MODE_RECURSIVE)
+        return DEFT_ERR_INVALID_ARG;
     if (b->batch < 0 || b->item_stride < 1 || b->knap_stride < 1) return DEFT_ERR_INVALID_ARG;
-    if (b->mode == DEFT_MODE_JOINT2 && b->knap_stride < 2) return DEFT_ERR_INVALID_ARG;
+    if (b->mode != DEFT_MODE_SEQUENTIAL && b->knap_stride < 2) return DEFT_ERR_INVALID_ARG;
+    if (b->mode == DEFT_MODE_RECURSIVE && !b->drop_time) return DEFT_ERR_INVALID_ARG;
     if (!b->n_items || !b->n_knapsacks || !b->weights || !b->values || !b->capacities || !b->total_value ||
         !b->knap_value || !b->knap_load || !b->assignment || !b->status)
         return DEFT_ERR_INVALID_ARG;
@@ -188,6 +190,8 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         return DEFT_ERR_LIMIT;
     if (b->mode == DEFT_MODE_SEQUENTIAL && h->seq_path == 0) return DEFT_ERR_LIMIT;
     if (b->mode == DEFT_MODE_JOINT2 && h->joint_path == 0) return DEFT_ERR_LIMIT;
+    // Algorithm 1 runs on the LDS-resident row only
+    if (b->mode == DEFT_MODE_RECURSIVE && h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;
     if (b->batch == 0) return DEFT_OK;
 
     DeviceGuard g(h->cfg.device);
@@ -207,6 +211,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     a.values = b->values;
     a.capacities = b->capacities;
     a.fill_order = b->fill_order;
+    a.drop_time = b->mode == DEFT_MODE_RECURSIVE ? b->drop_time : nullptr;
     a.total_value = b->total_value;
     a.knap_value = b->knap_value;
     a.knap_load = b->knap_load;
@@ -225,6 +230,10 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
             e = seq_lds_launch(h->lds_plan, a, h->keep, st);
             if (prof) prof->sweep_end(st);
         }
+    } else if (b->mode == DEFT_MODE_RECURSIVE) {
+        if (prof) prof->sweep_begin(st);
+        e = seq_lds_rec_launch(h->lds_plan, a, h->keep, st);
+        if (prof) prof->sweep_end(st);
     } else {
         e = joint_launch(h->joint_plan, a, h->joint_scratch, st, prof);
     }

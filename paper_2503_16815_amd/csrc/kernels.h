@@ -14,6 +14,7 @@ struct BatchArgs {
     int32_t batch, item_stride, knap_stride;
     int32_t max_capacity, max_c1, max_c2;  // create-time limits (per-instance LIMIT status)
     const int32_t *n_items, *n_knapsacks, *weights, *values, *capacities, *fill_order;
+    const int32_t *drop_time;  // recursive mode only
     int64_t *total_value;
     int32_t *knap_value, *knap_load, *assignment, *status;
 };
@@ -46,6 +47,10 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
 hipError_t seq_lds_prepare(SeqLdsPlan *plan);
 hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
                           hipStream_t stream);
+// Algorithm 1 (recursive mode) under the same plan and scratch (seq_lds_rec.hip).
+hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan);
+hipError_t seq_lds_rec_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
+                              hipStream_t stream);
 
 // ---- per-call HIP-event timing (profile.hip) ---------------------------------
 class Profiler {

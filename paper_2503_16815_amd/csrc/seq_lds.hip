@@ -1,553 +1,8 @@
-// Sequential multiple-knapsack solve with the capacity row resident in LDS.
-//
-// One launch solves every stage of every instance (Sec. III.B: Problem 1 per
-// window, windows filled one after the other).  An instance is owned by T
-// lanes.  Cell c of the row lives in lane (c mod T), register slot (c div T),
-// and a copy lives in LDS so that the shifted operand row[c - w] can be read
-// by whichever lane needs it.  Per offered item:
-//   phase A  every lane reads row[c - w] for its cells (LDS, 4 B/cell) and, as
-//            the values arrive, computes cand = row[c - w] + v, take = cand >
-//            row[c], row[c] = max(row[c], cand) in registers; the reads run a
-//            fixed number of slots ahead of the arithmetic
-//   barrier  (every lane has read the old row)
-//   phase B  the new cells are written back (LDS, 4 B/cell); the take bits, one
-//            32-bit word per 32 register slots, go to the keep table (HBM,
-//            1/8 B/cell)
-//   barrier  (the new row is visible)
-// The textbook reverse sweep (c from C down to w) exists to read old values
-// only; reading everything before the first barrier gives the same result.
-// Cells below w must not change.  A guard zone of 128 or 256 cells holding
-// INT_MIN (which can never win) sits below the row: for w <= guard size every
-// lane simply reads row[c - w], landing in the guard when c < w.  Heavier items
-// clamp each read index into the guard.
-// Where the row's byte offsets fit 16 bits the write-back uses
-// ds_write_addtid_b32 (address = M0 + immediate + 4 * lane), which ships no
-// address and runs at twice the rate of ds_write_b32; the reads are ordinary
-// loads, so the compiler tracks their completion itself.
-//
-// After the last item of a stage the same lanes trace the selection back
-// from (last offered item, C) through the keep words just written and mark
-// the chosen items, which the next stage then leaves out.
-#include <limits.h>
-#include <stdlib.h>
-
-#include <type_traits>
-
-
-#include "kernels.h"
+// Sequential mode with the capacity row resident in LDS: variant choice for the
+// create-time limits, and the launch of the kernels in seq_lds_kernel.h.
+#include "seq_lds_kernel.h"
 
 namespace deft {
-
-namespace {
-
-
-template <int T>
-__device__ __forceinline__ void lds_sync()
-{
-    if constexpr (T == 64) {
-        // one wavefront: LDS executes its instructions in order; only the
-        // compiler has to be kept from reordering
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-    } else {
-        // waits for LDS traffic only: keep-table stores stay in flight
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    }
-}
-
-// Makes what the lanes of the instance wrote to global memory (keep words, item
-// lists) visible to its other lanes.  All of them run on one compute unit, so
-// workgroup scope is enough: the stores have reached L2 when the wait ends, and the
-// readers go to L2 (scalar loads, and vector loads that bypass L1).  A wider scope
-// would write back and invalidate L2 at every call.
-template <int T>
-__device__ __forceinline__ void global_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if constexpr (T == 64) {
-        __builtin_amdgcn_wave_barrier();
-    } else {
-        __builtin_amdgcn_s_barrier();
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
-__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
-
-// bits = 2 * bits + (cand > own): compare into vcc, add-with-carry.
-__device__ __forceinline__ uint32_t shift_in_take(uint32_t bits, int cand, int own)
-{
-    uint32_t out;
-    asm("v_cmp_gt_i32 vcc, %2, %3\n\tv_addc_co_u32 %0, vcc, %1, %1, vcc"
-        : "=v"(out)
-        : "v"(bits), "v"(cand), "v"(own)
-        : "vcc");
-    return out;
-}
-
-typedef __attribute__((address_space(3))) int32_t lds_i32;
-// One offered item as the sweep and the traceback see it.
-struct __attribute__((aligned(16))) OfferedItem {
-    int32_t w, v, index, pad;
-};
-// Reads the first or second half of a list entry from L2, past the vector L1.  The
-// lists are written and read inside one launch, and the scalar cache is not a way
-// to read them: it can still hold a line from an earlier launch.
-__device__ __forceinline__ int2 load_item_wv(const OfferedItem *e)
-{
-    const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(e), __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-    return make_int2((int)(uint32_t)u, (int)(uint32_t)(u >> 32));
-}
-__device__ __forceinline__ int load_item_index(const OfferedItem *e)
-{
-    return __hip_atomic_load(&e->index, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// The same pointer in every lane of the wavefront: says so to the compiler, which then
-// keeps it in scalar registers and addresses memory as scalar base + lane offset.
-template <class P>
-__device__ __forceinline__ P *uniform_ptr(P *p)
-{
-    const uintptr_t v = (uintptr_t)p;
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    // rebuilt as a global-memory pointer, so that accesses stay global_* instructions
-    typedef P __attribute__((address_space(1))) GlobalP;
-    return (P *)(GlobalP *)(((uintptr_t)hi << 32) | lo);
-}
-__device__ __forceinline__ uint32_t lds_offset(int32_t *p)
-{
-    return (uint32_t)(uintptr_t)(lds_i32 *)p;
-}
-
-// LDS write addressed as M0 + OFF + 4 * lane.  M0 is an operand the compiler
-// materialises and keeps across consecutive statements that use the same value.
-// The hardware needs one wait state between a scalar write of M0 and an add-TID
-// access, which the compiler's hazard pass does not know to apply to inline asm:
-// m0_settle() supplies it and must precede the first add-TID access of a run.
-// The compiler does not track these accesses either, so a run ends with an
-// explicit s_waitcnt lgkmcnt(0) before the barrier that publishes it.
-template <int OFF>
-__device__ __forceinline__ void write_addtid(int m0, int d)
-{
-    asm volatile("ds_write_addtid_b32 %0 offset:%2" ::"v"(d), "{m0}"(m0), "n"(OFF) : "memory");
-}
-__device__ __forceinline__ void m0_settle(int m0) { asm volatile("s_nop 0" ::"{m0}"(m0) : "memory"); }
-// Calls f(integral_constant<int, k>) for k = K0 down to 0 (compile-time indices for
-// the immediate offsets of the add-TID writes).
-template <int K0>
-struct SlotsDown {
-    template <class F>
-    static __device__ __forceinline__ void all(F &&f)
-    {
-        f(std::integral_constant<int, K0>{});
-        if constexpr (K0 > 0) SlotsDown<K0 - 1>::all(f);
-    }
-};
-__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-// LDS of one instance: [8 ints of scratch][guard_cells - 8 ints of INT_MIN][row_cells].
-// The scratch words are the lowest cells of the guard zone; an item counts as light
-// only if it cannot reach them (w <= guard_cells - 8).
-struct LdsLayout {
-    int32_t guard_cells, row_cells, ints_per_inst;
-};
-constexpr int kMiscInts = 8;
-
-// All offered items of one stage, for a row of NB register slots per lane (NB is a
-// compile-time multiple of the chunk size, so the code is straight-line per item).
-// Slots 0 .. NB-1 cover cells 0 .. NB*T - 1 >= C; the cells above C are swept along and
-// never read back.
-template <int T, int NB, int NW, bool ADDTID, bool VEQW>
-__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
-                                            const OfferedItem *list, uint32_t *kp, unsigned long long &nzm)
-{
-    constexpr int D = NB < 12 ? NB : 12;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
-    const int wave_first = tid & ~63;     // first lane of this wavefront within the instance
-    // VEQW (every value equals its weight, the paper's Problem 1): the row is kept as
-    // row[c] - c, which turns row[c-w] + w into a plain copy of the shifted operand and
-    // saves the add; comparisons and hence take bits are unchanged.
-    // Each wavefront holds 64 list entries in two registers (lane l: entry 64 c + l) and
-    // fetches the next 64 while it works through these, so an item's weight and value are
-    // two lane reads and the sweep waits on vector memory once per 64 items.
-    const int lane = tid & 63;
-    auto load_chunk = [&](int first) {
-        return first + lane < nact ? load_item_wv(list + first + lane) : make_int2(0, 0);
-    };
-    int2 cur = load_chunk(0);
-    int own[NB];
-#pragma unroll
-    for (int k = 0; k < NB; ++k) {
-        own[k] = VEQW ? -(k * T + tid) : 0;
-        row[k * T + tid] = own[k];
-    }
-    lds_sync<T>();  // initial row visible to every lane
-
-    const int m0w = uniform((int)row_off + wave_first * 4);
-    // One item.  HEAVY is a compile-time flag and the two kinds run in separate loops
-    // below, so that the loop over the (common) light items has a single body and the
-    // compiler keeps every cell in one register across iterations.
-    auto item = [&](auto heavy_tag, int q, int w, int v) {
-        constexpr bool HEAVY = decltype(heavy_tag)::value;
-        uint32_t bits[NW];
-#pragma unroll
-        for (int x = 0; x < NW; ++x) bits[x] = 0;
-        int rd[NB];
-        auto update = [&](int k) {
-            const int cand = VEQW ? rd[k] : rd[k] + v;
-            bits[k >> 5] = shift_in_take(bits[k >> 5], cand, own[k]);  // slot k ends at bit k % 32
-            own[k] = max(own[k], cand);
-        };
-        const int idx = tid - w;
-        const int32_t *src = row + idx;
-        // light item: every lane reads row[c - w]; c < w lands in the guard.  Heavy item
-        // (rare): each lane clamps its read index into the guard, so cells below w read
-        // INT_MIN wherever they are.
-        auto read = [&](int k) { return HEAVY ? row[max(idx + k * T, -1)] : src[k * T]; };
-        // The order of phase A is pinned: D slots of reads up front, then two slots of
-        // arithmetic for every two further reads.
-#pragma unroll
-        for (int k = NB - 1; k >= NB - D; --k) rd[k] = read(k);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int k = NB - 1; k >= 0; k -= 2) {
-            update(k);
-            if (k >= 1) update(k - 1);
-            if (k - D >= 0) rd[k - D] = read(k - D);
-            if (k - D - 1 >= 0) rd[k - D - 1] = read(k - D - 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        lds_sync<T>();  // every lane has read the old row
-
-        if constexpr (ADDTID) {
-            m0_settle(m0w);
-            SlotsDown<NB - 1>::all([&](auto kc) { write_addtid<kc.value * T * 4>(m0w, own[kc.value]); });
-        } else {
-#pragma unroll
-            for (int k = NB - 1; k >= 0; --k) row[k * T + tid] = own[k];
-        }
-        // Row q of the keep table belongs to the q-th offered item.  A wavefront whose 64
-        // lanes took nothing writes nothing and notes that in nzm: bit (q % 64) of lane
-        // (q / 64) says whether this wavefront's part of row q exists.
-        uint32_t any_bits = bits[0];
-#pragma unroll
-        for (int x = 1; x < NW; ++x) any_bits |= bits[x];
-        const bool nz = __builtin_amdgcn_ballot_w64(any_bits != 0) != 0ull;
-        if (nz) {
-#pragma unroll
-            for (int x = 0; x < NW; ++x) kp[((size_t)q * NW + x) * T + tid] = bits[x];
-        }
-        if ((tid & 63) == (q >> 6)) nzm |= (unsigned long long)nz << (q & 63);
-        if constexpr (ADDTID) wait_lds();
-        lds_sync<T>();  // the new row is visible
-    };
-
-    for (int q0 = 0; q0 < nact; q0 += 64) {
-        const int2 nxt = load_chunk(q0 + 64);
-        const int q1 = min(q0 + 64, nact);
-        int q = q0;
-        while (q < q1) {
-            int w = __builtin_amdgcn_readlane(cur.x, q & 63);
-            while (w <= light_max) {  // run of light items
-                item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (++q >= q1) break;
-                w = __builtin_amdgcn_readlane(cur.x, q & 63);
-            }
-            if (q < q1) {  // one heavy item
-                item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                ++q;
-            }
-        }
-        cur = nxt;
-    }
-}
-
-// Picks the sweep_stage instance for the stage's chunk count (1 .. N).
-template <int T, int G, int NW, bool ADDTID, bool VEQW, int N>
-__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
-                                               int nact, const OfferedItem *list, uint32_t *kp,
-                                               unsigned long long &nzm)
-{
-    if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID, VEQW>(row, row_off, light_max, tid, nact, list, kp, nzm);
-    } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, VEQW, N - 1>(nchunk, row, row_off, light_max, tid, nact, list, kp, nzm);
-    }
-}
-
-// WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
-template <int T, int K, int G, int WPE>
-__global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
-seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, OfferedItem *lists,
-               int list_stride)
-{
-    extern __shared__ __align__(16) int32_t lds_raw[];
-    static_assert(K <= 64, "at most 64 segments per wavefront");
-    constexpr int NW = (K + 31) / 32;
-    static_assert(K % G == 0, "whole chunks");
-    constexpr bool ADDTID = K * T * 4 <= 65536;  // row offsets fit the 16-bit immediate
-    constexpr int NCH = (K + G - 1) / G;
-    constexpr int LOG_T = (T == 64) ? 6 : (T == 256) ? 8 : (T == 512) ? 9 : 10;
-    static_assert((1 << LOG_T) == T, "T must be 64, 256, 512 or 1024");
-
-    const int sub = (T == 64) ? (int)(threadIdx.x >> 6) : 0;
-    const int tid = (T == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
-    const int inst = (T == 64) ? (int)blockIdx.x * 4 + sub : (int)blockIdx.x;
-    if (inst >= a.batch) return;  // whole wavefront (T == 64) or never (grid == batch)
-
-    int32_t *misc = lds_raw + (size_t)sub * lay.ints_per_inst;
-    int32_t *row = misc + lay.guard_cells;
-    const uint32_t row_off = lds_offset(row);
-    // misc: [0] fault flags (bit 2: some value differs from its weight), [1] offered-item count,
-    //       [2..3] value sum, [4..5] fill-order seen mask
-
-    const int n = a.n_items[inst];
-    const int m = a.n_knapsacks[inst];
-    const int32_t *__restrict__ W = a.weights + (size_t)inst * a.item_stride;
-    const int32_t *__restrict__ V = a.values + (size_t)inst * a.item_stride;
-    const int32_t *__restrict__ cap = a.capacities + (size_t)inst * a.knap_stride;
-    const int32_t *__restrict__ ord =
-        a.fill_order ? a.fill_order + (size_t)inst * a.knap_stride : nullptr;
-    int32_t *out_asg = a.assignment + (size_t)inst * a.item_stride;
-    int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
-    int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
-    uint32_t *kp = uniform_ptr(keep + (size_t)inst * keep_words_per_inst);
-    // one item list per stage
-    OfferedItem *inst_lists = uniform_ptr(lists + (size_t)inst * a.knap_stride * list_stride);
-
-    // ---- per-instance validation -------------------------------------------
-    if (tid < kMiscInts) misc[tid] = 0;
-    for (int i = kMiscInts + tid; i < lay.guard_cells; i += T) misc[i] = INT_MIN;
-    lds_sync<T>();
-    {
-        uint32_t flags = 0;
-        unsigned long long vs = 0;
-        const bool counts_ok = n >= 0 && n <= a.item_stride && m >= 0 && m <= a.knap_stride;
-        if (!counts_ok) {
-            flags = 1;
-        } else {
-            for (int i = tid; i < n; i += T) {
-                const int w = W[i], v = V[i];
-                if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
-                if (v != w) flags |= 4;
-            }
-            for (int j = tid; j < m; j += T) {
-                const int c = cap[j];
-                if (c < 0) flags |= 1; else if (c > a.max_capacity) flags |= 2;
-                if (ord) {
-                    const int o = ord[j];
-                    if (o < 0 || o >= m) {
-                        flags |= 1;
-                    } else {
-                        const uint32_t bit = 1u << (o & 31);
-                        const uint32_t old = atomicOr(reinterpret_cast<uint32_t *>(&misc[4 + (o >> 5)]), bit);
-                        if (old & bit) flags |= 1;
-                    }
-                }
-            }
-        }
-        if (flags) atomicOr(reinterpret_cast<uint32_t *>(&misc[0]), flags);
-        if (vs) atomicAdd(reinterpret_cast<unsigned long long *>(&misc[2]), vs);
-    }
-    lds_sync<T>();
-    int status = DEFT_OK;
-    const bool veqw = uniform(misc[0] & 4) == 0;
-    {
-        const uint32_t flags = (uint32_t)misc[0];
-        const unsigned long long vs = *reinterpret_cast<unsigned long long *>(&misc[2]);
-        if (flags & 1) status = DEFT_ERR_INVALID_ARG;
-        else if (flags & 2) status = DEFT_ERR_LIMIT;
-        else if (vs >= (1ull << 31)) status = DEFT_ERR_OVERFLOW;
-    }
-    status = uniform(status);
-    if (tid == 0) {
-        for (int j = 0; j < a.knap_stride; ++j) { out_kv[j] = 0; out_kl[j] = 0; }
-        a.status[inst] = status;
-    }
-    for (int i = tid; i < a.item_stride; i += T) out_asg[i] = -1;
-    if (status != DEFT_OK) {
-        if (tid == 0) a.total_value[inst] = 0;
-        return;
-    }
-
-    // ---- stages ----------------------------------------------------------------
-    // Items already placed: bit (i / 64) of lane (i % 64) of the first wavefront.
-    unsigned long long placed = 0;
-    long long total = 0;
-    for (int s = 0; s < m; ++s) {
-        const int j = uniform(ord ? ord[s] : s);
-        const int C = uniform(cap[j]);
-        OfferedItem *list = inst_lists + (size_t)s * list_stride;
-
-        // offered items: not yet placed and able to fit at all, ascending index
-        if (tid < 64) {
-            int cnt = 0;
-            for (int i0 = 0; i0 < n; i0 += 64) {
-                const int i = i0 + tid;
-                const int w = i < n ? W[i] : 0;
-                const int v = i < n ? V[i] : 0;
-                const bool f = i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C;
-                const unsigned long long mask = __ballot(f);
-                if (f) {
-                    OfferedItem e;
-                    e.w = w; e.v = v; e.index = i; e.pad = 0;
-                    list[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = e;
-                }
-                cnt += __popcll(mask);
-            }
-            if (tid == 0) misc[1] = cnt;
-        }
-
-        const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
-        global_sync<T>();  // the list (global memory) and the count (LDS) are visible
-        const int nact = min(uniform(misc[1]), list_stride);
-        unsigned long long nzm = 0;
-        if (veqw)
-            sweep_dispatch<T, G, NW, ADDTID, true, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid, nact,
-                                                        list, kp, nzm);
-        else
-            sweep_dispatch<T, G, NW, ADDTID, false, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid, nact,
-                                                         list, kp, nzm);
-
-        const int value = uniform(row[C]) + (veqw ? C : 0);
-
-        // ---- traceback ------------------------------------------------------------
-        // The row is dead now; its LDS holds what the walk needs: weight and index of
-        // every offered item and, per wavefront, which keep-row parts exist.
-        lds_sync<T>();  // every lane has read row[C]
-        int32_t *tb_w = row, *tb_index = row + list_stride;
-        unsigned long long *tb_nz = reinterpret_cast<unsigned long long *>(row + 2 * list_stride);
-        for (int i = tid; i < nact; i += T) {
-            tb_w[i] = load_item_wv(list + i).x;
-            tb_index[i] = load_item_index(list + i);
-        }
-        tb_nz[tid] = nzm;  // wavefront x, lane l: rows 64 l .. 64 l + 63
-        global_sync<T>();  // keep words (global memory) and the staged data (LDS) are visible
-
-        // One wavefront walks the keep words back from (last offered item, C).  The
-        // walk is a chain of dependent loads, so six steps are taken per memory round
-        // trip: lane L in [2^d, 2^(d+1)) assumes the decisions spelled by the bits of
-        // L below its leading one for the items q .. q-d+1 (most significant first)
-        // and fetches the keep bit of item q-d at the capacity those decisions leave;
-        // a ballot then gives all 63 answers and the true path is read off it.  A lane
-        // whose keep-row part was never written knows its answer (not taken) without a
-        // load, so rounds through all-zero rows cost no memory round trip.
-        if (tid < 64) {
-            const int L = tid;
-            const int d = 31 - __clz(L | 1);
-            const int p = L - (1 << d);
-            // Every index is range-checked before it is used; a violation (never expected)
-            // marks the instance DEFT_ERR_DEVICE instead of touching memory.
-            bool broken = false;
-            int c = C;
-            int q = nact - 1;
-            unsigned long long chosen = 0;  // items this stage places, laid out like `placed`
-            while (q >= 0) {
-                int wv[6], tv[6];
-                {
-                    const bool have = L < 6 && q - L >= 0;
-                    int w_l = 0, t_l = 0;
-                    if (have) {
-                        w_l = tb_w[q - L];
-                        t_l = tb_index[q - L];
-                        if (t_l < 0 || t_l >= n) { broken = true; t_l = 0; }
-                    }
-#pragma unroll
-                    for (int i = 0; i < 6; ++i) {
-                        tv[i] = __builtin_amdgcn_readlane(t_l, i);
-                        wv[i] = __builtin_amdgcn_readlane(w_l, i);
-                    }
-                }
-                int cl = c, wd = wv[0];
-#pragma unroll
-                for (int i = 0; i < 5; ++i) {
-                    if (i < d && ((p >> (d - 1 - i)) & 1)) cl -= wv[i];
-                    if (d == i + 1) wd = wv[i + 1];
-                }
-                uint32_t bit = 0;
-                // lane L tests offered item q-d; items past the head of the list (q-d < 0) carry
-                // w = 0 and are excluded here, so cl never leaves [-5*C, C]
-                if (L >= 1 && q - d >= 0 && cl >= 0 && wd <= cl) {
-                    const int k = cl >> LOG_T, lane = cl & (T - 1), qd = q - d;
-                    if (k < K && cl <= C) {
-                        const unsigned long long nzw = tb_nz[(lane >> 6) * 64 + (qd >> 6)];
-                        if ((nzw >> (qd & 63)) & 1ull) {
-                            const uint32_t word = __hip_atomic_load(&kp[((size_t)qd * NW + (k >> 5)) * T + lane],
-                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            bit = (word >> (k & 31)) & 1u;
-                        }
-                    } else {
-                        broken = true;
-                    }
-                }
-                const unsigned long long takes = __ballot(bit != 0);
-                int node = 1;
-#pragma unroll
-                for (int i = 0; i < 6; ++i) {
-                    const int b = (int)((takes >> node) & 1ull);
-                    if (b) {
-                        const int t = tv[i];  // uniform
-                        if (L == (t & 63)) chosen |= 1ull << (t >> 6);
-                        c -= wv[i];
-                    }
-                    node = 2 * node + b;
-                }
-                q -= 6;
-            }
-            placed |= chosen;
-            while (chosen) {  // outside the walk: no store sits in its chain of loads
-                const int b = __builtin_ctzll(chosen);
-                chosen &= chosen - 1;
-                out_asg[b * 64 + L] = j;
-            }
-            if (L == 0) {
-                out_kv[j] = value;
-                out_kl[j] = C - c;
-            }
-            if (__ballot(broken) != 0ull && L == 0) a.status[inst] = DEFT_ERR_DEVICE;
-        }
-        total += value;
-        lds_sync<T>();
-    }
-
-    if (tid == 0) a.total_value[inst] = total;
-}
-
-struct Variant {
-    int threads, cells, chunk;
-    int guard;  // cells below the row (8 scratch words + INT_MIN); items up to guard - 8 take the light path
-    const void *fn;
-};
-
-#define DEFT_VARIANT(T, K, G, WPE, GUARD) { T, K, G, GUARD, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, G, WPE>) }
-const Variant kVariants[] = {
-    DEFT_VARIANT(64, 16, 4, 5, 256),    // capacity <= 1023: one wavefront per instance, four per workgroup
-    DEFT_VARIANT(256, 16, 4, 7, 256),   // <= 4095
-    DEFT_VARIANT(256, 32, 4, 4, 256),   // <= 8191
-    DEFT_VARIANT(512, 20, 1, 8, 128),   // <= 10239: four workgroups per CU when the row stays under 40 KB
-    DEFT_VARIANT(512, 26, 1, 6, 128),   // <= 13311: with the 128-cell guard three workgroups share a CU's LDS
-    DEFT_VARIANT(512, 51, 3, 2, 256),   // <= 26111
-    DEFT_VARIANT(1024, 40, 4, 4, 256),  // <= 40959 (if LDS allows)
-};
-#undef DEFT_VARIANT
-constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-
-template <int T, int K, int G, int WPE>
-hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
-{
-    const LdsLayout lay{p.guard_cells, p.row_cells, p.lds_bytes / p.inst_per_wg / 4};
-    const unsigned grid = (unsigned)((a.batch + p.inst_per_wg - 1) / p.inst_per_wg);
-    uint32_t *keep = static_cast<uint32_t *>(scratch);
-    OfferedItem *lists = reinterpret_cast<OfferedItem *>(static_cast<char *>(scratch) + p.keep_bytes);
-    hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
-                       a, lay, keep, p.keep_words_per_inst, lists, p.n_pad);
-    return hipGetLastError();
-}
-
-}  // namespace
 
 // LDS is handed out in granules of 1280 bytes, 128 of them per compute unit (measured:
 // three 53760-byte workgroups run together on a CU, three 54016-byte ones do not, whatever
@@ -562,7 +17,7 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
     if (const char *e = getenv("DEFT_SEQ_VARIANT")) only = atoi(e);  // tuning aid: force a table entry
     for (int i = 0; i < kNumVariants; ++i) {
         if (only >= 0 && i != only) continue;
-        const Variant &v = kVariants[i];
+        const Variant &v = variant_table<false>()[i];
         const int guard = v.guard;
         // register slots needed by lane 0, rounded up to whole chunks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
@@ -596,11 +51,8 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
 
 hipError_t seq_lds_prepare(SeqLdsPlan *plan)
 {
-    const void *fn = kVariants[plan->variant].fn;
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, plan->lds_bytes);
-    if (e != hipSuccess) return e;
     int nb = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, plan->wg_threads, (size_t)plan->lds_bytes);
+    const hipError_t e = prepare_variant<false>(*plan, &nb);
     if (e != hipSuccess) return e;
     const int by_lds = kLdsGranulesPerCu / ((plan->lds_bytes + kLdsGranule - 1) / kLdsGranule);
     plan->wg_per_cu = nb < by_lds ? nb : by_lds;
@@ -609,16 +61,7 @@ hipError_t seq_lds_prepare(SeqLdsPlan *plan)
 
 hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
 {
-    switch (p.variant) {
-    case 0: return launch_one<64, 16, 4, 5>(p, a, scratch, st);
-    case 1: return launch_one<256, 16, 4, 7>(p, a, scratch, st);
-    case 2: return launch_one<256, 32, 4, 4>(p, a, scratch, st);
-    case 3: return launch_one<512, 20, 1, 8>(p, a, scratch, st);
-    case 4: return launch_one<512, 26, 1, 6>(p, a, scratch, st);
-    case 5: return launch_one<512, 51, 3, 2>(p, a, scratch, st);
-    case 6: return launch_one<1024, 40, 4, 4>(p, a, scratch, st);
-    default: return hipErrorInvalidValue;
-    }
+    return launch_variant<false>(p, a, scratch, st);
 }
 
 }  // namespace deft

@@ -1,0 +1,21 @@
+// Algorithm 1 (RecursiveKnapsack) on the LDS-resident row: the kernels of
+// seq_lds_kernel.h instantiated with REC = true, under the plan made for the
+// sequential mode (same variants, same scratch).
+#include "seq_lds_kernel.h"
+
+namespace deft {
+
+hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan)
+{
+    int nb = 0;
+    const hipError_t e = prepare_variant<true>(plan, &nb);
+    if (e != hipSuccess) return e;
+    return nb > 0 ? hipSuccess : hipErrorInvalidConfiguration;
+}
+
+hipError_t seq_lds_rec_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
+{
+    return launch_variant<true>(p, a, scratch, st);
+}
+
+}  // namespace deft

@@ -39,7 +39,7 @@ def test_binding_struct_layouts_match_header():
     assert ctypes.sizeof(b.deft_knapsack_config_t) == 8 * 4
     assert [f[0] for f in b.deft_knapsack_config_t._fields_] == [
         "device", "max_batch", "max_items", "max_knapsacks", "max_capacity", "max_c1", "max_c2", "flags"]
-    assert ctypes.sizeof(b.deft_knapsack_batch_t) == 4 * 4 + 12 * 8
+    assert ctypes.sizeof(b.deft_knapsack_batch_t) == 4 * 4 + 13 * 8
     hdr = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
     body = re.search(r"typedef struct \{([^}]*)\} deft_knapsack_batch_t;", hdr).group(1)
     fields = re.findall(r"\**\s*([a-z_0-9]+)\s*;", body)

@@ -1,9 +1,10 @@
 """Host-side check of the generated gfx950 code for one hardware rule the compiler does
 not apply to inline asm: between a scalar write of M0 and an add-TID LDS access
 (ds_read_addtid_b32 / ds_write_addtid_b32) there must be at least one other instruction.
-seq_lds.hip relies on the compiler to place and merge the M0 writes ("{m0}" operands) and
+seq_lds_kernel.h relies on the compiler to place and merge the M0 writes ("{m0}" operands) and
 on m0_settle() to supply the wait state; this test compiles the file to assembly and
-verifies that every run of add-TID accesses is so protected.  No GPU needed."""
+verifies that every run of add-TID accesses is so protected, in both files that
+instantiate the kernels.  No GPU needed."""
 import os
 import re
 import subprocess
@@ -12,7 +13,7 @@ import tempfile
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SRC = os.path.join(ROOT, "paper_2503_16815_amd", "csrc", "seq_lds.hip")
+SRCS = [os.path.join(ROOT, "paper_2503_16815_amd", "csrc", f) for f in ("seq_lds.hip", "seq_lds_rec.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 M0_WRITE = re.compile(r"^\s*s_\w+\s+m0\s*,")          # any scalar instruction whose destination is m0
@@ -32,20 +33,27 @@ def instructions(asm_text):
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
 def test_m0_write_is_never_directly_followed_by_an_addtid_access():
     with tempfile.TemporaryDirectory() as tmp:
-        out = os.path.join(tmp, "seq_lds.s")
-        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fno-gpu-rdc", "-Xclang", "-target-feature",
-               "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
-               "--cuda-device-only", "-S", "-o", out, SRC]
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        assert res.returncode == 0, res.stderr[-2000:]
-        text = open(out).read()
-    prev = None
-    n_addtid = n_m0 = 0
-    for ins in instructions(text):
-        if ADDTID.match(ins):
-            n_addtid += 1
-            assert prev is None or not M0_WRITE.match(prev), f"add-TID access right after an M0 write: {prev!r} -> {ins!r}"
-        if M0_WRITE.match(ins):
-            n_m0 += 1
-        prev = ins
-    assert n_addtid > 100 and n_m0 > 0, (n_addtid, n_m0)   # the file really uses them
+        jobs = []
+        for src in SRCS:   # both compilations at once
+            out = os.path.join(tmp, os.path.basename(src) + ".s")
+            cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fno-gpu-rdc", "-Xclang", "-target-feature",
+                   "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
+                   "--cuda-device-only", "-S", "-o", out, src]
+            jobs.append((out, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)))
+        texts = []
+        for out, proc in jobs:
+            _, err = proc.communicate()
+            assert proc.returncode == 0, err[-2000:]
+            texts.append(open(out).read())
+    for text in texts:
+        prev = None
+        n_addtid = n_m0 = 0
+        for ins in instructions(text):
+            if ADDTID.match(ins):
+                n_addtid += 1
+                assert prev is None or not M0_WRITE.match(prev), \
+                    f"add-TID access right after an M0 write: {prev!r} -> {ins!r}"
+            if M0_WRITE.match(ins):
+                n_m0 += 1
+            prev = ins
+        assert n_addtid > 100 and n_m0 > 0, (n_addtid, n_m0)   # the file really uses them
