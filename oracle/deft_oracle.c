@@ -30,13 +30,17 @@
  *   - joint DP: per item the order of tests is skip, link 0, link 1, each
  *     replacing the incumbent only if strictly greater.
  *   - values and weights are separate arrays (value == weight is Problem 1).
+ *   - Algorithm 1: the time taken off when an item leaves the list is an input
+ *     per item; a list met with a negative remaining time schedules nothing;
+ *     the sums compared are the values.
  *
  * Arithmetic: int64 accumulators; inputs int32.  No blocking, no bit packing:
  * the keep table is one byte per (item, capacity cell).
  *
  * Pins: tests/test_oracle_*.py (brute force over all 2^n / 3^n selections,
  * the bitset subset-sum recurrence, closed forms, invariants, the Table II
- * bucket times as a worked vector).
+ * bucket times as a worked vector; for Algorithm 1: enumeration of every
+ * level and subset, reductions to Problem 1, a case worked by hand).
  */
 #include <pthread.h>
 #include <stdint.h>
