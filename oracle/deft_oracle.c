@@ -22,6 +22,10 @@
  *     list with the remaining time, against the same procedure on the list
  *     without its last item and with that item's time taken off the remaining
  *     time; the shallower answer wins only if its sum is strictly greater.
+ *   - Section III.C, the greedy heuristic of the paper's own Solver: capacities
+ *     and bucket times are sorted, then the knapsacks are gone through from the
+ *     smallest capacity up and each takes, longest bucket first, whatever still
+ *     fits.
  *
  * Conventions the paper leaves open, fixed here:
  *   - an item is taken at capacity c only if it strictly improves the value;
@@ -30,6 +34,9 @@
  *   - joint DP: per item the order of tests is skip, link 0, link 1, each
  *     replacing the incumbent only if strictly greater.
  *   - values and weights are separate arrays (value == weight is Problem 1).
+ *   - greedy heuristic: both sorts are stable (equal capacities: lower knapsack
+ *     id first; equal times: lower item index first); with one time per link,
+ *     each link goes through the items in the order of its own times.
  *   - Algorithm 1: the time taken off when an item leaves the list is an input
  *     per item; a list met with a negative remaining time schedules nothing;
  *     the sums compared are the values.
@@ -320,6 +327,80 @@ int deft_oracle_recursive(int32_t n, int32_t item_stride, const int32_t *w, cons
     return ST_OK;
 }
 
+/*
+ * The greedy heuristic of Section III.C for one instance.
+ * per_link = 0: one time per item (w[0..n)), m knapsacks.
+ * per_link = 1: the two-link layout, w[j * item_stride + i] = time of item i on link j,
+ *               m must be 2; link j looks at the items in the order of its own times.
+ * Step 1: knapsack ids sorted by capacity, ascending, stable.
+ * Step 2: item indices sorted by time, descending, stable.
+ * Step 3: for each knapsack in step 1's order, for each item in step 2's order:
+ *         an item not placed yet whose time fits what is left of the knapsack is placed.
+ */
+static void stable_sort_ids(int count, int32_t *ids, const int32_t *key, int descending)
+{
+    for (int a = 1; a < count; ++a) {          /* insertion sort: stable, plain */
+        int32_t id = ids[a];
+        int b = a - 1;
+        while (b >= 0 && (descending ? key[ids[b]] < key[id] : key[ids[b]] > key[id])) {
+            ids[b + 1] = ids[b];
+            --b;
+        }
+        ids[b + 1] = id;
+    }
+}
+
+int deft_oracle_greedy(int32_t n, int32_t item_stride, const int32_t *w, int per_link, const int32_t *v,
+                       int32_t m, int32_t knap_stride, const int32_t *cap, int32_t cap_limit,
+                       int32_t c1_limit, int32_t c2_limit, int64_t *total, int32_t *knap_value,
+                       int32_t *knap_load, int32_t *assign)
+{
+    clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+    if (n < 0 || n > item_stride || m < 0 || m > knap_stride) return ST_INVALID;
+    if (per_link && (m != 2 || knap_stride < 2)) return ST_INVALID;
+    for (int i = 0; i < n; ++i)
+        if (w[i] < 1 || v[i] < 0 || (per_link && w[item_stride + i] < 1)) return ST_INVALID;
+    for (int j = 0; j < m; ++j)
+        if (cap[j] < 0) return ST_INVALID;
+    for (int j = 0; j < m; ++j) {
+        int32_t lim = per_link ? (j == 0 ? c1_limit : c2_limit) : cap_limit;
+        if (lim >= 0 && cap[j] > lim) return ST_LIMIT;
+    }
+    int64_t vsum = 0;
+    for (int i = 0; i < n; ++i) vsum += v[i];
+    if (vsum >= VALUE_SUM_LIMIT) return ST_OVERFLOW;
+
+    int32_t *knaps = (int32_t *)malloc(sizeof(int32_t) * (size_t)(m > 0 ? m : 1));
+    int32_t *items = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    if (!knaps || !items) { free(knaps); free(items); return ST_OOM; }
+    for (int j = 0; j < m; ++j) knaps[j] = j;
+    stable_sort_ids(m, knaps, cap, 0);
+    for (int s = 0; s < m; ++s) {
+        int j = knaps[s];
+        const int32_t *time = per_link ? w + (size_t)j * item_stride : w;
+        if (s == 0 || per_link) {                /* one sort serves every knapsack unless times differ per link */
+            for (int i = 0; i < n; ++i) items[i] = i;
+            stable_sort_ids(n, items, time, 1);
+        }
+        int64_t left = cap[j], load = 0, value = 0;
+        for (int t = 0; t < n; ++t) {
+            int i = items[t];
+            if (assign[i] == -1 && time[i] <= left) {
+                assign[i] = j;
+                left -= time[i];
+                load += time[i];
+                value += v[i];
+            }
+        }
+        knap_load[j] = (int32_t)load;
+        knap_value[j] = (int32_t)value;
+        *total += value;
+    }
+    free(knaps);
+    free(items);
+    return ST_OK;
+}
+
 /* ---- batch driver: instances split statically over nthreads ------------- */
 
 typedef struct {
@@ -351,6 +432,12 @@ static void solve_one(const batch_args_t *a, int b)
                                    a->capacities + b * ks, a->cap_limit, a->total + b,
                                    a->knap_value + b * ks, a->knap_load + b * ks, a->assign + b * is,
                                    &touched, &table);
+    } else if (a->mode == 3 || a->mode == 4) {
+        int per_link = a->mode == 4;
+        st = deft_oracle_greedy(a->n_items[b], a->item_stride, a->weights + b * (per_link ? 2 : 1) * is, per_link,
+                                a->values + b * is, a->n_knapsacks[b], a->knap_stride, a->capacities + b * ks,
+                                a->cap_limit, a->c1_limit, a->c2_limit, a->total + b, a->knap_value + b * ks,
+                                a->knap_load + b * ks, a->assign + b * is);
     } else {
         st = deft_oracle_joint2(a->n_items[b], a->item_stride, a->weights + b * 2 * is,
                                 a->weights + b * 2 * is + is, a->values + b * is,
@@ -381,7 +468,7 @@ int deft_oracle_solve_batch(int32_t mode, int32_t batch, int32_t item_stride, in
                             int32_t *assign, int32_t *status, int64_t *touched, int64_t *table,
                             int32_t nthreads)
 {
-    if (mode < 0 || mode > 2 || (mode == 2 && !drop_time) || batch < 0 || item_stride < 0 || knap_stride < 0)
+    if (mode < 0 || mode > 4 || (mode == 2 && !drop_time) || batch < 0 || item_stride < 0 || knap_stride < 0)
         return -1;
     batch_args_t a = { mode, batch, item_stride, knap_stride, n_items, n_knapsacks, weights,
                        values, capacities, fill_order, drop_time, cap_limit, c1_limit, c2_limit, total,

@@ -79,7 +79,7 @@ def solve_batch(kb, cap_limit: int = -1, c1_limit: int = -1, c2_limit: int = -1,
     assert kb.mode != 2 or (dt is not None and dt.shape == (B, IS))
     assert n_items.shape == (B,) and n_knap.shape == (B,)
     assert v.shape == (B, IS) and cap.shape == (B, KS)
-    assert w.shape == ((B, 2, IS) if kb.mode == 1 else (B, IS))
+    assert w.shape == ((B, 2, IS) if kb.mode in (1, 4) else (B, IS))
     total = np.zeros(B, np.int64)
     kv = np.zeros((B, KS), np.int32)
     kl = np.zeros((B, KS), np.int32)

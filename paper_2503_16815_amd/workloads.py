@@ -33,6 +33,8 @@ import numpy as np
 MODE_SEQUENTIAL = 0
 MODE_JOINT2 = 1
 MODE_RECURSIVE = 2
+MODE_GREEDY = 3       # the paper's greedy heuristic on the sequential layout
+MODE_GREEDY2 = 4      # the same on the two-link layout (one time per link)
 
 SEED_TINY = 1001
 SEED_RESNET = 1002
@@ -290,3 +292,14 @@ def backward_stage_shaped(batch: int = 1024, n: int = 314, seed: int = SEED_RESN
         name="backward_stage", mode=MODE_RECURSIVE, batch=batch, item_stride=n, knap_stride=2,
         n_items=_i32(np.full(batch, n)), n_knapsacks=_i32(np.full(batch, 1)), weights=_i32(w), values=_i32(w.copy()),
         capacities=_i32(cap), meta={"seed": seed}, drop_time=_i32(drop))
+
+
+def as_greedy(kb: KnapsackBatch) -> KnapsackBatch:
+    """The same instances, to be solved by the greedy heuristic of Section III.C
+    (sequential layout -> MODE_GREEDY, two-link layout -> MODE_GREEDY2)."""
+    assert kb.mode in (MODE_SEQUENTIAL, MODE_JOINT2)
+    g = kb.slice(0, kb.batch)
+    g.name = kb.name + "_greedy"
+    g.mode = MODE_GREEDY if kb.mode == MODE_SEQUENTIAL else MODE_GREEDY2
+    g.fill_order = None
+    return g
