@@ -36,7 +36,9 @@ typedef enum {
 enum {
     DEFT_MODE_SEQUENTIAL = 0, /* m knapsacks filled one after the other (Sec. III.B)       */
     DEFT_MODE_JOINT2 = 1,     /* two links, one joint 2-D DP (Sec. III.C, Problem 2)       */
-    DEFT_MODE_RECURSIVE = 2   /* one window, the list shortened from its end (Algorithm 1) */
+    DEFT_MODE_RECURSIVE = 2,  /* one window, the list shortened from its end (Algorithm 1) */
+    DEFT_MODE_GREEDY = 3,     /* the paper's greedy heuristic, SEQUENTIAL layout (Sec. III.C)   */
+    DEFT_MODE_GREEDY2 = 4     /* the same on the JOINT2 layout (one time per link)              */
 };
 
 /* Limits fixed at create time; they size the scratch memory and select the
@@ -98,11 +100,22 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *   fill_order is ignored.  Only handles whose max_capacity fits the LDS-resident row
  *   (seq_path 1 or 2) serve this mode; others return LIMIT from the call.
  *
+ * DEFT_MODE_GREEDY / DEFT_MODE_GREEDY2 (Sec. III.C, the heuristic of the paper's Solver;
+ * here so that the exact modes can be compared with it on the same inputs):
+ *   knapsacks sorted by capacity, ascending (equal capacities: lower id first); items
+ *   sorted by weight (the bucket's time), descending (equal weights: lower index first);
+ *   each knapsack in that order goes through the items in that order and takes every
+ *   item not placed yet that fits what is left of it.  Values only add up; they play no
+ *   part in the order.  GREEDY takes the SEQUENTIAL layout (fill_order ignored), GREEDY2
+ *   the JOINT2 layout (n_knapsacks must be 2; link j goes through the items in the order
+ *   of its own weights).  Outputs as in SEQUENTIAL.  Served by any handle whose limits
+ *   cover the layout (max_capacity > 0, or max_c1 / max_c2 > 0).
+ *
  * Layout (row-major, device memory):
  *   n_items     [batch]                      0 <= n_items[b] <= item_stride
  *   n_knapsacks [batch]                      0 <= n_knapsacks[b] <= knap_stride
- *   weights     SEQUENTIAL [batch][item_stride]      each >= 1
- *               JOINT2     [batch][2][item_stride]   row 0 = link 0, row 1 = link 1
+ *   weights     SEQUENTIAL, RECURSIVE, GREEDY [batch][item_stride]   each >= 1
+ *               JOINT2, GREEDY2 [batch][2][item_stride]   row 0 = link 0, row 1 = link 1
  *   values      [batch][item_stride]         each >= 0, sum per instance < 2^31
  *   capacities  [batch][knap_stride]         indexed by knapsack id, each >= 0
  *   fill_order  [batch][knap_stride] or NULL a permutation of 0..n_knapsacks[b]-1

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DEFT_KNAPSACK_LIB") or os.path.join(_HERE, "libdeft_knapsack.so")
 
 DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, DEFT_ERR_DEVICE = range(6)
-DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2, DEFT_MODE_RECURSIVE = 0, 1, 2
+DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2, DEFT_MODE_RECURSIVE, DEFT_MODE_GREEDY, DEFT_MODE_GREEDY2 = range(5)
 
 EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_destroy",
            "deft_knapsack_get_info", "deft_knapsack_set_profiling", "deft_knapsack_get_profile",
@@ -202,7 +202,7 @@ class DeftKnapsack:
 
 def solve(kb, device: int = 0, **limits) -> SolveOutputs:
     """Convenience: create a handle sized for `kb`, solve, synchronise, destroy."""
-    seq = kb.mode != DEFT_MODE_JOINT2
+    seq = kb.mode not in (DEFT_MODE_JOINT2, DEFT_MODE_GREEDY2)
     cap = int(kb.capacities.max()) if kb.capacities.size else 1
     args = dict(max_batch=max(1, kb.batch), max_items=kb.item_stride, max_knapsacks=kb.knap_stride,
                 max_capacity=max(1, cap) if seq else 0,

@@ -166,6 +166,10 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
             st = alloc(&h->joint_scratch, h->joint_plan.scratch_bytes, &h->scratch_bytes);
         }
     }
+    if (st == DEFT_OK && greedy_prepare(cfg->max_items) != hipSuccess) {
+        (void)hipGetLastError();
+        st = DEFT_ERR_DEVICE;
+    }
     if (st != DEFT_OK) {
         free_handle(h);
         return st;
@@ -177,10 +181,10 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
 extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *b)
 {
     if (!h || !b) return DEFT_ERR_INVALID_ARG;
-    if (b->mode != DEFT_MODE_SEQUENTIAL && b->mode != DEFT_MODE_JOINT2 && b->mode != DEFT_MODE_RECURSIVE)
-        return DEFT_ERR_INVALID_ARG;
+    if (b->mode < DEFT_MODE_SEQUENTIAL || b->mode > DEFT_MODE_GREEDY2) return DEFT_ERR_INVALID_ARG;
     if (b->batch < 0 || b->item_stride < 1 || b->knap_stride < 1) return DEFT_ERR_INVALID_ARG;
-    if (b->mode != DEFT_MODE_SEQUENTIAL && b->knap_stride < 2) return DEFT_ERR_INVALID_ARG;
+    const bool two_link = b->mode == DEFT_MODE_JOINT2 || b->mode == DEFT_MODE_GREEDY2;
+    if ((two_link || b->mode == DEFT_MODE_RECURSIVE) && b->knap_stride < 2) return DEFT_ERR_INVALID_ARG;
     if (b->mode == DEFT_MODE_RECURSIVE && !b->drop_time) return DEFT_ERR_INVALID_ARG;
     if (!b->n_items || !b->n_knapsacks || !b->weights || !b->values || !b->capacities || !b->total_value ||
         !b->knap_value || !b->knap_load || !b->assignment || !b->status)
@@ -188,8 +192,8 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     if (b->batch > h->cfg.max_batch || b->item_stride > h->cfg.max_items ||
         b->knap_stride > h->cfg.max_knapsacks)
         return DEFT_ERR_LIMIT;
-    if (b->mode == DEFT_MODE_SEQUENTIAL && h->seq_path == 0) return DEFT_ERR_LIMIT;
-    if (b->mode == DEFT_MODE_JOINT2 && h->joint_path == 0) return DEFT_ERR_LIMIT;
+    if (!two_link && h->seq_path == 0) return DEFT_ERR_LIMIT;
+    if (two_link && h->joint_path == 0) return DEFT_ERR_LIMIT;
     // Algorithm 1 runs on the LDS-resident row only
     if (b->mode == DEFT_MODE_RECURSIVE && h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;
     if (b->batch == 0) return DEFT_OK;
@@ -210,7 +214,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     a.weights = b->weights;
     a.values = b->values;
     a.capacities = b->capacities;
-    a.fill_order = b->fill_order;
+    a.fill_order = b->mode == DEFT_MODE_SEQUENTIAL ? b->fill_order : nullptr;
     a.drop_time = b->mode == DEFT_MODE_RECURSIVE ? b->drop_time : nullptr;
     a.total_value = b->total_value;
     a.knap_value = b->knap_value;
@@ -230,6 +234,10 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
             e = seq_lds_launch(h->lds_plan, a, h->keep, st);
             if (prof) prof->sweep_end(st);
         }
+    } else if (b->mode == DEFT_MODE_GREEDY || b->mode == DEFT_MODE_GREEDY2) {
+        if (prof) prof->sweep_begin(st);
+        e = greedy_launch(a, two_link, st);
+        if (prof) prof->sweep_end(st);
     } else if (b->mode == DEFT_MODE_RECURSIVE) {
         if (prof) prof->sweep_begin(st);
         e = seq_lds_rec_launch(h->lds_plan, a, h->keep, st);

@@ -107,7 +107,7 @@ jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uin
     const bool loader = wave < kLoadWaves;
     const int segs = pitch / 64;
     const int ncol = st.c2 + 1, nrow = st.c1 + 1;
-    const int nseg = (ncol + 63) / 64, ntile = (ncol + 255) / 256;
+    const int ntile = (ncol + 255) / 256;
     const size_t tsz = (size_t)rows * pitch;
     const int32_t *W0 = a.weights + (size_t)inst * 2 * a.item_stride;
     const int32_t *W1 = W0 + a.item_stride;

@@ -113,4 +113,9 @@ hipError_t joint_prepare(const JointPlan &plan);
 hipError_t joint_launch(const JointPlan &plan, const BatchArgs &args, void *scratch, hipStream_t stream,
                         Profiler *prof);
 
+// ---- the paper's greedy heuristic (greedy.hip) ----------------------------------
+// No scratch memory.  per_link: the two-link weight layout.
+hipError_t greedy_prepare(int32_t max_items);
+hipError_t greedy_launch(const BatchArgs &args, bool per_link, hipStream_t stream);
+
 }  // namespace deft

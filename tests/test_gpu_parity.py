@@ -37,7 +37,7 @@ def assert_same(kb, out, ref):
 
 def run(binding, oracle, kb, **limits):
     print(f"case {kb.name} batch={kb.batch} n={kb.item_stride} m={kb.knap_stride} limits={limits}", flush=True)
-    seq = kb.mode != W.MODE_JOINT2
+    seq = kb.mode not in (W.MODE_JOINT2, W.MODE_GREEDY2)
     ref = oracle.solve_batch(kb, nthreads=16, cap_limit=limits.get("max_capacity", -1) if seq else -1,
                              c1_limit=limits.get("max_c1", -1), c2_limit=limits.get("max_c2", -1))
     out = binding.solve(kb, **limits)
