@@ -26,6 +26,10 @@
  *     and bucket times are sorted, then the knapsacks are gone through from the
  *     smallest capacity up and each takes, longest bucket first, whatever still
  *     fits.
+ *   - Section IV.C, the feedback mechanism: when a schedule fails the convergence
+ *     test the knapsack capacity is raised and the problem solved again, up to
+ *     ten times -> one instance = one item list and several capacities, each an
+ *     independent Problem 1.
  *
  * Conventions the paper leaves open, fixed here:
  *   - an item is taken at capacity c only if it strictly improves the value;
@@ -401,6 +405,59 @@ int deft_oracle_greedy(int32_t n, int32_t item_stride, const int32_t *w, int per
     return ST_OK;
 }
 
+/*
+ * Capacity sweep for one instance (the Solver called again with a larger capacity,
+ * Section IV.C): cap[0..m) are m capacities of ONE knapsack; each is Problem 1 over the
+ * whole item list, solved on its own from scratch.
+ * Outputs: knap_value[j] / knap_load[j] = value and weight scheduled at capacity cap[j];
+ * assign[i] = bit mask over j of the capacities at which item i is scheduled (0 if none;
+ * slots >= n also 0); total = the value at the largest capacity.  m <= 31.
+ */
+int deft_oracle_capacity_sweep(int32_t n, int32_t item_stride, const int32_t *w, const int32_t *v,
+                               int32_t m, int32_t knap_stride, const int32_t *cap, int32_t cap_limit,
+                               int64_t *total, int32_t *knap_value, int32_t *knap_load, int32_t *assign,
+                               int64_t *touched_cells, int64_t *table_cells)
+{
+    int64_t touched = 0, table = 0;
+    clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+    for (int i = 0; i < item_stride; ++i) assign[i] = 0;      /* masks, not knapsack ids */
+    if (touched_cells) *touched_cells = 0;
+    if (table_cells) *table_cells = 0;
+    if (n < 0 || n > item_stride || m < 0 || m > knap_stride || m > 31) return ST_INVALID;
+    for (int i = 0; i < n; ++i)
+        if (w[i] < 1 || v[i] < 0) return ST_INVALID;
+    for (int j = 0; j < m; ++j)
+        if (cap[j] < 0) return ST_INVALID;
+    for (int j = 0; j < m; ++j)
+        if (cap_limit >= 0 && cap[j] > cap_limit) return ST_LIMIT;
+    int64_t vsum = 0;
+    for (int i = 0; i < n; ++i) vsum += v[i];
+    if (vsum >= VALUE_SUM_LIMIT) return ST_OVERFLOW;
+
+    uint8_t *chosen = (uint8_t *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!chosen) return ST_OOM;
+    int32_t largest = -1;
+    for (int j = 0; j < m; ++j) {
+        int64_t value = 0, load = 0;
+        int rc = single_stage(n, w, v, cap[j], &value, &load, chosen, &touched, &table);
+        if (rc != ST_OK) {
+            free(chosen);
+            clear_outputs(item_stride, knap_stride, total, knap_value, knap_load, assign);
+            for (int i = 0; i < item_stride; ++i) assign[i] = 0;
+            return rc;
+        }
+        knap_value[j] = (int32_t)value;
+        knap_load[j] = (int32_t)load;
+        for (int i = 0; i < n; ++i)
+            if (chosen[i]) assign[i] |= (int32_t)(1u << j);
+        if (cap[j] > largest) { largest = cap[j]; *total = value; }
+    }
+    free(chosen);
+    if (touched_cells) *touched_cells = touched;
+    if (table_cells) *table_cells = table;
+    return ST_OK;
+}
+
 /* ---- batch driver: instances split statically over nthreads ------------- */
 
 typedef struct {
@@ -432,6 +489,11 @@ static void solve_one(const batch_args_t *a, int b)
                                    a->capacities + b * ks, a->cap_limit, a->total + b,
                                    a->knap_value + b * ks, a->knap_load + b * ks, a->assign + b * is,
                                    &touched, &table);
+    } else if (a->mode == 5) {
+        st = deft_oracle_capacity_sweep(a->n_items[b], a->item_stride, a->weights + b * is, a->values + b * is,
+                                        a->n_knapsacks[b], a->knap_stride, a->capacities + b * ks, a->cap_limit,
+                                        a->total + b, a->knap_value + b * ks, a->knap_load + b * ks,
+                                        a->assign + b * is, &touched, &table);
     } else if (a->mode == 3 || a->mode == 4) {
         int per_link = a->mode == 4;
         st = deft_oracle_greedy(a->n_items[b], a->item_stride, a->weights + b * (per_link ? 2 : 1) * is, per_link,
@@ -468,7 +530,7 @@ int deft_oracle_solve_batch(int32_t mode, int32_t batch, int32_t item_stride, in
                             int32_t *assign, int32_t *status, int64_t *touched, int64_t *table,
                             int32_t nthreads)
 {
-    if (mode < 0 || mode > 4 || (mode == 2 && !drop_time) || batch < 0 || item_stride < 0 || knap_stride < 0)
+    if (mode < 0 || mode > 5 || (mode == 2 && !drop_time) || batch < 0 || item_stride < 0 || knap_stride < 0)
         return -1;
     batch_args_t a = { mode, batch, item_stride, knap_stride, n_items, n_knapsacks, weights,
                        values, capacities, fill_order, drop_time, cap_limit, c1_limit, c2_limit, total,

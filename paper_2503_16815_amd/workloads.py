@@ -35,6 +35,7 @@ MODE_JOINT2 = 1
 MODE_RECURSIVE = 2
 MODE_GREEDY = 3       # the paper's greedy heuristic on the sequential layout
 MODE_GREEDY2 = 4      # the same on the two-link layout (one time per link)
+MODE_CAPACITY_SWEEP = 5   # one item list, several capacities of one knapsack (Section IV.C feedback)
 
 SEED_TINY = 1001
 SEED_RESNET = 1002
@@ -303,3 +304,35 @@ def as_greedy(kb: KnapsackBatch) -> KnapsackBatch:
     g.mode = MODE_GREEDY if kb.mode == MODE_SEQUENTIAL else MODE_GREEDY2
     g.fill_order = None
     return g
+
+
+def random_capacity_sweep(seed: int, batch: int, n_max: int, m_max: int, w_hi: int, v_hi: int, cap_hi: int,
+                          ragged: bool = True, ties: bool = False) -> KnapsackBatch:
+    """Capacity sweeps (Section IV.C feedback: the Solver called again with a larger
+    capacity): per instance one item list and up to m_max capacities in random order."""
+    r = _rng(seed)
+    n_items = r.integers(0, n_max + 1, size=batch) if ragged else np.full(batch, n_max)
+    m = r.integers(0, m_max + 1, size=batch) if ragged else np.full(batch, m_max)
+    w = r.integers(1, w_hi + 1, size=(batch, n_max))
+    v = w.copy() if ties else r.integers(0, v_hi + 1, size=(batch, n_max))
+    cap = r.integers(0, cap_hi + 1, size=(batch, m_max))
+    return KnapsackBatch(
+        name=f"random_capacity_sweep_{seed}", mode=MODE_CAPACITY_SWEEP, batch=batch, item_stride=n_max,
+        knap_stride=m_max, n_items=_i32(n_items), n_knapsacks=_i32(m), weights=_i32(w), values=_i32(v),
+        capacities=_i32(cap), meta={"seed": seed})
+
+
+def inflation_sweep_shaped(batch: int = 1024, n: int = 314, probes: int = 11, seed: int = SEED_RESNET + 60) -> KnapsackBatch:
+    """ResNet-101-shaped feedback sweep: the backward window (11800 +-10 %, 10 us units) and
+    ten inflated capacities, +5 % of the window each (the paper retries up to ten times and
+    does not say by how much the capacity grows), over the 314 bucket times of
+    resnet101_shaped."""
+    r = _rng(seed)
+    x = r.lognormal(mean=0.0, sigma=1.2, size=(batch, n))
+    w = _rescale_to_sum(x, 24200.0)
+    base = 11800.0 * r.uniform(0.9, 1.1, size=(batch, 1))
+    cap = np.rint(base * (1.0 + 0.05 * np.arange(probes)[None, :])).astype(np.int64)
+    return KnapsackBatch(
+        name="inflation_sweep", mode=MODE_CAPACITY_SWEEP, batch=batch, item_stride=n, knap_stride=probes,
+        n_items=_i32(np.full(batch, n)), n_knapsacks=_i32(np.full(batch, probes)), weights=_i32(w),
+        values=_i32(w.copy()), capacities=_i32(cap), meta={"seed": seed})
