@@ -64,6 +64,11 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
         desc = (f"Algorithm 1 on ResNet-101-shaped backward stages: batch {sc(1024)}, n=314, remaining time "
                 f"11800 +-10%, v=w, every level read off one sweep")
         algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+    elif name == "inflation":
+        calls = [W.inflation_sweep_shaped(batch=sc(1024))]
+        desc = (f"capacity sweep on ResNet-101-shaped backward windows: batch {sc(1024)}, n=314, the window "
+                f"(11800 +-10%) and ten inflations of +5% each, v=w, all read off one sweep at the largest")
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
     elif name == "tiny":
         calls = [W.tiny_bruteforce(batch=sc(64))]
         desc = f"Tiny: batch {sc(64)}, n=16, capacities 500/250"
@@ -79,7 +84,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet101",
-                    choices=["resnet101", "vgg19", "gpt2", "hetero", "backward", "tiny"])
+                    choices=["resnet101", "vgg19", "gpt2", "hetero", "backward", "inflation", "tiny"])
     ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
     ap.add_argument("--per-k-calls", action="store_true",
@@ -139,14 +144,16 @@ def main() -> int:
     table = [int(r.table_cells.sum()) for r in refs]
     cells_step = sum(touched)
     recursion_cells = None
-    if calls[0].mode == 2:
-        # Algorithm 1: the oracle runs one DP per level and counts them all; the solver does one
-        # sweep over the whole list at the full remaining time, and that is what the metric counts
+    if calls[0].mode in (2, 5):
+        # Algorithm 1 / capacity sweep: the oracle runs one DP per level / per capacity and counts
+        # them all; the solver does one sweep over the whole list at the full remaining time / the
+        # largest capacity, and that is what the metric counts
         recursion_cells = cells_step
         cells_step = 0
         for kb in calls:
             live = np.arange(kb.item_stride)[None, :] < kb.n_items[:, None]
-            room = kb.capacities[:, :1].astype(np.int64) - kb.weights + 1
+            top = kb.capacities[:, :1] if kb.mode == 2 else kb.capacities.max(axis=1, keepdims=True)
+            room = top.astype(np.int64) - kb.weights + 1
             cells_step += int((np.maximum(room, 0) * live).sum())
     inst_step = sum(kb.batch for kb in calls)
     if not args.no_cpu:

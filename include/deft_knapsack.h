@@ -38,7 +38,8 @@ enum {
     DEFT_MODE_JOINT2 = 1,     /* two links, one joint 2-D DP (Sec. III.C, Problem 2)       */
     DEFT_MODE_RECURSIVE = 2,  /* one window, the list shortened from its end (Algorithm 1) */
     DEFT_MODE_GREEDY = 3,     /* the paper's greedy heuristic, SEQUENTIAL layout (Sec. III.C)   */
-    DEFT_MODE_GREEDY2 = 4     /* the same on the JOINT2 layout (one time per link)              */
+    DEFT_MODE_GREEDY2 = 4,    /* the same on the JOINT2 layout (one time per link)              */
+    DEFT_MODE_CAPACITY_SWEEP = 5 /* one item list at several capacities (Sec. IV.C feedback)    */
 };
 
 /* Limits fixed at create time; they size the scratch memory and select the
@@ -100,6 +101,20 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *   fill_order is ignored.  Only handles whose max_capacity fits the LDS-resident row
  *   (seq_path 1 or 2) serve this mode; others return LIMIT from the call.
  *
+ * DEFT_MODE_CAPACITY_SWEEP (Sec. IV.C, the feedback mechanism: the Solver is called again
+ * with a larger knapsack capacity, up to ten times):
+ *   SEQUENTIAL layout, but capacities[b][0 .. n_knapsacks-1] are capacities of ONE knapsack,
+ *   in any order; each is Problem 1 over the whole item list, solved exactly as a
+ *   SEQUENTIAL stage (same tie rule).  One DP sweep at the largest capacity answers all of
+ *   them: the value at capacity c is cell c of the final row and the selection is walked
+ *   back from (last item, c).  n_knapsacks <= 31.
+ *     knap_value[j], knap_load[j]  value and weight scheduled at capacities[b][j]
+ *     assignment[i]                bit j set iff item i is scheduled at capacities[b][j]
+ *                                  (0 = nowhere; also for slots >= n_items and faulted
+ *                                  instances)
+ *     total_value                  the value at the largest capacity
+ *   fill_order is ignored.  Served by handles with seq_path 1 or 2 only (else LIMIT).
+ *
  * DEFT_MODE_GREEDY / DEFT_MODE_GREEDY2 (Sec. III.C, the heuristic of the paper's Solver;
  * here so that the exact modes can be compared with it on the same inputs):
  *   knapsacks sorted by capacity, ascending (equal capacities: lower id first); items
@@ -114,7 +129,7 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  * Layout (row-major, device memory):
  *   n_items     [batch]                      0 <= n_items[b] <= item_stride
  *   n_knapsacks [batch]                      0 <= n_knapsacks[b] <= knap_stride
- *   weights     SEQUENTIAL, RECURSIVE, GREEDY [batch][item_stride]   each >= 1
+ *   weights     SEQUENTIAL, RECURSIVE, GREEDY, CAPACITY_SWEEP [batch][item_stride]   each >= 1
  *               JOINT2, GREEDY2 [batch][2][item_stride]   row 0 = link 0, row 1 = link 1
  *   values      [batch][item_stride]         each >= 0, sum per instance < 2^31
  *   capacities  [batch][knap_stride]         indexed by knapsack id, each >= 0
@@ -127,8 +142,8 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *   assignment  [batch][item_stride]         knapsack id, or -1 (also for slots >= n_items)
  *   status      [batch]                      deft_status_t of the instance
  * A faulted instance (status != DEFT_OK: bad n/m, w < 1, v < 0, capacity < 0,
- * fill_order not a permutation, drop_time < 0, RECURSIVE with n_knapsacks != 1
- * -> INVALID_ARG; capacity above the create-time
+ * fill_order not a permutation, drop_time < 0, RECURSIVE with n_knapsacks != 1,
+ * CAPACITY_SWEEP with n_knapsacks > 31 -> INVALID_ARG; capacity above the create-time
  * limit -> LIMIT; value sum >= 2^31 -> OVERFLOW; in that precedence) gets
  * total_value 0, knap_value/knap_load 0 and assignment -1; other instances are
  * unaffected.

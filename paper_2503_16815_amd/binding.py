@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DEFT_KNAPSACK_LIB") or os.path.join(_HERE, "libdeft_knapsack.so")
 
 DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, DEFT_ERR_DEVICE = range(6)
-DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2, DEFT_MODE_RECURSIVE, DEFT_MODE_GREEDY, DEFT_MODE_GREEDY2 = range(5)
+(DEFT_MODE_SEQUENTIAL, DEFT_MODE_JOINT2, DEFT_MODE_RECURSIVE, DEFT_MODE_GREEDY, DEFT_MODE_GREEDY2,
+ DEFT_MODE_CAPACITY_SWEEP) = range(6)
 
 EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_destroy",
            "deft_knapsack_get_info", "deft_knapsack_set_profiling", "deft_knapsack_get_profile",

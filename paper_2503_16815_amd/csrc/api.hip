@@ -181,7 +181,7 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
 extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *b)
 {
     if (!h || !b) return DEFT_ERR_INVALID_ARG;
-    if (b->mode < DEFT_MODE_SEQUENTIAL || b->mode > DEFT_MODE_GREEDY2) return DEFT_ERR_INVALID_ARG;
+    if (b->mode < DEFT_MODE_SEQUENTIAL || b->mode > DEFT_MODE_CAPACITY_SWEEP) return DEFT_ERR_INVALID_ARG;
     if (b->batch < 0 || b->item_stride < 1 || b->knap_stride < 1) return DEFT_ERR_INVALID_ARG;
     const bool two_link = b->mode == DEFT_MODE_JOINT2 || b->mode == DEFT_MODE_GREEDY2;
     if ((two_link || b->mode == DEFT_MODE_RECURSIVE) && b->knap_stride < 2) return DEFT_ERR_INVALID_ARG;
@@ -194,8 +194,9 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         return DEFT_ERR_LIMIT;
     if (!two_link && h->seq_path == 0) return DEFT_ERR_LIMIT;
     if (two_link && h->joint_path == 0) return DEFT_ERR_LIMIT;
-    // Algorithm 1 runs on the LDS-resident row only
-    if (b->mode == DEFT_MODE_RECURSIVE && h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;
+    // Algorithm 1 and the capacity sweep run on the LDS-resident row only
+    const bool probing = b->mode == DEFT_MODE_RECURSIVE || b->mode == DEFT_MODE_CAPACITY_SWEEP;
+    if (probing && h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;
     if (b->batch == 0) return DEFT_OK;
 
     DeviceGuard g(h->cfg.device);
@@ -203,6 +204,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     hipStream_t st = static_cast<hipStream_t>(b->stream);
 
     BatchArgs a;
+    a.mode = b->mode;
     a.batch = b->batch;
     a.item_stride = b->item_stride;
     a.knap_stride = b->knap_stride;
@@ -238,7 +240,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         if (prof) prof->sweep_begin(st);
         e = greedy_launch(a, two_link, st);
         if (prof) prof->sweep_end(st);
-    } else if (b->mode == DEFT_MODE_RECURSIVE) {
+    } else if (probing) {
         if (prof) prof->sweep_begin(st);
         e = seq_lds_rec_launch(h->lds_plan, a, h->keep, st);
         if (prof) prof->sweep_end(st);

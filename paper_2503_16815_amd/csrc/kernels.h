@@ -11,6 +11,7 @@ namespace deft {
 
 // Arguments of one solve call as the kernels see them (all device pointers).
 struct BatchArgs {
+    int32_t mode;  // DEFT_MODE_*
     int32_t batch, item_stride, knap_stride;
     int32_t max_capacity, max_c1, max_c2;  // create-time limits (per-instance LIMIT status)
     const int32_t *n_items, *n_knapsacks, *weights, *values, *capacities, *fill_order;

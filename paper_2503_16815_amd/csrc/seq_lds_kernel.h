@@ -318,8 +318,13 @@ __device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_
 }
 
 // WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
-// REC = false: the sequential mode.  REC = true: Algorithm 1 on one knapsack (every item
-// offered, the best level tracked during the sweep, the walk started at that level).
+// REC = false: the sequential mode.  REC = true: the modes that read more than row[C] off
+// one sweep, chosen by a.mode at run time:
+//   Algorithm 1 on one knapsack (every item offered, the best level tracked during the
+//   sweep, the walk started at that level);
+//   the capacity sweep (Sec. IV.C feedback): one sweep at the largest of the instance's
+//   capacities, then the value at each capacity is a cell of the final row and each
+//   capacity gets a walk of its own, the wavefronts of the instance sharing the walks.
 template <int T, int K, int G, int WPE, bool REC>
 __global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
 seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, OfferedItem *lists,
@@ -352,7 +357,9 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     const int32_t *__restrict__ cap = a.capacities + (size_t)inst * a.knap_stride;
     const int32_t *__restrict__ ord =
         !REC && a.fill_order ? a.fill_order + (size_t)inst * a.knap_stride : nullptr;
-    const int32_t *__restrict__ drop = REC ? a.drop_time + (size_t)inst * a.item_stride : nullptr;
+    const bool levels = REC && a.mode == DEFT_MODE_RECURSIVE;      // Algorithm 1
+    const bool caps_sweep = REC && a.mode == DEFT_MODE_CAPACITY_SWEEP;
+    const int32_t *__restrict__ drop = levels ? a.drop_time + (size_t)inst * a.item_stride : nullptr;
     int32_t *out_asg = a.assignment + (size_t)inst * a.item_stride;
     int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
     int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
@@ -367,7 +374,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     {
         uint32_t flags = 0;
         unsigned long long vs = 0;
-        const bool counts_ok = n >= 0 && n <= a.item_stride && m >= 0 && m <= a.knap_stride && (!REC || m == 1);
+        const bool counts_ok = n >= 0 && n <= a.item_stride && m >= 0 && m <= a.knap_stride &&
+                               (!levels || m == 1) && (!caps_sweep || m <= 31);
         if (!counts_ok) {
             flags = 1;
         } else {
@@ -376,7 +384,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
                 if (v != w) flags |= 4;
                 if constexpr (REC) {
-                    if (drop[i] < 0) flags |= 1;
+                    if (levels && drop[i] < 0) flags |= 1;
                 }
             }
             for (int j = tid; j < m; j += T) {
@@ -412,7 +420,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         for (int j = 0; j < a.knap_stride; ++j) { out_kv[j] = 0; out_kl[j] = 0; }
         a.status[inst] = status;
     }
-    for (int i = tid; i < a.item_stride; i += T) out_asg[i] = -1;
+    // knapsack ids start at "none"; the capacity sweep's masks start empty
+    for (int i = tid; i < a.item_stride; i += T) out_asg[i] = caps_sweep ? 0 : -1;
     if (status != DEFT_OK) {
         if (tid == 0) a.total_value[inst] = 0;
         return;
@@ -422,12 +431,18 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     // Items already placed: bit (i / 64) of lane (i % 64) of the first wavefront.
     unsigned long long placed = 0;
     long long total = 0;
-    for (int s = 0; s < m; ++s) {
+    const int stages = caps_sweep ? min(m, 1) : m;
+    for (int s = 0; s < stages; ++s) {
         const int j = uniform(ord ? ord[s] : s);
-        const int C = uniform(cap[j]);
+        int C = uniform(cap[j]);
+        if constexpr (REC) {
+            if (caps_sweep) {  // one sweep at the largest capacity serves them all
+                for (int x = 1; x < m; ++x) C = max(C, uniform(cap[x]));
+            }
+        }
         OfferedItem *list = inst_lists + (size_t)s * list_stride;
 
-        if (REC && tid < 64) {
+        if (levels && tid < 64) {
             // Algorithm 1: the whole list is offered in generation order (an item heavier
             // than the remaining time changes nothing, but the levels are counted in list
             // positions).  Entry i gets P_i = R - sum of drop[t] over t >= i, the remaining
@@ -453,7 +468,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             if (tid == 0) misc[1] = n;
         }
         // offered items: not yet placed and able to fit at all, ascending index
-        if (!REC && tid < 64) {
+        if (!levels && tid < 64) {
             int cnt = 0;
             for (int i0 = 0; i0 < n; i0 += 64) {
                 const int i = i0 + tid;
@@ -463,7 +478,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 const unsigned long long mask = __ballot(f);
                 if (f) {
                     OfferedItem e;
-                    e.w = w; e.v = v; e.index = i; e.pad = 0;
+                    e.w = w; e.v = v; e.index = i; e.pad = -1;  // no level ends here
                     list[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = e;
                 }
                 cnt += __popcll(mask);
@@ -484,20 +499,27 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                                                               nact, list, kp, nzm, best);
 
         int value = uniform(row[C]) + (veqw ? C : 0);
-        // where the walk starts: the last offered item at the full capacity, or (REC) the
-        // last item of the best level at that level's remaining time
+        // where the walk starts: the last offered item at the full capacity, or (Algorithm 1)
+        // the last item of the best level at that level's remaining time
         int walk_from = nact - 1, walk_cap = C;
+        int sweep_cap = 0, sweep_value = 0;  // capacity sweep: lane x holds capacity x and the value there
         if constexpr (REC) {
-            if (value > best.value) best = BestLevel{value, nact, C};  // level 0: the whole list
-            value = best.value;
-            walk_from = best.length - 1;
-            walk_cap = best.remain;
+            if (levels) {
+                if (value > best.value) best = BestLevel{value, nact, C};  // level 0: the whole list
+                value = best.value;
+                walk_from = best.length - 1;
+                walk_cap = best.remain;
+            }
+            if (caps_sweep && (tid & 63) < m) {
+                sweep_cap = cap[tid & 63];
+                sweep_value = row[sweep_cap] + (veqw ? sweep_cap : 0);
+            }
         }
 
         // ---- traceback ------------------------------------------------------------
         // The row is dead now; its LDS holds what the walk needs: weight and index of
         // every offered item and, per wavefront, which keep-row parts exist.
-        lds_sync<T>();  // every lane has read row[C]
+        lds_sync<T>();  // every lane has read its cells of the final row
         int32_t *tb_w = row, *tb_index = row + list_stride;
         unsigned long long *tb_nz = reinterpret_cast<unsigned long long *>(row + 2 * list_stride);
         for (int i = tid; i < nact; i += T) {
@@ -515,16 +537,17 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         // a ballot then gives all 63 answers and the true path is read off it.  A lane
         // whose keep-row part was never written knows its answer (not taken) without a
         // load, so rounds through all-zero rows cost no memory round trip.
-        if (tid < 64) {
-            const int L = tid;
-            const int d = 31 - __clz(L | 1);
-            const int p = L - (1 << d);
+        // Returns the capacity left at the end; `chosen` gets the items taken, laid out
+        // like `placed`.
+        auto walk = [&](int L, int from, int at, unsigned long long &chosen) {
             // Every index is range-checked before it is used; a violation (never expected)
             // marks the instance DEFT_ERR_DEVICE instead of touching memory.
             bool broken = false;
-            int c = walk_cap;
-            int q = walk_from;
-            unsigned long long chosen = 0;  // items this stage places, laid out like `placed`
+            int c = at;
+            int q = from;
+            chosen = 0;
+            const int d = 31 - __clz(L | 1);
+            const int p = L - (1 << d);
             while (q >= 0) {
                 int wv[6], tv[6];
                 {
@@ -577,21 +600,47 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 }
                 q -= 6;
             }
-            placed |= chosen;
-            while (chosen) {  // outside the walk: no store sits in its chain of loads
-                const int b = __builtin_ctzll(chosen);
-                chosen &= chosen - 1;
-                out_asg[b * 64 + L] = j;
-            }
-            if (L == 0) {
-                out_kv[j] = value;
-                out_kl[j] = walk_cap - c;
-                if constexpr (REC) {  // slot 1 reports the level: items left off the list, its remaining time
-                    out_kv[1] = n - best.length;
-                    out_kl[1] = value > 0 ? walk_cap : 0;
+            if (__ballot(broken) != 0ull && L == 0) a.status[inst] = DEFT_ERR_DEVICE;
+            return c;
+        };
+        if (!caps_sweep) {
+            if (tid < 64) {
+                const int L = tid;
+                unsigned long long chosen;
+                const int c = walk(L, walk_from, walk_cap, chosen);
+                placed |= chosen;
+                while (chosen) {  // outside the walk: no store sits in its chain of loads
+                    const int b = __builtin_ctzll(chosen);
+                    chosen &= chosen - 1;
+                    out_asg[b * 64 + L] = j;
+                }
+                if (L == 0) {
+                    out_kv[j] = value;
+                    out_kl[j] = walk_cap - c;
+                    if constexpr (REC) {  // slot 1 reports the level: items left off the list, its remaining time
+                        out_kv[1] = n - best.length;
+                        out_kl[1] = value > 0 ? walk_cap : 0;
+                    }
                 }
             }
-            if (__ballot(broken) != 0ull && L == 0) a.status[inst] = DEFT_ERR_DEVICE;
+        } else if constexpr (REC) {
+            // one walk per capacity, dealt out to the wavefronts of the instance; an item's
+            // mask collects the capacities at which it is taken
+            const int L = tid & 63;
+            for (int x = tid >> 6; x < m; x += T / 64) {
+                const int at = __builtin_amdgcn_readlane(sweep_cap, x);
+                unsigned long long chosen;
+                const int c = walk(L, nact - 1, at, chosen);
+                while (chosen) {
+                    const int b = __builtin_ctzll(chosen);
+                    chosen &= chosen - 1;
+                    atomicOr(reinterpret_cast<unsigned int *>(&out_asg[b * 64 + L]), 1u << x);
+                }
+                if (L == 0) {
+                    out_kv[x] = __builtin_amdgcn_readlane(sweep_value, x);
+                    out_kl[x] = at - c;
+                }
+            }
         }
         total += value;
         lds_sync<T>();

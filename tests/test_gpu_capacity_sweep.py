@@ -1,0 +1,57 @@
+"""GPU parity of the capacity sweep (Section IV.C feedback): the HIP path answers every
+capacity from one DP sweep at the largest; the oracle solves each capacity from scratch.
+Bit-exact on every output."""
+import numpy as np
+import pytest
+
+from paper_2503_16815_amd import workloads as W
+from tests.test_gpu_parity import assert_same, binding, run  # noqa: F401  (binding is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cap_hi,max_capacity", [
+    (700, 1023), (3000, 4095), (8000, 8191), (10000, 10239), (13000, 13055), (20000, 26111), (33000, 36800),
+])
+def test_random_ragged_every_lds_variant(binding, oracle, cap_hi, max_capacity):
+    """Ragged n and capacity counts (0 .. 31, more capacities than wavefronts per
+    instance), capacities in random order from 0 up, items heavier than some or all of
+    them; then a tie-heavy batch."""
+    kb = W.random_capacity_sweep(9000 + cap_hi, batch=23, n_max=100, m_max=31, w_hi=max(20, cap_hi // 4),
+                                 v_hi=1000, cap_hi=cap_hi)
+    run(binding, oracle, kb, max_capacity=max_capacity)
+    kt = W.random_capacity_sweep(9500 + cap_hi, batch=13, n_max=70, m_max=12, w_hi=max(9, cap_hi // 40), v_hi=9,
+                                 cap_hi=cap_hi, ties=True)
+    run(binding, oracle, kt, max_capacity=max_capacity)
+
+
+def test_status_and_degenerate(binding, oracle):
+    kb = W.random_capacity_sweep(9601, batch=8, n_max=9, m_max=4, w_hi=9, v_hi=9, cap_hi=20, ragged=False)
+    kb.n_items[0] = 0
+    kb.n_knapsacks[1] = 0
+    kb.weights[2, 3] = 0
+    kb.capacities[3, 2] = -1
+    kb.capacities[4, 1] = 21
+    kb.values[5] = 2 ** 29
+    kb.weights[6] = 100
+    kb.capacities[7] = 5            # the same capacity four times
+    ref = run(binding, oracle, kb, max_capacity=20)
+    assert ref.status.tolist() == [0, 0, 1, 1, 2, 3, 0, 0]
+    big = W.random_capacity_sweep(9602, batch=2, n_max=5, m_max=32, w_hi=9, v_hi=9, cap_hi=20, ragged=False)
+    big.n_knapsacks[1] = 31
+    refb = run(binding, oracle, big, max_capacity=20)
+    assert refb.status.tolist() == [1, 0]
+
+
+def test_host_side_limit_on_global_rows(binding):
+    kb = W.random_capacity_sweep(9603, batch=2, n_max=5, m_max=3, w_hi=9, v_hi=9, cap_hi=20)
+    with binding.DeftKnapsack(max_batch=2, max_items=5, max_knapsacks=3, max_capacity=100000) as h:
+        with pytest.raises(binding.DeftError) as e:
+            h.solve_batch(h.upload(kb))
+        assert e.value.code == binding.DEFT_ERR_LIMIT
+
+
+def test_inflation_sweep_at_paper_shape(binding, oracle):
+    """1024 ResNet-101-shaped instances x 11 capacities (the window and ten inflations),
+    every output of every instance."""
+    run(binding, oracle, W.inflation_sweep_shaped())
