@@ -30,6 +30,9 @@
  *     test the knapsack capacity is raised and the problem solved again, up to
  *     ten times -> one instance = one item list and several capacities, each an
  *     independent Problem 1.
+ *   - Section III.B, the current and the future task queue and Cases 1-4: which item
+ *     list and which capacity each forward and backward stage solves, over several
+ *     iterations, and when parameter updates fire (deft_oracle_simulate).
  *
  * Conventions the paper leaves open, fixed here:
  *   - an item is taken at capacity c only if it strictly improves the value;
@@ -561,4 +564,180 @@ int deft_oracle_solve_batch(int32_t mode, int32_t batch, int32_t item_stride, in
         if (live[t]) pthread_join(tid[t], NULL);
     free(tid); free(sl); free(live);
     return started > 0 ? nthreads : 1;
+}
+
+/* ---- the two task queues over several iterations (Section III.B, Cases 1-4) ---- */
+/*
+ * One candidate schedule simulated for `iterations` iterations.  Every iteration has a
+ * forward stage (window fwd) and then a backward stage (window bwd) during which its n
+ * buckets are generated; bucket i takes comm[i] to synchronise, and leaving it off the
+ * end of Algorithm 1's list takes drop[i] off the remaining time.
+ *
+ * State: the current task queue (a subset of the n buckets, holding the gradients of cur_k
+ * iterations merged together), the future task queue (empty, or all n buckets holding
+ * fut_k iterations), and done_k = iterations whose buckets are all synchronised but not
+ * yet applied.
+ *   Forward stage, current queue not empty (Case 1): plain knapsack over the current
+ *     queue with capacity fwd.
+ *   Backward stage, current queue not empty, its total time above bwd (Case 2): plain
+ *     knapsack over the current queue with capacity bwd; the new buckets join the future
+ *     queue (merged with what waits there).
+ *   Backward stage, current queue not empty and fits (Case 3): all of it is synchronised;
+ *     the new buckets join the future queue; Algorithm 1 over the future queue with what
+ *     is left of bwd; what it leaves becomes the current queue.
+ *   Backward stage, current queue empty (Case 4): the new buckets merged with the future
+ *     queue; Algorithm 1 over them with bwd; what it leaves becomes the current queue.
+ *   A queue that empties is complete; at the end of each iteration every complete set is
+ *   applied in one update, update_k[t] = iterations of gradients it carries (0 = none).
+ * Outputs per iteration t and stage s (0 forward, 1 backward):
+ *   stage_case[2t+s]  0 = nothing to do, else the case number
+ *   stage_count[2t+s] buckets synchronised in the stage, stage_time[2t+s] their time
+ *   update_k[t]
+ *   tail[0..2) = cur_k, fut_k after the last iteration;  *sweep_cells = sum over solved
+ *   stages of sum over listed buckets of max(0, capacity - comm + 1).
+ */
+int deft_oracle_simulate(int32_t n, int32_t iterations, const int32_t *comm, const int32_t *drop,
+                         int32_t fwd, int32_t bwd, int32_t cap_limit,
+                         int32_t *stage_case, int32_t *stage_count, int32_t *stage_time,
+                         int32_t *update_k, int32_t *tail, int64_t *sweep_cells)
+{
+    for (int x = 0; x < 2 * iterations; ++x) { stage_case[x] = 0; stage_count[x] = 0; stage_time[x] = 0; }
+    for (int t = 0; t < iterations; ++t) update_k[t] = 0;
+    tail[0] = tail[1] = 0;
+    *sweep_cells = 0;
+    if (n < 1 || iterations < 0 || fwd < 0 || bwd < 0) return ST_INVALID;
+    int64_t sum = 0;
+    for (int i = 0; i < n; ++i) {
+        if (comm[i] < 1 || drop[i] < 0) return ST_INVALID;
+        sum += comm[i];
+    }
+    if (cap_limit >= 0 && (fwd > cap_limit || bwd > cap_limit)) return ST_LIMIT;
+    if (sum >= VALUE_SUM_LIMIT) return ST_OVERFLOW;
+
+    uint8_t *cur = (uint8_t *)calloc((size_t)n, 1);       /* in the current task queue? */
+    uint8_t *chosen = (uint8_t *)calloc((size_t)n, 1);
+    int32_t *lw = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);   /* the stage's item list */
+    int32_t *lid = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+    if (!cur || !chosen || !lw || !lid) { free(cur); free(chosen); free(lw); free(lid); return ST_OOM; }
+    int cur_k = 0, fut_k = 0, done_k = 0, rc = ST_OK;
+    int64_t touched = 0, table = 0;
+
+    for (int t = 0; t < iterations && rc == ST_OK; ++t) {
+        for (int stage = 0; stage < 2 && rc == ST_OK; ++stage) {
+            int32_t *o_case = &stage_case[2 * t + stage], *o_count = &stage_count[2 * t + stage];
+            int32_t *o_time = &stage_time[2 * t + stage];
+            int in_cur = 0;
+            int64_t cur_time = 0;
+            for (int i = 0; i < n; ++i)
+                if (cur[i]) { ++in_cur; cur_time += comm[i]; }
+            int32_t window = stage == 0 ? fwd : bwd;
+
+            if (in_cur > 0 && (stage == 0 || cur_time > window)) {
+                /* Case 1 / Case 2: NaiveKnapsack over the current task queue */
+                int A = 0;
+                for (int i = 0; i < n; ++i)
+                    if (cur[i]) { lw[A] = comm[i]; lid[A] = i; ++A; }
+                for (int a = 0; a < A; ++a)
+                    if (lw[a] <= window) *sweep_cells += (int64_t)window - lw[a] + 1;
+                int64_t value = 0, load = 0;
+                rc = single_stage(A, lw, lw, window, &value, &load, chosen, &touched, &table);
+                if (rc != ST_OK) break;
+                int got = 0;
+                for (int a = 0; a < A; ++a)
+                    if (chosen[a]) { cur[lid[a]] = 0; ++got; }
+                *o_case = stage == 0 ? 1 : 2;
+                *o_count = got;
+                *o_time = (int32_t)load;
+                if (stage == 1) ++fut_k;                  /* the new buckets wait in the future queue */
+                if (got == in_cur) { done_k += cur_k; cur_k = 0; }
+            } else if (stage == 1) {
+                /* Case 3 (the current queue fits: all of it goes first) or Case 4 (it is empty) */
+                int64_t remain = window;
+                if (in_cur > 0) {
+                    *o_case = 3;
+                    *o_count = in_cur;
+                    *o_time = (int32_t)cur_time;
+                    remain -= cur_time;
+                    for (int i = 0; i < n; ++i) cur[i] = 0;
+                    done_k += cur_k;
+                } else {
+                    *o_case = 4;
+                }
+                int list_k = fut_k + 1;                   /* this iteration's buckets merged with the future queue */
+                fut_k = 0;
+                for (int i = 0; i < n; ++i)
+                    if (comm[i] <= remain) *sweep_cells += remain - comm[i] + 1;
+                rec_result_t res = { 0, 0, 0, 0, chosen };
+                memset(chosen, 0, (size_t)n);
+                rc = recursive_knapsack(n, comm, comm, drop, remain, &res, &touched, &table);
+                if (rc != ST_OK) break;
+                if (res.value == 0) res.len = 0;
+                int got = 0;
+                for (int i = 0; i < n; ++i) {
+                    int take = i < res.len && chosen[i];
+                    cur[i] = (uint8_t)!take;              /* what Algorithm 1 leaves is the new current queue */
+                    got += take;
+                }
+                *o_count += got;
+                *o_time += (int32_t)res.load;
+                cur_k = list_k;
+                if (got == n) { done_k += cur_k; cur_k = 0; }
+            }
+            if (stage == 1) {                             /* end of the iteration: apply what is complete */
+                update_k[t] = done_k;
+                done_k = 0;
+            }
+        }
+    }
+    tail[0] = cur_k;
+    tail[1] = fut_k;
+    free(cur); free(chosen); free(lw); free(lid);
+    return rc;
+}
+
+typedef struct {
+    int32_t n, iterations, cap_limit, lo, hi;
+    const int32_t *comm, *drop, *fwd, *bwd;
+    int32_t *stage_case, *stage_count, *stage_time, *update_k, *tail, *status;
+    int64_t *sweep_cells;
+} sim_slice_t;
+
+static void *sim_worker(void *p)
+{
+    sim_slice_t *s = (sim_slice_t *)p;
+    for (int b = s->lo; b < s->hi; ++b) {
+        size_t sn = (size_t)b * (size_t)s->n, si = (size_t)b * (size_t)s->iterations;
+        s->status[b] = deft_oracle_simulate(s->n, s->iterations, s->comm + sn, s->drop + sn, s->fwd[b], s->bwd[b],
+                                            s->cap_limit, s->stage_case + 2 * si, s->stage_count + 2 * si,
+                                            s->stage_time + 2 * si, s->update_k + si, s->tail + 2 * (size_t)b,
+                                            s->sweep_cells + b);
+    }
+    return NULL;
+}
+
+/* Batch of candidate schedules; arrays are [batch][n], [batch], [batch][iterations][2], [batch][iterations], [batch][2]. */
+int deft_oracle_simulate_batch(int32_t batch, int32_t n, int32_t iterations, const int32_t *comm, const int32_t *drop,
+                               const int32_t *fwd, const int32_t *bwd, int32_t cap_limit, int32_t *stage_case,
+                               int32_t *stage_count, int32_t *stage_time, int32_t *update_k, int32_t *tail,
+                               int32_t *status, int64_t *sweep_cells, int32_t nthreads)
+{
+    if (batch < 0 || n < 1 || iterations < 0) return -1;
+    if (nthreads < 1) nthreads = 1;
+    if (nthreads > batch) nthreads = batch > 0 ? batch : 1;
+    pthread_t *tid = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)nthreads);
+    sim_slice_t *sl = (sim_slice_t *)malloc(sizeof(sim_slice_t) * (size_t)nthreads);
+    char *live = (char *)calloc((size_t)nthreads, 1);
+    if (!tid || !sl || !live) { free(tid); free(sl); free(live); return -1; }
+    for (int t = 0; t < nthreads; ++t) {
+        sim_slice_t s = { n, iterations, cap_limit, (int)((int64_t)batch * t / nthreads),
+                          (int)((int64_t)batch * (t + 1) / nthreads), comm, drop, fwd, bwd, stage_case, stage_count,
+                          stage_time, update_k, tail, status, sweep_cells };
+        sl[t] = s;
+        if (nthreads > 1 && pthread_create(&tid[t], NULL, sim_worker, &sl[t]) == 0) live[t] = 1;
+        else sim_worker(&sl[t]);
+    }
+    for (int t = 0; t < nthreads; ++t)
+        if (live[t]) pthread_join(tid[t], NULL);
+    free(tid); free(sl); free(live);
+    return nthreads;
 }

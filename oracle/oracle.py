@@ -43,6 +43,9 @@ def _load():
         lib.deft_oracle_solve_batch.restype = ctypes.c_int
         lib.deft_oracle_solve_batch.argtypes = [i32, i32, i32, i32, p32, p32, p32, p32, p32, p32, p32,
                                                 i32, i32, i32, p64, p32, p32, p32, p32, p64, p64, i32]
+        lib.deft_oracle_simulate_batch.restype = ctypes.c_int
+        lib.deft_oracle_simulate_batch.argtypes = [i32, i32, i32, p32, p32, p32, p32, i32, p32, p32, p32, p32, p32,
+                                                   p32, p64, i32]
         _lib = lib
     return _lib
 
@@ -94,3 +97,38 @@ def solve_batch(kb, cap_limit: int = -1, c1_limit: int = -1, c2_limit: int = -1,
     if used < 0:
         raise ValueError("oracle: bad batch arguments")
     return OracleResult(total, kv, kl, asg, st, touched, table, used)
+
+
+@dataclass
+class SimulationResult:
+    stage_case: np.ndarray    # int32 [batch, iterations, 2]  0 = nothing to do, else Case 1..4
+    stage_count: np.ndarray   # int32 [batch, iterations, 2]  buckets synchronised in the stage
+    stage_time: np.ndarray    # int32 [batch, iterations, 2]  their communication time
+    update_k: np.ndarray      # int32 [batch, iterations]     iterations of gradients applied at the end of t
+    tail: np.ndarray          # int32 [batch, 2]              cur_k, fut_k after the last iteration
+    status: np.ndarray        # int32 [batch]
+    sweep_cells: np.ndarray   # int64 [batch]  sum over solved stages of sum_i max(0, capacity - comm_i + 1)
+    threads: int
+
+
+def simulate_batch(sb, cap_limit: int = -1, nthreads: int = 1) -> SimulationResult:
+    """sb: any object with batch, n_buckets, iterations, comm_time [batch, n], drop_time [batch, n],
+    forward_time [batch], backward_time [batch]."""
+    lib = _load()
+    B, n, I = int(sb.batch), int(sb.n_buckets), int(sb.iterations)
+    c = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+    comm, drop, fwd, bwd = c(sb.comm_time), c(sb.drop_time), c(sb.forward_time), c(sb.backward_time)
+    assert comm.shape == (B, n) and drop.shape == (B, n) and fwd.shape == (B,) and bwd.shape == (B,)
+    case = np.zeros((B, I, 2), np.int32)
+    count = np.zeros((B, I, 2), np.int32)
+    tim = np.zeros((B, I, 2), np.int32)
+    upd = np.zeros((B, I), np.int32)
+    tail = np.zeros((B, 2), np.int32)
+    st = np.zeros(B, np.int32)
+    cells = np.zeros(B, np.int64)
+    used = lib.deft_oracle_simulate_batch(B, n, I, _p32(comm), _p32(drop), _p32(fwd), _p32(bwd), cap_limit,
+                                          _p32(case), _p32(count), _p32(tim), _p32(upd), _p32(tail), _p32(st),
+                                          _p64(cells), nthreads)
+    if used < 0:
+        raise ValueError("oracle: bad simulation arguments")
+    return SimulationResult(case, count, tim, upd, tail, st, cells, used)

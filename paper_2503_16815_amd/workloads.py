@@ -336,3 +336,45 @@ def inflation_sweep_shaped(batch: int = 1024, n: int = 314, probes: int = 11, se
         name="inflation_sweep", mode=MODE_CAPACITY_SWEEP, batch=batch, item_stride=n, knap_stride=probes,
         n_items=_i32(np.full(batch, n)), n_knapsacks=_i32(np.full(batch, probes)), weights=_i32(w),
         values=_i32(w.copy()), capacities=_i32(cap), meta={"seed": seed})
+
+
+@dataclass
+class ScheduleBatch:
+    """Candidate schedules for the task-queue simulation (Section III.B, Cases 1-4): per
+    candidate the n bucket communication times in Algorithm 1's list order, the time each
+    takes off the remaining time when left off the list, and the forward and backward
+    windows; simulated for `iterations` iterations."""
+    name: str
+    batch: int
+    n_buckets: int
+    iterations: int
+    comm_time: np.ndarray      # int32 [batch, n_buckets]
+    drop_time: np.ndarray      # int32 [batch, n_buckets]
+    forward_time: np.ndarray   # int32 [batch]
+    backward_time: np.ndarray  # int32 [batch]
+
+
+def random_schedules(seed: int, batch: int, n: int, iterations: int, w_hi: int, t_hi: int, f_hi: int,
+                     b_hi: int) -> ScheduleBatch:
+    r = _rng(seed)
+    return ScheduleBatch(
+        name=f"random_schedules_{seed}", batch=batch, n_buckets=n, iterations=iterations,
+        comm_time=_i32(r.integers(1, w_hi + 1, size=(batch, n))),
+        drop_time=_i32(r.integers(0, t_hi + 1, size=(batch, n))),
+        forward_time=_i32(r.integers(0, f_hi + 1, size=batch)),
+        backward_time=_i32(r.integers(0, b_hi + 1, size=batch)))
+
+
+def resnet101_schedules(batch: int = 1024, n: int = 314, iterations: int = 8,
+                        seed: int = SEED_RESNET + 70) -> ScheduleBatch:
+    """ResNet-101-shaped candidates: bucket times as resnet101_shaped (sum 24200 in 10 us
+    units), backward window 11800 and forward window 5900, each +-10 % per candidate (Table
+    I); leaving a bucket off Algorithm 1's list costs its share of the backward window."""
+    r = _rng(seed)
+    x = r.lognormal(mean=0.0, sigma=1.2, size=(batch, n))
+    w = _rescale_to_sum(x, 24200.0)
+    bwd = np.rint(11800.0 * r.uniform(0.9, 1.1, size=batch)).astype(np.int64)
+    fwd = np.rint(5900.0 * r.uniform(0.9, 1.1, size=batch)).astype(np.int64)
+    drop = np.rint(x / x.sum(axis=1, keepdims=True) * bwd[:, None]).astype(np.int64)
+    return ScheduleBatch(name="resnet101_schedules", batch=batch, n_buckets=n, iterations=iterations,
+                         comm_time=_i32(w), drop_time=_i32(drop), forward_time=_i32(fwd), backward_time=_i32(bwd))
