@@ -178,6 +178,68 @@ typedef struct {
  */
 deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *batch);
 
+/*
+ * The current and the future task queue of Sec. III.B (Cases 1-4), simulated for
+ * `iterations` iterations over `batch` independent candidate schedules.  A candidate is
+ * n_buckets communication times (in the order of Algorithm 1's list: the last bucket is
+ * the first one the list loses), the time each bucket takes off the remaining time when
+ * it is left off that list, and a forward and a backward window.  Every iteration has a
+ * forward stage and then a backward stage, during which its buckets are generated:
+ *   forward stage, current queue not empty (Case 1): Problem 1 over the current queue,
+ *     capacity = forward window;
+ *   backward stage, current queue not empty and longer than the backward window (Case 2):
+ *     Problem 1 over it, capacity = backward window; the new buckets join the future queue
+ *     (merged with what waits there);
+ *   backward stage, current queue not empty and fitting (Case 3): all of it is
+ *     synchronised first; the new buckets join the future queue; Algorithm 1 over the
+ *     future queue with what is left of the window; what it leaves becomes the current
+ *     queue;
+ *   backward stage, current queue empty (Case 4): Algorithm 1 over the new buckets merged
+ *     with the future queue, with the whole window; what it leaves becomes the current
+ *     queue.
+ * A queue that empties is complete; at the end of each iteration all complete gradients
+ * are applied in one parameter update.  Each stage's problem is solved exactly as
+ * DEFT_MODE_SEQUENTIAL / DEFT_MODE_RECURSIVE solve it (value = communication time).
+ *
+ * Inputs (device, int32):  comm_time [batch][n_buckets] >= 1 (sum per candidate < 2^31),
+ *   drop_time [batch][n_buckets] >= 0, forward_time [batch], backward_time [batch]
+ *   (0 .. max_capacity).
+ * Outputs (device, int32, every slot written; s = 0 forward, 1 backward):
+ *   stage_case  [batch][iterations][2]  0 = nothing to solve, else the case number
+ *   stage_count [batch][iterations][2]  buckets synchronised in the stage
+ *   stage_time  [batch][iterations][2]  their communication time (<= the window)
+ *   update_k    [batch][iterations]     iterations of gradients applied at the end of
+ *                                       iteration t (0 = no update)
+ *   tail        [batch][2]              iterations still held by the current / the future
+ *                                       queue after the last iteration
+ *   status      [batch]                 INVALID_ARG (time < 1, drop time < 0, window < 0),
+ *                                       LIMIT (window above max_capacity), OVERFLOW; such a
+ *                                       candidate's other outputs are 0
+ * The call enqueues everything on `stream` and returns; its first use on a handle
+ * allocates the queue state (sized for max_batch x max_items; OOM if that fails).
+ * Host-side errors: INVALID_ARG (NULL, batch < 0, n_buckets < 1, iterations < 1), LIMIT
+ * (above the create-time limits, iterations > 4096, max_knapsacks < 2, or a handle whose
+ * rows do not fit LDS: seq_path 3), DEVICE.
+ */
+typedef struct {
+    int32_t batch;
+    int32_t n_buckets;
+    int32_t iterations;
+    const int32_t *comm_time;
+    const int32_t *drop_time;
+    const int32_t *forward_time;
+    const int32_t *backward_time;
+    int32_t *stage_case;
+    int32_t *stage_count;
+    int32_t *stage_time;
+    int32_t *update_k;
+    int32_t *tail;
+    int32_t *status;
+    void *stream; /* hipStream_t; NULL = the default stream */
+} deft_schedule_batch_t;
+
+deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, const deft_schedule_batch_t *s);
+
 /* deft_knapsack_destroy: free the scratch and the handle.  NULL is a no-op. */
 void deft_knapsack_destroy(deft_knapsack_t *h);
 

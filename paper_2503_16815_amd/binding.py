@@ -22,7 +22,7 @@ DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, 
 
 EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_destroy",
            "deft_knapsack_get_info", "deft_knapsack_set_profiling", "deft_knapsack_get_profile",
-           "deft_knapsack_status_string")
+           "deft_knapsack_status_string", "deft_knapsack_simulate_schedule")
 
 
 class deft_knapsack_config_t(ctypes.Structure):
@@ -39,6 +39,14 @@ class deft_knapsack_batch_t(ctypes.Structure):
                 ("total_value", ctypes.c_void_p), ("knap_value", ctypes.c_void_p),
                 ("knap_load", ctypes.c_void_p), ("assignment", ctypes.c_void_p), ("status", ctypes.c_void_p),
                 ("stream", ctypes.c_void_p), ("drop_time", ctypes.c_void_p)]
+
+
+class deft_schedule_batch_t(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_buckets", ctypes.c_int32), ("iterations", ctypes.c_int32),
+                ("comm_time", ctypes.c_void_p), ("drop_time", ctypes.c_void_p), ("forward_time", ctypes.c_void_p),
+                ("backward_time", ctypes.c_void_p), ("stage_case", ctypes.c_void_p),
+                ("stage_count", ctypes.c_void_p), ("stage_time", ctypes.c_void_p), ("update_k", ctypes.c_void_p),
+                ("tail", ctypes.c_void_p), ("status", ctypes.c_void_p), ("stream", ctypes.c_void_p)]
 
 
 class deft_knapsack_info_t(ctypes.Structure):
@@ -77,6 +85,8 @@ def load_library() -> ctypes.CDLL:
     lib.deft_knapsack_set_profiling.argtypes = [vp, ctypes.c_int32]
     lib.deft_knapsack_get_profile.restype = ctypes.c_int
     lib.deft_knapsack_get_profile.argtypes = [vp, ctypes.POINTER(deft_knapsack_profile_t)]
+    lib.deft_knapsack_simulate_schedule.restype = ctypes.c_int
+    lib.deft_knapsack_simulate_schedule.argtypes = [vp, ctypes.POINTER(deft_schedule_batch_t)]
     lib.deft_knapsack_status_string.restype = ctypes.c_char_p
     lib.deft_knapsack_status_string.argtypes = [ctypes.c_int32]
     _lib = lib
@@ -199,6 +209,50 @@ class DeftKnapsack:
         if rc != DEFT_OK:
             raise DeftError("deft_knapsack_solve_batch", rc)
         return db.out
+
+
+@dataclass
+class ScheduleOutputs:
+    stage_case: torch.Tensor   # int32 [batch, iterations, 2]
+    stage_count: torch.Tensor  # int32 [batch, iterations, 2]
+    stage_time: torch.Tensor   # int32 [batch, iterations, 2]
+    update_k: torch.Tensor     # int32 [batch, iterations]
+    tail: torch.Tensor         # int32 [batch, 2]
+    status: torch.Tensor       # int32 [batch]
+
+
+class DeviceSchedules:
+    """Inputs of one simulation call resident on the device, outputs pre-allocated."""
+
+    def __init__(self, sb, device: torch.device):
+        self.batch, self.n_buckets, self.iterations = int(sb.batch), int(sb.n_buckets), int(sb.iterations)
+        self.comm_time = _dev_i32(sb.comm_time, device)
+        self.drop_time = _dev_i32(sb.drop_time, device)
+        self.forward_time = _dev_i32(sb.forward_time, device)
+        self.backward_time = _dev_i32(sb.backward_time, device)
+        B, I = self.batch, self.iterations
+        e = lambda *shape: torch.empty(shape, dtype=torch.int32, device=device)
+        self.out = ScheduleOutputs(e(B, I, 2), e(B, I, 2), e(B, I, 2), e(B, I), e(B, 2), e(B))
+
+    def c_struct(self, stream_handle: int) -> deft_schedule_batch_t:
+        o = self.out
+        p = lambda t: ctypes.c_void_p(t.data_ptr())
+        return deft_schedule_batch_t(
+            self.batch, self.n_buckets, self.iterations, p(self.comm_time), p(self.drop_time),
+            p(self.forward_time), p(self.backward_time), p(o.stage_case), p(o.stage_count), p(o.stage_time),
+            p(o.update_k), p(o.tail), p(o.status), ctypes.c_void_p(stream_handle))
+
+
+def simulate_schedule(h: "DeftKnapsack", ds: DeviceSchedules,
+                      stream: Optional[torch.cuda.Stream] = None) -> ScheduleOutputs:
+    """Enqueue one task-queue simulation on `stream` (default: torch's current stream)."""
+    if stream is None:
+        stream = torch.cuda.current_stream(h.device)
+    cs = ds.c_struct(stream.cuda_stream)
+    rc = h._lib.deft_knapsack_simulate_schedule(h._h, ctypes.byref(cs))
+    if rc != DEFT_OK:
+        raise DeftError("deft_knapsack_simulate_schedule", rc)
+    return ds.out
 
 
 def solve(kb, device: int = 0, **limits) -> SolveOutputs:

@@ -17,6 +17,7 @@ constexpr int32_t kMaxKnapsacks = 64;
 constexpr int32_t kMaxBatch = 1 << 20;
 constexpr int32_t kMaxCapacity = 1 << 24;
 constexpr int32_t kMaxJointCapacity = 4095;
+constexpr int32_t kMaxIterations = 4096;
 
 struct DeviceGuard {
     int prev = -1;
@@ -46,6 +47,8 @@ struct deft_knapsack {
     void *glob_scratch = nullptr;
     unsigned long long *glob_streamed = nullptr;  // device counter read by get_profile
 
+    void *sim_buffers = nullptr;  // task-queue simulation: allocated by its first call
+
     int joint_path = 0;
     JointPlan joint_plan{};
     void *joint_scratch = nullptr;
@@ -64,6 +67,7 @@ void free_handle(deft_knapsack *h)
     if (h->glob_scratch) (void)hipFree(h->glob_scratch);
     if (h->glob_streamed) (void)hipFree(h->glob_streamed);
     if (h->joint_scratch) (void)hipFree(h->joint_scratch);
+    if (h->sim_buffers) (void)hipFree(h->sim_buffers);
     h->prof.destroy();
     delete h;
 }
@@ -247,6 +251,54 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     } else {
         e = joint_launch(h->joint_plan, a, h->joint_scratch, st, prof);
     }
+    if (prof) prof->end(st);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return DEFT_ERR_DEVICE;
+    }
+    return DEFT_OK;
+}
+
+extern "C" deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, const deft_schedule_batch_t *s)
+{
+    if (!h || !s) return DEFT_ERR_INVALID_ARG;
+    if (s->batch < 0 || s->n_buckets < 1 || s->iterations < 1) return DEFT_ERR_INVALID_ARG;
+    if (!s->comm_time || !s->drop_time || !s->forward_time || !s->backward_time || !s->stage_case ||
+        !s->stage_count || !s->stage_time || !s->update_k || !s->tail || !s->status)
+        return DEFT_ERR_INVALID_ARG;
+    if (s->batch > h->cfg.max_batch || s->n_buckets > h->cfg.max_items || s->iterations > kMaxIterations ||
+        h->cfg.max_knapsacks < 2)
+        return DEFT_ERR_LIMIT;
+    if (h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;  // Algorithm 1 needs the LDS-resident row
+    if (s->batch == 0) return DEFT_OK;
+
+    DeviceGuard g(h->cfg.device);
+    if (!g.ok) return DEFT_ERR_DEVICE;
+    if (!h->sim_buffers) {
+        const deft_status_t rc = alloc(&h->sim_buffers, schedule_sim_bytes(h->cfg.max_batch, h->cfg.max_items),
+                                       &h->scratch_bytes);
+        if (rc != DEFT_OK) return rc;
+    }
+    hipStream_t st = static_cast<hipStream_t>(s->stream);
+    ScheduleArgs a;
+    a.batch = s->batch;
+    a.n_buckets = s->n_buckets;
+    a.iterations = s->iterations;
+    a.max_capacity = h->cfg.max_capacity;
+    a.comm_time = s->comm_time;
+    a.drop_time = s->drop_time;
+    a.forward_time = s->forward_time;
+    a.backward_time = s->backward_time;
+    a.stage_case = s->stage_case;
+    a.stage_count = s->stage_count;
+    a.stage_time = s->stage_time;
+    a.update_k = s->update_k;
+    a.tail = s->tail;
+    a.status = s->status;
+
+    Profiler *prof = h->profiling ? &h->prof : nullptr;
+    if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
+    const hipError_t e = schedule_sim_launch(h->lds_plan, a, h->sim_buffers, h->keep, st, prof);
     if (prof) prof->end(st);
     if (e != hipSuccess) {
         (void)hipGetLastError();

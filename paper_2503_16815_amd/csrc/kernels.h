@@ -114,6 +114,20 @@ hipError_t joint_prepare(const JointPlan &plan);
 hipError_t joint_launch(const JointPlan &plan, const BatchArgs &args, void *scratch, hipStream_t stream,
                         Profiler *prof);
 
+// ---- the two task queues over several iterations (schedule_sim.hip) -------------
+// Arguments of one simulation call as the kernels see them (all device pointers).
+struct ScheduleArgs {
+    int32_t batch, n_buckets, iterations, max_capacity;
+    const int32_t *comm_time, *drop_time, *forward_time, *backward_time;
+    int32_t *stage_case, *stage_count, *stage_time, *update_k, *tail, *status;
+};
+// Bytes of the handle-owned buffers (queue state and the per-stage solver problem).
+int64_t schedule_sim_bytes(int32_t max_batch, int32_t max_items);
+// Enqueues the whole simulation: per stage a set-up kernel, the Algorithm 1 solver of the
+// LDS path (under `plan`, with its `scratch`), a kernel that applies the answer.
+hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &args, void *sim_buffers, void *scratch,
+                               hipStream_t stream, Profiler *prof);
+
 // ---- the paper's greedy heuristic (greedy.hip) ----------------------------------
 // No scratch memory.  per_link: the two-link weight layout.
 hipError_t greedy_prepare(int32_t max_items);

@@ -44,6 +44,10 @@ def test_binding_struct_layouts_match_header():
     body = re.search(r"typedef struct \{([^}]*)\} deft_knapsack_batch_t;", hdr).group(1)
     fields = re.findall(r"\**\s*([a-z_0-9]+)\s*;", body)
     assert fields == [f[0] for f in b.deft_knapsack_batch_t._fields_]
+    body = re.search(r"typedef struct \{([^}]*)\} deft_schedule_batch_t;", hdr).group(1)
+    fields = re.findall(r"\**\s*([a-z_0-9]+)\s*;", body)
+    assert fields == [f[0] for f in b.deft_schedule_batch_t._fields_]
+    assert ctypes.sizeof(b.deft_schedule_batch_t) == 4 * 4 + 11 * 8
     assert set(b.EXPORTS) == set(declared_functions())
 
 
