@@ -78,13 +78,88 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
     return calls, desc, algo
 
 
+def run_schedule(args) -> int:
+    """The task-queue simulation (Sec. III.B, Cases 1-4) on the ResNet-101 shape: a step is one
+    call simulating every candidate for 8 iterations (16 stages, each one solver launch)."""
+    import torch
+    from oracle import oracle
+    from paper_2503_16815_amd import binding, workloads as W
+
+    sb = W.resnet101_schedules(batch=max(1, int(round(1024 * args.batch_scale))))
+    cap = int(max(sb.backward_time.max(), sb.forward_time.max()))
+    oracle.build()
+    threads = min(os.cpu_count() or 1, 16)
+    # the oracle's recursion costs n DPs per backward stage: it replays a sample of the candidates
+    rows = np.arange(sb.batch) if args.batch_scale < 0.2 else np.linspace(0, sb.batch - 1, 96).astype(int)
+    part = W.ScheduleBatch(name="sample", batch=len(rows), n_buckets=sb.n_buckets, iterations=sb.iterations,
+                           comm_time=sb.comm_time[rows], drop_time=sb.drop_time[rows],
+                           forward_time=sb.forward_time[rows], backward_time=sb.backward_time[rows])
+    t0 = time.perf_counter()
+    ref = oracle.simulate_batch(part, nthreads=threads)
+    t_cpu = time.perf_counter() - t0
+    dev = torch.device("cuda", 0)
+    stream = torch.cuda.Stream(device=dev)
+    with binding.DeftKnapsack(device=0, max_batch=sb.batch, max_items=sb.n_buckets, max_knapsacks=2,
+                              max_capacity=cap) as h:
+        info = h.info()
+        ds = binding.DeviceSchedules(sb, dev)
+        torch.cuda.synchronize(dev)
+        for _ in range(args.warmup):
+            binding.simulate_schedule(h, ds, stream)
+        stream.synchronize()
+        h.set_profiling(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            out = binding.simulate_schedule(h, ds, stream)
+        stream.synchronize()
+        t1 = time.perf_counter()
+        prof = h.get_profile()
+        got = {k: getattr(out, k).cpu().numpy() for k in ("stage_case", "stage_count", "stage_time", "update_k",
+                                                          "tail", "status")}
+    parity = all(np.array_equal(got[k][rows], getattr(ref, k)) for k in got)
+    # cell-updates of the sweeps the solver runs: per stage, sum over the listed buckets of
+    # max(0, window left - time + 1); the lists follow from the records, the oracle counts
+    # them for its sample and the per-candidate mean is applied to the batch
+    cells_step = float(ref.sweep_cells.mean()) * sb.batch
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    sweep_s = float(prof.sweep_ms) * 1e-3
+    launches = int(prof.sweep_launches)
+    achieved = cells_step * args.steps * 8.0 / sweep_s / 1e9 if sweep_s > 0 else 0.0
+    upd = got["update_k"]
+    line = dict(
+        metric="knapsack DP cell-updates/sec", value=cells_step / (ms_step * 1e-3), unit="cell-updates/s", n_gpus=1,
+        steps=args.steps, warmup=args.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
+        vs_baseline=None, dtype="int32", data="synthetic",
+        config=dict(workload=f"task-queue simulation (Cases 1-4), ResNet-101-shaped: {sb.batch} candidates x "
+                             f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%",
+                    candidates_per_step=sb.batch, iterations=sb.iterations,
+                    cell_updates_per_step_estimated_from_sample=cells_step, seq_path=int(info.seq_path),
+                    threads_per_instance=int(info.seq_threads), cells_per_thread=int(info.seq_cells_per_thread),
+                    updates_per_iteration_mean=float((upd > 0).mean()),
+                    buckets_per_iteration_mean=float(got["stage_count"].sum(axis=(1, 2)).mean() / sb.iterations)),
+        candidate_iterations_per_s=sb.batch * sb.iterations / (ms_step * 1e-3), parity_vs_oracle=bool(parity),
+        profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
+                     sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
+        roofline=dict(bound="lds", achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s", frac=achieved / PEAK_LDS_GBS,
+                      traffic=None, kernel="seq_lds_kernel", bytes_per_cell=8.0, launches=launches,
+                      avg_launch_ms=float(prof.sweep_ms) / max(launches, 1)),
+        cpu_baseline=None if args.no_cpu else dict(
+            value=float(ref.sweep_cells.sum()) / t_cpu, unit="cell-updates/s", cores=int(ref.threads), kind="oracle",
+            sample=f"{len(rows)} of the {sb.batch} candidates, all {sb.iterations} iterations, {t_cpu:.2f} s wall "
+                   f"(the oracle solves Algorithm 1 level by level; the figure counts the same one-sweep cells as "
+                   f"the GPU line)",
+            candidate_iterations_per_s=len(rows) * sb.iterations / t_cpu))
+    print(json.dumps(line))
+    return 0 if parity else 3
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet101",
-                    choices=["resnet101", "vgg19", "gpt2", "hetero", "backward", "inflation", "tiny"])
+                    choices=["resnet101", "vgg19", "gpt2", "hetero", "backward", "inflation", "schedule", "tiny"])
     ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
     ap.add_argument("--per-k-calls", action="store_true",
@@ -110,6 +185,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.workload == "schedule":
+        return run_schedule(args)
     calls, desc, algo = make_workload(args.workload, args.batch_scale, args.per_k_calls or bool(args.only_k))
     if args.only_k:
         calls = [kb for kb in calls if kb.meta.get("k") == args.only_k]
