@@ -171,6 +171,8 @@ struct LdsLayout {
     int32_t guard_cells, row_cells, ints_per_inst;
 };
 constexpr int kMiscInts = 8;
+// Second M0 base of the add-TID write-back, in bytes above the first.
+constexpr int kSecondBase = 60416;
 
 // All offered items of one stage, for a row of NB register slots per lane (NB is a
 // compile-time multiple of the chunk size, so the code is straight-line per item).
@@ -214,6 +216,7 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
     lds_sync<T>();  // initial row visible to every lane
 
     const int m0w = uniform((int)row_off + wave_first * 4);
+    const int m0w2 = m0w + kSecondBase;
     // One item.  HEAVY is a compile-time flag and the two kinds run in separate loops
     // below, so that the loop over the (common) light items has a single body and the
     // compiler keeps every cell in one register across iterations.
@@ -259,8 +262,25 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
         lds_sync<T>();  // every lane has read the old row
 
         if constexpr (ADDTID) {
-            m0_settle(m0w);
-            SlotsDown<NB - 1>::all([&](auto kc) { write_addtid<kc.value * T * 4>(m0w, own[kc.value]); });
+            // The instruction's offset and M0's base are 16 bits each: slots whose byte
+            // offset within the row is above 65535 go through a second base, kSecondBase
+            // further up (both bases stay below 65536: the row starts within 5 KB of the
+            // start of LDS); slots beyond the reach of that one are written with addresses.
+            constexpr int kTopSlot = NB - 1;
+            constexpr int kLastLowSlot = 65535 / (T * 4) < kTopSlot ? 65535 / (T * 4) : kTopSlot;
+            SlotsDown<NB - 1>::all([&](auto kc) {
+                constexpr int k = kc.value;
+                constexpr int off = k * T * 4;
+                if constexpr (off <= 65535) {
+                    if constexpr (k == kLastLowSlot) m0_settle(m0w);
+                    write_addtid<off>(m0w, own[k]);
+                } else if constexpr (off - kSecondBase <= 65535) {
+                    if constexpr (k == kTopSlot || off + T * 4 - kSecondBase > 65535) m0_settle(m0w2);
+                    write_addtid<off - kSecondBase>(m0w2, own[k]);
+                } else {
+                    row[k * T + tid] = own[k];
+                }
+            });
         } else {
 #pragma unroll
             for (int k = NB - 1; k >= 0; --k) row[k * T + tid] = own[k];
@@ -334,7 +354,11 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     static_assert(K <= 64, "at most 64 segments per wavefront");
     constexpr int NW = (K + 31) / 32;
     static_assert(K % G == 0, "whole chunks");
-    constexpr bool ADDTID = K * T * 4 <= 65536;  // row offsets fit the 16-bit immediate
+    // add-TID write-back wherever M0 stays below 65536 (one instance per workgroup: the row
+    // starts at most 1 KB into LDS and a wavefront's first lane at most 4 KB further; the
+    // four-instances-per-workgroup variant keeps its rows within 64 KB altogether)
+    constexpr bool ADDTID = true;
+    static_assert(T != 64 || 4 * (256 + K * T) * 4 <= 65536, "rows of the packed variant stay below 64 KB");
     constexpr int NCH = (K + G - 1) / G;
     constexpr int LOG_T = (T == 64) ? 6 : (T == 256) ? 8 : (T == 512) ? 9 : 10;
     static_assert((1 << LOG_T) == T, "T must be 64, 256, 512 or 1024");
@@ -666,7 +690,7 @@ const Variant *variant_table()
     DEFT_VARIANT(256, 32, 4, 4, 256),   // <= 8191
     DEFT_VARIANT(512, 20, 1, 8, 128),   // <= 10239: four workgroups per CU when the row stays under 40 KB
     DEFT_VARIANT(512, 26, 1, 6, 128),   // <= 13311: with the 128-cell guard three workgroups share a CU's LDS
-    DEFT_VARIANT(512, 51, 3, 2, 256),   // <= 26111
+    DEFT_VARIANT(1024, 26, 1, 4, 256),  // <= 26623: sixteen wavefronts on a 104 KB row
     DEFT_VARIANT(1024, 40, 4, 4, 256),  // <= 36863 (36 of the 40 slots: what 160 KB of LDS holds)
     };
     return table;
@@ -695,7 +719,7 @@ hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
     case 2: return launch_one<256, 32, 4, 4, REC>(p, a, scratch, st);
     case 3: return launch_one<512, 20, 1, 8, REC>(p, a, scratch, st);
     case 4: return launch_one<512, 26, 1, 6, REC>(p, a, scratch, st);
-    case 5: return launch_one<512, 51, 3, 2, REC>(p, a, scratch, st);
+    case 5: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st);
     case 6: return launch_one<1024, 40, 4, 4, REC>(p, a, scratch, st);
     default: return hipErrorInvalidValue;
     }

@@ -54,8 +54,9 @@ def test_tiny_single_and_bruteforce_batch(binding, oracle):
     (700, 1023),       # wavefront-per-instance variant
     (3000, 4095),      # 256 x 16
     (8000, 8191),      # 256 x 32
-    (13000, 13055),    # 256 x 51
-    (20000, 26111),    # 512 x 51
+    (10000, 10239),    # 512 x 20
+    (13000, 13055),    # 512 x 26
+    (20000, 26111),    # 1024 x 26
     (33000, 36800),    # 1024 x 40
 ])
 def test_random_ragged_every_lds_variant(binding, oracle, cap_hi, max_capacity):
