@@ -494,6 +494,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         // offered items: not yet placed and able to fit at all, ascending index
         if (!levels && tid < 64) {
             int cnt = 0;
+            long long offered_weight = 0;
             for (int i0 = 0; i0 < n; i0 += 64) {
                 const int i = i0 + tid;
                 const int w = i < n ? W[i] : 0;
@@ -504,14 +505,55 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                     OfferedItem e;
                     e.w = w; e.v = v; e.index = i; e.pad = -1;  // no level ends here
                     list[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = e;
+                    offered_weight += w;
                 }
                 cnt += __popcll(mask);
+            }
+            // Nothing is offered, or everything offered fits together: the DP has nothing to
+            // decide.  Its answer is known: at every step of the walk the capacity left
+            // still holds all earlier items, so an item is taken exactly when its value is
+            // positive (a zero-value item never strictly improves a cell).  The stage is
+            // settled here, without a sweep.  (Not for the capacity sweep: its other
+            // capacities are smaller.)
+            if (!caps_sweep) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) offered_weight += __shfl_down(offered_weight, off);
+                offered_weight = __shfl(offered_weight, 0);
+                if (offered_weight <= C) {
+                    long long vsum = 0, lsum = 0;
+                    for (int i0 = 0; i0 < n; i0 += 64) {
+                        const int i = i0 + tid;
+                        const int w = i < n ? W[i] : 0;
+                        const int v = i < n ? V[i] : 0;
+                        if (i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C && v > 0) {
+                            placed |= 1ull << (i0 >> 6);
+                            out_asg[i] = j;
+                            vsum += v;
+                            lsum += w;
+                        }
+                    }
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) {
+                        vsum += __shfl_down(vsum, off);
+                        lsum += __shfl_down(lsum, off);
+                    }
+                    if (tid == 0) {
+                        out_kv[j] = (int)vsum;
+                        out_kl[j] = (int)lsum;
+                        total += vsum;
+                    }
+                    cnt = -1;  // tells every wavefront that the stage is done
+                }
             }
             if (tid == 0) misc[1] = cnt;
         }
 
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
         global_sync<T>();  // the list (global memory) and the count (LDS) are visible
+        if (uniform(misc[1]) < 0) {  // settled by the set-up
+            lds_sync<T>();           // everyone has read the count before the next stage writes it
+            continue;
+        }
         const int nact = min(uniform(misc[1]), list_stride);
         unsigned long long nzm = 0;
         BestLevel best{0, 0, 0};
