@@ -33,7 +33,8 @@ PEAK_HBM_GBS = 8000.0
 def settled_without_sweep_cells(kb, ref) -> int:
     """Touched cells (as the oracle counts them) of the stages the solver settles without a DP
     sweep: sequential-mode stages whose offered items (not placed by an earlier stage, w <= C)
-    all fit together.  The oracle's assignment says which stage placed what."""
+    all fit together, or number at most six (settled by enumeration).  The oracle's assignment
+    says which stage placed what."""
     if kb.mode != 0:
         return 0
     n = np.arange(kb.item_stride)[None, :] < kb.n_items[:, None]
@@ -48,7 +49,7 @@ def settled_without_sweep_cells(kb, ref) -> int:
         j = order[:, s]
         cap = kb.capacities[rows, j].astype(np.int64)[:, None]
         offered = n & ~placed & (w <= cap) & live[:, None]
-        fits = (w * offered).sum(axis=1) <= cap[:, 0]
+        fits = ((w * offered).sum(axis=1) <= cap[:, 0]) | (offered.sum(axis=1) <= 6)
         cells += int((np.maximum(cap - w + 1, 0) * offered)[fits].sum())
         placed |= (ref.assignment == j[:, None]) & live[:, None]
     return cells

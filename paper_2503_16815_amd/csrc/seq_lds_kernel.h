@@ -171,6 +171,8 @@ struct LdsLayout {
     int32_t guard_cells, row_cells, ints_per_inst;
 };
 constexpr int kMiscInts = 8;
+// Stages that are offered at most this many items are settled by enumeration of their subsets.
+constexpr int kEnumItems = 6;
 // Second M0 base of the add-TID write-back, in bytes above the first.
 constexpr int kSecondBase = 60416;
 
@@ -543,6 +545,57 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                         total += vsum;
                     }
                     cnt = -1;  // tells every wavefront that the stage is done
+                } else if (cnt <= kEnumItems) {
+                    // A handful of offered items: lane L weighs the subset whose members are the
+                    // set bits of L (bit t = the t-th offered item).  The DP with its walk returns
+                    // the feasible subset of greatest value and, among equals, the one with the
+                    // smallest such number; that is picked here directly.
+                    int wq[kEnumItems], vq[kEnumItems], iq[kEnumItems];
+#pragma unroll
+                    for (int t = 0; t < kEnumItems; ++t) { wq[t] = 0; vq[t] = 0; iq[t] = 0; }
+                    int got = 0;
+                    for (int i0 = 0; i0 < n; i0 += 64) {
+                        const int i = i0 + tid;
+                        const int w = i < n ? W[i] : 0;
+                        const int v = i < n ? V[i] : 0;
+                        unsigned long long mask =
+                            __ballot(i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C);
+                        while (mask) {
+                            const int l = __builtin_ctzll(mask);
+                            mask &= mask - 1;
+                            const int wl = __builtin_amdgcn_readlane(w, l), vl = __builtin_amdgcn_readlane(v, l);
+#pragma unroll
+                            for (int t = 0; t < kEnumItems; ++t)
+                                if (t == got) { wq[t] = wl; vq[t] = vl; iq[t] = i0 + l; }
+                            ++got;
+                        }
+                    }
+                    long long ws = 0, vs = 0;
+#pragma unroll
+                    for (int t = 0; t < kEnumItems; ++t)
+                        if ((tid >> t) & 1) { ws += wq[t]; vs += vq[t]; }
+                    const bool feasible = tid < (1 << cnt) && ws <= C;
+                    long long best_value = feasible ? vs : -1;
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) {
+                        const long long other = __shfl_xor(best_value, off);
+                        best_value = other > best_value ? other : best_value;
+                    }
+                    const int pick = __builtin_ctzll(__ballot(feasible && vs == best_value));  // the empty subset is feasible
+                    const long long load = __shfl(ws, pick);
+#pragma unroll
+                    for (int t = 0; t < kEnumItems; ++t) {
+                        if ((pick >> t) & 1) {
+                            if (tid == (iq[t] & 63)) placed |= 1ull << (iq[t] >> 6);
+                            if (tid == 0) out_asg[iq[t]] = j;
+                        }
+                    }
+                    if (tid == 0) {
+                        out_kv[j] = (int)best_value;
+                        out_kl[j] = (int)load;
+                        total += best_value;
+                    }
+                    cnt = -1;
                 }
             }
             if (tid == 0) misc[1] = cnt;
