@@ -458,155 +458,180 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     unsigned long long placed = 0;
     long long total = 0;
     const int stages = caps_sweep ? min(m, 1) : m;
-    for (int s = 0; s < stages; ++s) {
-        const int j = uniform(ord ? ord[s] : s);
+    auto stage_knapsack = [&](int s) { return uniform(ord ? ord[s] : s); };
+    auto stage_capacity = [&](int j) {
         int C = uniform(cap[j]);
         if constexpr (REC) {
             if (caps_sweep) {  // one sweep at the largest capacity serves them all
                 for (int x = 1; x < m; ++x) C = max(C, uniform(cap[x]));
             }
         }
+        return C;
+    };
+    int s = 0;
+    while (true) {
+        // The first wavefront prepares stages one after the other, settling those that need
+        // no sweep on its own, until it reaches one that does; only then do the other
+        // wavefronts of the instance join in.  misc[1] = that stage's offered-item count
+        // (negative: every stage is done), misc[6] = the stage.
+        if (tid < 64) {
+            int cnt = -1;
+            for (; s < stages; ++s) {
+                const int j = stage_knapsack(s);
+                const int C = stage_capacity(j);
+                OfferedItem *list = inst_lists + (size_t)s * list_stride;
+                if (levels) {
+                    // Algorithm 1: the whole list is offered in generation order (an item heavier
+                    // than the remaining time changes nothing, but the levels are counted in list
+                    // positions).  Entry i gets P_i = R - sum of drop[t] over t >= i, the remaining
+                    // time of the level that ends before item i, from a suffix sum taken 64 items
+                    // at a time from the end of the list.
+                    long long behind = 0;  // sum of drop over the chunks already done (uniform)
+                    for (int i0 = (n - 1) & ~63; i0 >= 0 && n > 0; i0 -= 64) {
+                        const int i = i0 + tid;
+                        long long x = i < n ? drop[i] : 0;
+#pragma unroll
+                        for (int off = 1; off < 64; off <<= 1) {
+                            const long long y = __shfl_down(x, off);
+                            if (tid + off < 64) x += y;
+                        }
+                        if (i < n) {
+                            const long long left = (long long)C - (x + behind);
+                            OfferedItem e;
+                            e.w = W[i]; e.v = V[i]; e.index = i; e.pad = left < 0 ? -1 : (int)left;
+                            list[i] = e;
+                        }
+                        behind += __shfl(x, 0);
+                    }
+                    cnt = n;
+                    break;
+                }
+                // offered items: not yet placed and able to fit at all, ascending index
+                cnt = 0;
+                int unplaced = 0;
+                long long offered_weight = 0;
+                for (int i0 = 0; i0 < n; i0 += 64) {
+                    const int i = i0 + tid;
+                    const int w = i < n ? W[i] : 0;
+                    const int v = i < n ? V[i] : 0;
+                    const bool open = i < n && ((placed >> (i0 >> 6)) & 1ull) == 0;
+                    const bool f = open && w <= C;
+                    unplaced += __popcll(__ballot(open));
+                    const unsigned long long mask = __ballot(f);
+                    if (f) {
+                        OfferedItem e;
+                        e.w = w; e.v = v; e.index = i; e.pad = -1;  // no level ends here
+                        list[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = e;
+                        offered_weight += w;
+                    }
+                    cnt += __popcll(mask);
+                }
+                if (unplaced == 0) {  // every item is placed: the remaining stages stay empty
+                    s = stages;
+                    break;
+                }
+                // Nothing is offered, or everything offered fits together: the DP has nothing to
+                // decide.  Its answer is known: at every step of the walk the capacity left
+                // still holds all earlier items, so an item is taken exactly when its value is
+                // positive (a zero-value item never strictly improves a cell).  The stage is
+                // settled here, without a sweep.  (Not for the capacity sweep: its other
+                // capacities are smaller.)
+                if (!caps_sweep) {
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) offered_weight += __shfl_down(offered_weight, off);
+                    offered_weight = __shfl(offered_weight, 0);
+                    if (offered_weight <= C) {
+                        long long vsum = 0, lsum = 0;
+                        for (int i0 = 0; i0 < n; i0 += 64) {
+                            const int i = i0 + tid;
+                            const int w = i < n ? W[i] : 0;
+                            const int v = i < n ? V[i] : 0;
+                            if (i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C && v > 0) {
+                                placed |= 1ull << (i0 >> 6);
+                                out_asg[i] = j;
+                                vsum += v;
+                                lsum += w;
+                            }
+                        }
+#pragma unroll
+                        for (int off = 32; off > 0; off >>= 1) {
+                            vsum += __shfl_down(vsum, off);
+                            lsum += __shfl_down(lsum, off);
+                        }
+                        if (tid == 0) {
+                            out_kv[j] = (int)vsum;
+                            out_kl[j] = (int)lsum;
+                            total += vsum;
+                        }
+                        cnt = -1;  // tells every wavefront that the stage is done
+                    } else if (cnt <= kEnumItems) {
+                        // A handful of offered items: lane L weighs the subset whose members are the
+                        // set bits of L (bit t = the t-th offered item).  The DP with its walk returns
+                        // the feasible subset of greatest value and, among equals, the one with the
+                        // smallest such number; that is picked here directly.
+                        int wq[kEnumItems], vq[kEnumItems], iq[kEnumItems];
+#pragma unroll
+                        for (int t = 0; t < kEnumItems; ++t) { wq[t] = 0; vq[t] = 0; iq[t] = 0; }
+                        int got = 0;
+                        for (int i0 = 0; i0 < n; i0 += 64) {
+                            const int i = i0 + tid;
+                            const int w = i < n ? W[i] : 0;
+                            const int v = i < n ? V[i] : 0;
+                            unsigned long long mask =
+                                __ballot(i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C);
+                            while (mask) {
+                                const int l = __builtin_ctzll(mask);
+                                mask &= mask - 1;
+                                const int wl = __builtin_amdgcn_readlane(w, l), vl = __builtin_amdgcn_readlane(v, l);
+#pragma unroll
+                                for (int t = 0; t < kEnumItems; ++t)
+                                    if (t == got) { wq[t] = wl; vq[t] = vl; iq[t] = i0 + l; }
+                                ++got;
+                            }
+                        }
+                        long long ws = 0, vs = 0;
+#pragma unroll
+                        for (int t = 0; t < kEnumItems; ++t)
+                            if ((tid >> t) & 1) { ws += wq[t]; vs += vq[t]; }
+                        const bool feasible = tid < (1 << cnt) && ws <= C;
+                        long long best_value = feasible ? vs : -1;
+#pragma unroll
+                        for (int off = 32; off > 0; off >>= 1) {
+                            const long long other = __shfl_xor(best_value, off);
+                            best_value = other > best_value ? other : best_value;
+                        }
+                        const int pick = __builtin_ctzll(__ballot(feasible && vs == best_value));  // the empty subset is feasible
+                        const long long load = __shfl(ws, pick);
+#pragma unroll
+                        for (int t = 0; t < kEnumItems; ++t) {
+                            if ((pick >> t) & 1) {
+                                if (tid == (iq[t] & 63)) placed |= 1ull << (iq[t] >> 6);
+                                if (tid == 0) out_asg[iq[t]] = j;
+                            }
+                        }
+                        if (tid == 0) {
+                            out_kv[j] = (int)best_value;
+                            out_kl[j] = (int)load;
+                            total += best_value;
+                        }
+                        cnt = -1;
+                    }
+                }
+                if (cnt >= 0) break;  // this stage needs its sweep
+            }
+            if (tid == 0) {
+                misc[1] = s < stages ? cnt : -1;
+                misc[6] = s;
+            }
+        }
+        global_sync<T>();  // the list (global memory), the count and the stage (LDS) are visible
+        if (uniform(misc[1]) < 0) break;
+        s = uniform(misc[6]);
+        const int j = stage_knapsack(s);
+        const int C = stage_capacity(j);
         OfferedItem *list = inst_lists + (size_t)s * list_stride;
 
-        if (levels && tid < 64) {
-            // Algorithm 1: the whole list is offered in generation order (an item heavier
-            // than the remaining time changes nothing, but the levels are counted in list
-            // positions).  Entry i gets P_i = R - sum of drop[t] over t >= i, the remaining
-            // time of the level that ends before item i, from a suffix sum taken 64 items
-            // at a time from the end of the list.
-            long long behind = 0;  // sum of drop over the chunks already done (uniform)
-            for (int i0 = (n - 1) & ~63; i0 >= 0 && n > 0; i0 -= 64) {
-                const int i = i0 + tid;
-                long long x = i < n ? drop[i] : 0;
-#pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    const long long y = __shfl_down(x, off);
-                    if (tid + off < 64) x += y;
-                }
-                if (i < n) {
-                    const long long left = (long long)C - (x + behind);
-                    OfferedItem e;
-                    e.w = W[i]; e.v = V[i]; e.index = i; e.pad = left < 0 ? -1 : (int)left;
-                    list[i] = e;
-                }
-                behind += __shfl(x, 0);
-            }
-            if (tid == 0) misc[1] = n;
-        }
-        // offered items: not yet placed and able to fit at all, ascending index
-        if (!levels && tid < 64) {
-            int cnt = 0;
-            long long offered_weight = 0;
-            for (int i0 = 0; i0 < n; i0 += 64) {
-                const int i = i0 + tid;
-                const int w = i < n ? W[i] : 0;
-                const int v = i < n ? V[i] : 0;
-                const bool f = i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C;
-                const unsigned long long mask = __ballot(f);
-                if (f) {
-                    OfferedItem e;
-                    e.w = w; e.v = v; e.index = i; e.pad = -1;  // no level ends here
-                    list[cnt + __popcll(mask & ((1ull << tid) - 1ull))] = e;
-                    offered_weight += w;
-                }
-                cnt += __popcll(mask);
-            }
-            // Nothing is offered, or everything offered fits together: the DP has nothing to
-            // decide.  Its answer is known: at every step of the walk the capacity left
-            // still holds all earlier items, so an item is taken exactly when its value is
-            // positive (a zero-value item never strictly improves a cell).  The stage is
-            // settled here, without a sweep.  (Not for the capacity sweep: its other
-            // capacities are smaller.)
-            if (!caps_sweep) {
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) offered_weight += __shfl_down(offered_weight, off);
-                offered_weight = __shfl(offered_weight, 0);
-                if (offered_weight <= C) {
-                    long long vsum = 0, lsum = 0;
-                    for (int i0 = 0; i0 < n; i0 += 64) {
-                        const int i = i0 + tid;
-                        const int w = i < n ? W[i] : 0;
-                        const int v = i < n ? V[i] : 0;
-                        if (i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C && v > 0) {
-                            placed |= 1ull << (i0 >> 6);
-                            out_asg[i] = j;
-                            vsum += v;
-                            lsum += w;
-                        }
-                    }
-#pragma unroll
-                    for (int off = 32; off > 0; off >>= 1) {
-                        vsum += __shfl_down(vsum, off);
-                        lsum += __shfl_down(lsum, off);
-                    }
-                    if (tid == 0) {
-                        out_kv[j] = (int)vsum;
-                        out_kl[j] = (int)lsum;
-                        total += vsum;
-                    }
-                    cnt = -1;  // tells every wavefront that the stage is done
-                } else if (cnt <= kEnumItems) {
-                    // A handful of offered items: lane L weighs the subset whose members are the
-                    // set bits of L (bit t = the t-th offered item).  The DP with its walk returns
-                    // the feasible subset of greatest value and, among equals, the one with the
-                    // smallest such number; that is picked here directly.
-                    int wq[kEnumItems], vq[kEnumItems], iq[kEnumItems];
-#pragma unroll
-                    for (int t = 0; t < kEnumItems; ++t) { wq[t] = 0; vq[t] = 0; iq[t] = 0; }
-                    int got = 0;
-                    for (int i0 = 0; i0 < n; i0 += 64) {
-                        const int i = i0 + tid;
-                        const int w = i < n ? W[i] : 0;
-                        const int v = i < n ? V[i] : 0;
-                        unsigned long long mask =
-                            __ballot(i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C);
-                        while (mask) {
-                            const int l = __builtin_ctzll(mask);
-                            mask &= mask - 1;
-                            const int wl = __builtin_amdgcn_readlane(w, l), vl = __builtin_amdgcn_readlane(v, l);
-#pragma unroll
-                            for (int t = 0; t < kEnumItems; ++t)
-                                if (t == got) { wq[t] = wl; vq[t] = vl; iq[t] = i0 + l; }
-                            ++got;
-                        }
-                    }
-                    long long ws = 0, vs = 0;
-#pragma unroll
-                    for (int t = 0; t < kEnumItems; ++t)
-                        if ((tid >> t) & 1) { ws += wq[t]; vs += vq[t]; }
-                    const bool feasible = tid < (1 << cnt) && ws <= C;
-                    long long best_value = feasible ? vs : -1;
-#pragma unroll
-                    for (int off = 32; off > 0; off >>= 1) {
-                        const long long other = __shfl_xor(best_value, off);
-                        best_value = other > best_value ? other : best_value;
-                    }
-                    const int pick = __builtin_ctzll(__ballot(feasible && vs == best_value));  // the empty subset is feasible
-                    const long long load = __shfl(ws, pick);
-#pragma unroll
-                    for (int t = 0; t < kEnumItems; ++t) {
-                        if ((pick >> t) & 1) {
-                            if (tid == (iq[t] & 63)) placed |= 1ull << (iq[t] >> 6);
-                            if (tid == 0) out_asg[iq[t]] = j;
-                        }
-                    }
-                    if (tid == 0) {
-                        out_kv[j] = (int)best_value;
-                        out_kl[j] = (int)load;
-                        total += best_value;
-                    }
-                    cnt = -1;
-                }
-            }
-            if (tid == 0) misc[1] = cnt;
-        }
-
         const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
-        global_sync<T>();  // the list (global memory) and the count (LDS) are visible
-        if (uniform(misc[1]) < 0) {  // settled by the set-up
-            lds_sync<T>();           // everyone has read the count before the next stage writes it
-            continue;
-        }
         const int nact = min(uniform(misc[1]), list_stride);
         unsigned long long nzm = 0;
         BestLevel best{0, 0, 0};
@@ -763,6 +788,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         }
         total += value;
         lds_sync<T>();
+        ++s;
     }
 
     if (tid == 0) a.total_value[inst] = total;
