@@ -30,11 +30,11 @@ PEAK_INT_LANE_OPS = N_CU * 64 * CLOCK_HZ                              # 39.3e12 
 PEAK_HBM_GBS = 8000.0
 
 
-def settled_without_sweep_cells(kb, ref) -> int:
+def settled_without_sweep_cells(kb, ref, enumerate_small: bool) -> int:
     """Touched cells (as the oracle counts them) of the stages the solver settles without a DP
     sweep: sequential-mode stages whose offered items (not placed by an earlier stage, w <= C)
-    all fit together, or number at most six (settled by enumeration).  The oracle's assignment
-    says which stage placed what."""
+    all fit together, or (LDS-row path only: enumerate_small) number at most six and are settled
+    by enumeration.  The oracle's assignment says which stage placed what."""
     if kb.mode != 0:
         return 0
     n = np.arange(kb.item_stride)[None, :] < kb.n_items[:, None]
@@ -49,7 +49,9 @@ def settled_without_sweep_cells(kb, ref) -> int:
         j = order[:, s]
         cap = kb.capacities[rows, j].astype(np.int64)[:, None]
         offered = n & ~placed & (w <= cap) & live[:, None]
-        fits = ((w * offered).sum(axis=1) <= cap[:, 0]) | (offered.sum(axis=1) <= 6)
+        fits = (w * offered).sum(axis=1) <= cap[:, 0]
+        if enumerate_small:
+            fits |= offered.sum(axis=1) <= 6
         cells += int((np.maximum(cap - w + 1, 0) * offered)[fits].sum())
         placed |= (ref.assignment == j[:, None]) & live[:, None]
     return cells
@@ -246,7 +248,9 @@ def main() -> int:
     table = [int(r.table_cells.sum()) for r in refs]
     # the metric counts the cell-updates the solver performs: stages it settles without a sweep
     # (every offered item fits) are left out, although the oracle sweeps them like any other
-    settled = sum(settled_without_sweep_cells(kb, r) for kb, r in zip(calls, refs))
+    settled_by_path = {small: sum(settled_without_sweep_cells(kb, r, small) for kb, r in zip(calls, refs))
+                       for small in (False, True)}
+    settled = settled_by_path[True]      # corrected below once the handle says which path runs
     cells_step = sum(touched) - settled
     recursion_cells = None
     if calls[0].mode in (2, 5):
@@ -273,6 +277,9 @@ def main() -> int:
     stream = torch.cuda.Stream(device=dev)
     with binding.DeftKnapsack(device=0, **limits) as h:
         info = h.info()
+        if seq and calls[0].mode == 0:
+            settled = settled_by_path[info.seq_path in (1, 2)]
+            cells_step = sum(touched) - settled
         dbs = [h.upload(kb) for kb in calls]
         torch.cuda.synchronize(dev)
 

@@ -93,12 +93,48 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
     const int32_t *asg = a.assignment + (size_t)inst * a.item_stride;
     int32_t *list = act + (size_t)inst * max_items;
     int cnt = 0;
+    long long offered_weight = 0;
     for (int i0 = 0; i0 < n; i0 += 64) {
         const int i = i0 + lane;
         const bool f = i < n && asg[i] < 0 && W[i] <= C;
         const unsigned long long mask = __ballot(f);
-        if (f) list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+        if (f) {
+            list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+            offered_weight += W[i];
+        }
         cnt += __popcll(mask);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) offered_weight += __shfl_down(offered_weight, off);
+    offered_weight = __shfl(offered_weight, 0);
+    if (offered_weight <= C) {
+        // Nothing is offered, or everything offered fits together: the DP and its walk would
+        // take exactly the offered items of positive value (at every step of the walk the
+        // capacity left still holds all earlier items, and a zero-value item never strictly
+        // improves a cell).  The stage is settled here; no sweep, no walk.
+        const int32_t *V = a.values + (size_t)inst * a.item_stride;
+        long long vsum = 0, lsum = 0;
+        for (int i = lane; i < n; i += 64) {
+            const int w = W[i], v = V[i];
+            if (asg[i] < 0 && w <= C && v > 0) {
+                a.assignment[(size_t)inst * a.item_stride + i] = j;
+                vsum += v;
+                lsum += w;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            vsum += __shfl_down(vsum, off);
+            lsum += __shfl_down(lsum, off);
+        }
+        if (lane == 0) {
+            a.knap_value[(size_t)inst * a.knap_stride + j] = (int)vsum;
+            a.knap_load[(size_t)inst * a.knap_stride + j] = (int)lsum;
+            st->total += vsum;
+            a.total_value[inst] = st->total;
+            st->n_act = 0, st->knap = -1, st->buf = -1;
+        }
+        return;
     }
     if (lane == 0) { st->n_act = cnt; st->knap = j; st->cap = C; st->buf = -1; }
 }
