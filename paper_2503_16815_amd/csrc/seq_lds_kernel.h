@@ -812,7 +812,7 @@ const Variant *variant_table()
     DEFT_VARIANT(512, 20, 1, 8, 128),   // <= 10239: four workgroups per CU when the row stays under 40 KB
     DEFT_VARIANT(512, 26, 1, 6, 128),   // <= 13311: with the 128-cell guard three workgroups share a CU's LDS
     DEFT_VARIANT(1024, 26, 1, 4, 256),  // <= 26623: sixteen wavefronts on a 104 KB row
-    DEFT_VARIANT(1024, 40, 4, 4, 256),  // <= 36863 (36 of the 40 slots: what 160 KB of LDS holds)
+    DEFT_VARIANT(1024, 38, 2, 4, 256),  // <= 38911: 153 KB of row, the most that 160 KB of LDS holds with the guard
     };
     return table;
 }
@@ -841,7 +841,7 @@ hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
     case 3: return launch_one<512, 20, 1, 8, REC>(p, a, scratch, st);
     case 4: return launch_one<512, 26, 1, 6, REC>(p, a, scratch, st);
     case 5: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st);
-    case 6: return launch_one<1024, 40, 4, 4, REC>(p, a, scratch, st);
+    case 6: return launch_one<1024, 38, 2, 4, REC>(p, a, scratch, st);
     default: return hipErrorInvalidValue;
     }
 }
