@@ -30,19 +30,25 @@ PEAK_INT_LANE_OPS = N_CU * 64 * CLOCK_HZ                              # 39.3e12 
 PEAK_HBM_GBS = 8000.0
 
 
-def settled_without_sweep_cells(kb, ref, enumerate_small: bool) -> int:
-    """Touched cells (as the oracle counts them) of the stages the solver settles without a DP
-    sweep: sequential-mode stages whose offered items (not placed by an earlier stage, w <= C)
-    all fit together, or (LDS-row path only: enumerate_small) number at most six and are settled
-    by enumeration.  The oracle's assignment says which stage placed what."""
+def cells_not_swept(kb, ref, lds_path: bool):
+    """Touched cells (as the oracle counts them) that the solver never evaluates, for a
+    sequential-mode batch; returns (settled, full):
+    settled - stages settled without a DP sweep: the offered items (not placed by an earlier
+        stage, w <= C) all fit together, or (LDS-row path only) number at most six;
+    full    - (LDS-row path, instances whose values all equal their weights) the items of a swept
+        stage that come after the row is full: after every eighth offered item the solver checks
+        whether every sum 0..C can be reached and ends the stage's sweep if so.  Replayed here
+        with the subset-sum bit recurrence on Python integers.
+    The oracle's assignment says which stage placed what."""
     if kb.mode != 0:
-        return 0
+        return 0, 0
     n = np.arange(kb.item_stride)[None, :] < kb.n_items[:, None]
     m = kb.n_knapsacks
     order = kb.fill_order if kb.fill_order is not None else np.tile(np.arange(kb.knap_stride), (kb.batch, 1))
     placed = np.zeros((kb.batch, kb.item_stride), bool)
     w = kb.weights.astype(np.int64)
-    cells = 0
+    veqw = ((kb.weights == kb.values) | ~n).all(axis=1)
+    settled = full = 0
     rows = np.arange(kb.batch)
     for s in range(kb.knap_stride):
         live = (s < m) & (ref.status == 0)
@@ -50,11 +56,22 @@ def settled_without_sweep_cells(kb, ref, enumerate_small: bool) -> int:
         cap = kb.capacities[rows, j].astype(np.int64)[:, None]
         offered = n & ~placed & (w <= cap) & live[:, None]
         fits = (w * offered).sum(axis=1) <= cap[:, 0]
-        if enumerate_small:
+        if lds_path:
             fits |= offered.sum(axis=1) <= 6
-        cells += int((np.maximum(cap - w + 1, 0) * offered)[fits].sum())
+        settled += int((np.maximum(cap - w + 1, 0) * offered)[fits].sum())
+        if lds_path:
+            for b in np.flatnonzero(~fits & veqw & live):
+                C = int(cap[b, 0])
+                goal = (1 << (C + 1)) - 1
+                bits = 1
+                ws = w[b][offered[b]].tolist()
+                for q, wq in enumerate(ws):
+                    bits |= bits << wq
+                    if q % 8 == 7 and (bits & goal) == goal:
+                        full += sum(C - x + 1 for x in ws[q + 1:])
+                        break
         placed |= (ref.assignment == j[:, None]) & live[:, None]
-    return cells
+    return settled, full
 
 
 def make_workload(name: str, batch_scale: float, per_k_calls: bool):
@@ -246,12 +263,16 @@ def main() -> int:
         t_cpu += time.perf_counter() - t0
     touched = [int(r.touched_cells.sum()) for r in refs]
     table = [int(r.table_cells.sum()) for r in refs]
-    # the metric counts the cell-updates the solver performs: stages it settles without a sweep
-    # (every offered item fits) are left out, although the oracle sweeps them like any other
-    settled_by_path = {small: sum(settled_without_sweep_cells(kb, r, small) for kb, r in zip(calls, refs))
-                       for small in (False, True)}
-    settled = settled_by_path[True]      # corrected below once the handle says which path runs
-    cells_step = sum(touched) - settled
+    # The metric's cell-updates are the oracle's count for the whole job (touched cells of every
+    # stage).  The solver does not evaluate all of them: stages it settles without a sweep and,
+    # where every value equals its weight, the items after the row is full.  The roofline is
+    # priced on the cell-updates it does evaluate (swept_step); both counts are reported.
+    # (and, where every value equals its weight, the items that come after the row is full)
+    not_swept = {path: [cells_not_swept(kb, r, path) for kb, r in zip(calls, refs)] for path in (False, True)}
+    settled = sum(x[0] for x in not_swept[True])     # corrected below once the handle says which path runs
+    after_full = sum(x[1] for x in not_swept[True])
+    cells_step = sum(touched)
+    swept_step = cells_step - settled - after_full
     recursion_cells = None
     if calls[0].mode in (2, 5):
         # Algorithm 1 / capacity sweep: the oracle runs one DP per level / per capacity and counts
@@ -264,6 +285,7 @@ def main() -> int:
             top = kb.capacities[:, :1] if kb.mode == 2 else kb.capacities.max(axis=1, keepdims=True)
             room = top.astype(np.int64) - kb.weights + 1
             cells_step += int((np.maximum(room, 0) * live).sum())
+        swept_step = cells_step
     inst_step = sum(kb.batch for kb in calls)
     if not args.no_cpu:
         cpu_cells = recursion_cells if recursion_cells is not None else sum(touched)   # the oracle sweeps every stage
@@ -278,8 +300,9 @@ def main() -> int:
     with binding.DeftKnapsack(device=0, **limits) as h:
         info = h.info()
         if seq and calls[0].mode == 0:
-            settled = settled_by_path[info.seq_path in (1, 2)]
-            cells_step = sum(touched) - settled
+            settled = sum(x[0] for x in not_swept[info.seq_path in (1, 2)])
+            after_full = sum(x[1] for x in not_swept[info.seq_path in (1, 2)])
+            swept_step = cells_step - settled - after_full
         dbs = [h.upload(kb) for kb in calls]
         torch.cuda.synchronize(dev)
 
@@ -343,13 +366,13 @@ def main() -> int:
     value = cells_step / (ms_step * 1e-3)
     launches = int(prof.sweep_launches)
     sweep_s = float(prof.sweep_ms) * 1e-3
-    algo_bytes_total = cells_step * args.steps * algo["bytes_per_cell"]
+    algo_bytes_total = swept_step * args.steps * algo["bytes_per_cell"]
     if seq and info.seq_path == 3 and int(prof.streamed_row_cells) > 0:
         # rows in global memory: a pass over a row (4 B read + 4 B written per cell) may serve two
         # items; the library counts the row cells it read and wrote, the keep stream is 1/8 B per
         # cell-update
-        algo_bytes_total = int(prof.streamed_row_cells) * 4.0 + cells_step * args.steps / 8.0
-        algo = dict(algo, bytes_per_cell=algo_bytes_total / (cells_step * args.steps))
+        algo_bytes_total = int(prof.streamed_row_cells) * 4.0 + swept_step * args.steps / 8.0
+        algo = dict(algo, bytes_per_cell=algo_bytes_total / (swept_step * args.steps))
     achieved_gbs = algo_bytes_total / sweep_s / 1e9 if sweep_s > 0 else 0.0
     peak = PEAK_LDS_GBS if algo["bound"] == "lds" else PEAK_HBM_GBS
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter passes
@@ -371,20 +394,24 @@ def main() -> int:
         bytes_per_cell=algo["bytes_per_cell"], launches=launches,
         avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
         algorithmic_bytes_per_launch=algo_bytes_total / max(launches, 1),
-        sweep_cell_updates_per_s=cells_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
+        swept_cell_updates_per_s=swept_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
+        frac_if_every_oracle_cell_counted=(cells_step * args.steps * algo["bytes_per_cell"] / sweep_s / 1e9) / peak
+        if sweep_s > 0 and algo["bound"] == "lds" else None,
         alu=dict(ops_per_cell=algo["ops_per_cell"], peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
-                 frac=(cells_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
+                 frac=(swept_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
                  if sweep_s > 0 else 0.0))
     line = dict(
         metric="knapsack DP cell-updates/sec", value=value, unit="cell-updates/s", n_gpus=1,
         steps=args.steps, warmup=args.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype="int32", data="synthetic",
         config=dict(workload=desc, instances_per_step=inst_step, cell_updates_per_step=cells_step,
+                    cell_updates_swept_per_step=swept_step,
                     table_cells_per_step=sum(table), seq_path=int(info.seq_path),
                     threads_per_instance=int(info.seq_threads), cells_per_thread=int(info.seq_cells_per_thread),
                     lds_bytes_per_workgroup=int(info.seq_lds_bytes),
                     workgroups_per_cu=int(info.seq_workgroups_per_cu), scratch_bytes=int(info.scratch_bytes),
                     oracle_cell_updates_of_stages_settled_without_sweep=settled,
+                    oracle_cell_updates_after_the_row_is_full=after_full,
                     same_set_as_one_call_per_k=per_k, oracle_recursion_cell_updates_per_step=recursion_cells),
         instances_per_s=inst_step / (ms_step * 1e-3), parity_vs_oracle=parity,
         profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,

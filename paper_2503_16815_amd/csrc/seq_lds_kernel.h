@@ -187,11 +187,19 @@ constexpr int kSecondBase = 60416;
 // read per item, taken while item q reads the row.  Levels are met deepest first and a
 // shallower one replaces the incumbent only when strictly greater, as the recursion does
 // on its way back up.
-template <int T, int NB, int NW, bool ADDTID, bool VEQW, bool REC>
+//
+// VEQW, sequential mode: once every cell up to C holds its own index (every sum up to the
+// capacity can be reached: the kept value row[c] - c is 0 everywhere) no later item can
+// improve anything, so the sweep ends there.  Checked after every eighth item, between two
+// items: a wavefront that still has an unfinished cell stores the check's tag in
+// `unfinished`, and after a barrier everyone looks at it.
+template <int T, int NB, int G, int NW, bool ADDTID, bool VEQW, bool REC>
 __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
                                             const OfferedItem *list, uint32_t *kp, unsigned long long &nzm,
-                                            BestLevel &best)
+                                            BestLevel &best, int C, int32_t *unfinished)
 {
+    constexpr bool STOP_WHEN_FULL = VEQW && !REC;
+    constexpr int kCheckEvery = 8;
     constexpr int D = NB < 12 ? NB : 12;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
     const int wave_first = tid & ~63;     // first lane of this wavefront within the instance
     // VEQW (every value equals its weight, the paper's Problem 1): the row is kept as
@@ -302,6 +310,26 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
     };
+    // After item q: is the row full?  (The same answer in every lane of the instance.)
+    auto row_is_full = [&](int q) -> bool {
+        if constexpr (!STOP_WHEN_FULL) {
+            return false;
+        } else {
+            if ((q % kCheckEvery) != kCheckEvery - 1) return false;
+            int any = 0;
+#pragma unroll
+            for (int k = 0; k < NB; ++k)  // the cells above C (in the last G slots at most) do not count
+                any |= (k < NB - G || k * T + tid <= C) ? own[k] : 0;
+            const bool wave_full = __builtin_amdgcn_ballot_w64(any != 0) == 0ull;
+            if constexpr (T == 64) {
+                return wave_full;
+            } else {
+                if (!wave_full && (tid & 63) == 0) *unfinished = q + 1;
+                lds_sync<T>();
+                return uniform(*unfinished) != q + 1;
+            }
+        }
+    };
 
     for (int q0 = 0; q0 < nact; q0 += 64) {
         const int2 nxt = load_chunk(q0 + 64);
@@ -312,11 +340,13 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             int w = __builtin_amdgcn_readlane(cur.x, q & 63);
             while (w <= light_max) {  // run of light items
                 item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
+                if (row_is_full(q)) return;
                 if (++q >= q1) break;
                 w = __builtin_amdgcn_readlane(cur.x, q & 63);
             }
             if (q < q1) {  // one heavy item
                 item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
+                if (row_is_full(q)) return;
                 ++q;
             }
         }
@@ -329,13 +359,14 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
 template <int T, int G, int NW, bool ADDTID, bool VEQW, bool REC, int N>
 __device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
                                                int nact, const OfferedItem *list, uint32_t *kp,
-                                               unsigned long long &nzm, BestLevel &best)
+                                               unsigned long long &nzm, BestLevel &best, int C, int32_t *unfinished)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, NW, ADDTID, VEQW, REC>(row, row_off, light_max, tid, nact, list, kp, nzm, best);
+        sweep_stage<T, N * G, G, NW, ADDTID, VEQW, REC>(row, row_off, light_max, tid, nact, list, kp, nzm, best, C,
+                                                     unfinished);
     } else if constexpr (N > 1) {
         sweep_dispatch<T, G, NW, ADDTID, VEQW, REC, N - 1>(nchunk, row, row_off, light_max, tid, nact, list, kp, nzm,
-                                                           best);
+                                                           best, C, unfinished);
     }
 }
 
@@ -374,7 +405,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     int32_t *row = misc + lay.guard_cells;
     const uint32_t row_off = lds_offset(row);
     // misc: [0] fault flags (bit 2: some value differs from its weight), [1] offered-item count,
-    //       [2..3] value sum, [4..5] fill-order seen mask
+    //       [2..3] value sum, [4..5] fill-order seen mask, [6] the stage being swept, [7] tag of the
+    //       last row-is-full check that found an unfinished cell
 
     const int n = a.n_items[inst];
     const int m = a.n_knapsacks[inst];
@@ -622,6 +654,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             if (tid == 0) {
                 misc[1] = s < stages ? cnt : -1;
                 misc[6] = s;
+                misc[7] = 0;  // no check of this stage has run yet
             }
         }
         global_sync<T>();  // the list (global memory), the count and the stage (LDS) are visible
@@ -637,10 +670,10 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         BestLevel best{0, 0, 0};
         if (veqw)
             sweep_dispatch<T, G, NW, ADDTID, true, REC, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid,
-                                                             nact, list, kp, nzm, best);
+                                                             nact, list, kp, nzm, best, C, &misc[7]);
         else
             sweep_dispatch<T, G, NW, ADDTID, false, REC, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid,
-                                                              nact, list, kp, nzm, best);
+                                                              nact, list, kp, nzm, best, C, &misc[7]);
 
         int value = uniform(row[C]) + (veqw ? C : 0);
         // where the walk starts: the last offered item at the full capacity, or (Algorithm 1)
