@@ -193,8 +193,9 @@ constexpr int kSecondBase = 60416;
 // improve anything, so the sweep ends there.  Checked after every eighth item, between two
 // items: a wavefront that still has an unfinished cell stores the check's tag in
 // `unfinished`, and after a barrier everyone looks at it.
+// Returns the number of items swept (the keep rows beyond were never written).
 template <int T, int NB, int G, int NW, bool ADDTID, bool VEQW, bool REC>
-__device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
+__device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
                                             const OfferedItem *list, uint32_t *kp, unsigned long long &nzm,
                                             BestLevel &best, int C, int32_t *unfinished)
 {
@@ -340,34 +341,36 @@ __device__ __forceinline__ void sweep_stage(int32_t *row, uint32_t row_off, int 
             int w = __builtin_amdgcn_readlane(cur.x, q & 63);
             while (w <= light_max) {  // run of light items
                 item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (row_is_full(q)) return;
+                if (row_is_full(q)) return q + 1;
                 if (++q >= q1) break;
                 w = __builtin_amdgcn_readlane(cur.x, q & 63);
             }
             if (q < q1) {  // one heavy item
                 item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (row_is_full(q)) return;
+                if (row_is_full(q)) return q + 1;
                 ++q;
             }
         }
         cur = nxt;
         cur_p = nxt_p;
     }
+    return nact;
 }
 
 // Picks the sweep_stage instance for the stage's chunk count (1 .. N).
 template <int T, int G, int NW, bool ADDTID, bool VEQW, bool REC, int N>
-__device__ __forceinline__ void sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
+__device__ __forceinline__ int sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
                                                int nact, const OfferedItem *list, uint32_t *kp,
                                                unsigned long long &nzm, BestLevel &best, int C, int32_t *unfinished)
 {
     if (nchunk == N) {
-        sweep_stage<T, N * G, G, NW, ADDTID, VEQW, REC>(row, row_off, light_max, tid, nact, list, kp, nzm, best, C,
-                                                     unfinished);
+        return sweep_stage<T, N * G, G, NW, ADDTID, VEQW, REC>(row, row_off, light_max, tid, nact, list, kp, nzm,
+                                                            best, C, unfinished);
     } else if constexpr (N > 1) {
-        sweep_dispatch<T, G, NW, ADDTID, VEQW, REC, N - 1>(nchunk, row, row_off, light_max, tid, nact, list, kp, nzm,
-                                                           best, C, unfinished);
+        return sweep_dispatch<T, G, NW, ADDTID, VEQW, REC, N - 1>(nchunk, row, row_off, light_max, tid, nact, list, kp,
+                                                                  nzm, best, C, unfinished);
     }
+    return 0;
 }
 
 // WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
@@ -632,7 +635,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                             const long long other = __shfl_xor(best_value, off);
                             best_value = other > best_value ? other : best_value;
                         }
-                        const int pick = __builtin_ctzll(__ballot(feasible && vs == best_value));  // the empty subset is feasible
+                        // (the empty subset is always feasible, so the ballot is never empty)
+                        const int pick = __builtin_ctzll(__ballot(feasible && vs == best_value));
                         const long long load = __shfl(ws, pick);
 #pragma unroll
                         for (int t = 0; t < kEnumItems; ++t) {
@@ -668,17 +672,19 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         const int nact = min(uniform(misc[1]), list_stride);
         unsigned long long nzm = 0;
         BestLevel best{0, 0, 0};
+        const int light_max = lay.guard_cells - kMiscInts;
+        int swept;
         if (veqw)
-            sweep_dispatch<T, G, NW, ADDTID, true, REC, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid,
-                                                             nact, list, kp, nzm, best, C, &misc[7]);
+            swept = sweep_dispatch<T, G, NW, ADDTID, true, REC, NCH>(nchunk, row, row_off, light_max, tid, nact, list,
+                                                                     kp, nzm, best, C, &misc[7]);
         else
-            sweep_dispatch<T, G, NW, ADDTID, false, REC, NCH>(nchunk, row, row_off, lay.guard_cells - kMiscInts, tid,
-                                                              nact, list, kp, nzm, best, C, &misc[7]);
+            swept = sweep_dispatch<T, G, NW, ADDTID, false, REC, NCH>(nchunk, row, row_off, light_max, tid, nact, list,
+                                                                      kp, nzm, best, C, &misc[7]);
 
         int value = uniform(row[C]) + (veqw ? C : 0);
         // where the walk starts: the last offered item at the full capacity, or (Algorithm 1)
         // the last item of the best level at that level's remaining time
-        int walk_from = nact - 1, walk_cap = C;
+        int walk_from = swept - 1, walk_cap = C;  // items that were not swept were not taken
         int sweep_cap = 0, sweep_value = 0;  // capacity sweep: lane x holds capacity x and the value there
         if constexpr (REC) {
             if (levels) {
@@ -699,7 +705,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         lds_sync<T>();  // every lane has read its cells of the final row
         int32_t *tb_w = row, *tb_index = row + list_stride;
         unsigned long long *tb_nz = reinterpret_cast<unsigned long long *>(row + 2 * list_stride);
-        for (int i = tid; i < nact; i += T) {
+        for (int i = tid; i < swept; i += T) {
             tb_w[i] = load_item_wv(list + i).x;
             tb_index[i] = load_item_index(list + i);
         }
