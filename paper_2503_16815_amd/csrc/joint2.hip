@@ -108,6 +108,11 @@ jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uin
     const int segs = pitch / 64;
     const int ncol = st.c2 + 1, nrow = st.c1 + 1;
     const int ntile = (ncol + 255) / 256;
+    // A last tile of a single column (capacities that are multiples of 256: C2 + 1 columns)
+    // is not worth a task of its own: the task of the tile before it takes the column along
+    // in one lane.
+    const bool lone_column = ncol > 256 && (ncol & 255) == 1;
+    const int ntile_tasks = lone_column ? ntile - 1 : ntile;
     const size_t tsz = (size_t)rows * pitch;
     const int32_t *W0 = a.weights + (size_t)inst * 2 * a.item_stride;
     const int32_t *W1 = W0 + a.item_stride;
@@ -173,7 +178,7 @@ jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uin
                 // HAS0: the row has a row-shifted operand (ar >= w0).  FULL: all four 64-column
                 // segments of the tile exist and no column needs clamping (straight-line code).
                 auto task = [&](auto in_ring_tag, auto mask_b_tag, auto has0_tag, auto full_tag, int ar, int slot,
-                                int tile) {
+                                int tile, bool with_lone_column) {
                     constexpr bool IN_RING = decltype(in_ring_tag)::value;
                     constexpr bool MASK_B = decltype(mask_b_tag)::value;
                     constexpr bool has0 = decltype(has0_tag)::value;
@@ -230,28 +235,50 @@ jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uin
                             if (jj == j) wsel = (lane & 1) ? m1[jj] : m0[jj];
                         ch[((size_t)ar * segs + tile * 4 + j) * 2 + (lane & 1)] = wsel;
                     }
+                    if (with_lone_column && lane == 0) {  // the row's last column, same tests in the same order
+                        const int col = ncol - 1;
+                        int best = own_row[col];
+                        unsigned long long t0 = 0, t1 = 0;
+                        if (has0) {
+                            const int cand0 =
+                                (IN_RING ? sh_row[col] : (first ? 0 : src[(size_t)(ar - w0) * pitch + col])) + v;
+                            t0 = cand0 > best;
+                            best = max(best, cand0);
+                        }
+                        const int cand1 = col >= w1 ? own_row[col - w1] + v : INT_MIN;
+                        t1 = cand1 > best;
+                        best = max(best, cand1);
+                        t0 &= ~t1;
+                        dst[(size_t)ar * pitch + col] = best;
+                        ch[((size_t)ar * segs + (col >> 6)) * 2] = t0;
+                        ch[((size_t)ar * segs + (col >> 6)) * 2 + 1] = t1;
+                    }
                 };
                 const int nr = min(R, nrow - a0);
                 int r = 0, tile = wave - kLoadWaves;
                 while (true) {
-                    while (tile >= ntile) { tile -= ntile; ++r; }
+                    while (tile >= ntile_tasks) { tile -= ntile_tasks; ++r; }
                     if (r >= nr) break;
                     int slot = slot_a0 + r;
                     if (slot >= ring_rows) slot -= ring_rows;
                     const bool mask_b = tile * 256 < w1, has0 = a0 + r >= w0, full = tile * 256 + 256 <= ncol;
+                    const bool lone = lone_column && tile == ntile_tasks - 1;
                     const std::true_type yes{};
                     const std::false_type no{};
                     const int ar = a0 + r;
+                    auto run = [&](auto in_ring, auto mask, auto has, auto is_full) {
+                        task(in_ring, mask, has, is_full, ar, slot, tile, lone);
+                    };
                     if (!shifted_in_ring || !full) {  // rare shapes: one general instance each
                         if (!shifted_in_ring) {
-                            if (has0) task(no, yes, yes, no, ar, slot, tile); else task(no, yes, no, no, ar, slot, tile);
+                            if (has0) run(no, yes, yes, no); else run(no, yes, no, no);
                         } else {
-                            if (has0) task(yes, yes, yes, no, ar, slot, tile); else task(yes, yes, no, no, ar, slot, tile);
+                            if (has0) run(yes, yes, yes, no); else run(yes, yes, no, no);
                         }
                     } else if (has0) {
-                        if (mask_b) task(yes, yes, yes, yes, ar, slot, tile); else task(yes, no, yes, yes, ar, slot, tile);
+                        if (mask_b) run(yes, yes, yes, yes); else run(yes, no, yes, yes);
                     } else {
-                        if (mask_b) task(yes, yes, no, yes, ar, slot, tile); else task(yes, no, no, yes, ar, slot, tile);
+                        if (mask_b) run(yes, yes, no, yes); else run(yes, no, no, yes);
                     }
                     tile += kComputeWaves;
                 }
