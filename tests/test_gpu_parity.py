@@ -194,3 +194,18 @@ def test_full_size_gpt2_and_two_link(binding, oracle):
     batch at full size: every output of every instance against the oracle."""
     run(binding, oracle, W.gpt2_shaped())
     run(binding, oracle, W.hetero_joint())
+
+
+@pytest.mark.parametrize("seed,n_max,w_hi,cap_hi,ties", [
+    (4001, 12, 9, 30, True),       # few items: enumeration, everything-fits and empty stages
+    (4002, 12, 40, 60, False),
+    (4003, 90, 6, 300, True),      # many small equal-value items: rows fill up long before the list ends
+    (4004, 90, 6, 300, False),     # the same with values that differ from the weights (no early end)
+    (4005, 200, 30, 4000, True),   # 256-lane variant, several 64-entry list chunks, rows that fill up
+])
+def test_stage_shortcuts_randomized(binding, oracle, seed, n_max, w_hi, cap_hi, ties):
+    """Large random batches aimed at the stages that are settled without a sweep (nothing
+    offered, everything fits, at most six items) and at sweeps that end when the row is
+    full, mixed with ordinary stages in one instance; ragged n and m, random fill order."""
+    kb = W.random_sequential(seed, batch=1500, n_max=n_max, m_max=6, w_hi=w_hi, v_hi=50, cap_hi=cap_hi, ties=ties)
+    run(binding, oracle, kb)
