@@ -5,8 +5,10 @@
 // candidates at once, and a second small kernel applies the answer to the queues and
 // writes the stage's record.  Nothing is read back by the host between stages.
 //
-// A plain knapsack is handed to the Algorithm 1 kernels as a list whose drop times exceed
-// any window, so that only the whole list has a non-negative remaining time.
+// Forward stages are plain knapsacks for every candidate and run on the sequential kernels.
+// In a backward stage some candidates pose a plain knapsack and others Algorithm 1; all go
+// to the Algorithm 1 kernels, a plain knapsack as a list whose drop times exceed any
+// window, so that only the whole list has a non-negative remaining time.
 #include "kernels.h"
 
 namespace deft {
@@ -249,7 +251,12 @@ hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &s, vo
         for (int stage = 0; stage < 2; ++stage) {
             hipLaunchKernelGGL(sim_prep, grid, block, 0, st, s, buf, stage);
             if (prof) prof->sweep_begin(st);
-            const hipError_t e = seq_lds_rec_launch(plan, a, scratch, st);
+            // forward stages are plain knapsacks for every candidate (Case 1): the sequential
+            // kernels solve them, with their shortcuts; backward stages mix plain knapsacks and
+            // Algorithm 1 and go to the Algorithm 1 kernels
+            a.mode = stage == 0 ? DEFT_MODE_SEQUENTIAL : DEFT_MODE_RECURSIVE;
+            const hipError_t e = stage == 0 ? seq_lds_launch(plan, a, scratch, st)
+                                            : seq_lds_rec_launch(plan, a, scratch, st);
             if (prof) prof->sweep_end(st);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(sim_post, grid, block, 0, st, s, buf, t, stage);
