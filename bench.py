@@ -168,7 +168,8 @@ def run_schedule(args) -> int:
     ms_step = (t1 - t0) * 1e3 / args.steps
     sweep_s = float(prof.sweep_ms) * 1e-3
     launches = int(prof.sweep_launches)
-    achieved = cells_step * args.steps * 8.0 / sweep_s / 1e9 if sweep_s > 0 else 0.0
+    swept_step = int(prof.swept_cell_updates) // args.steps   # counted by the library: what the sweeps evaluated
+    achieved = swept_step * args.steps * 8.0 / sweep_s / 1e9 if sweep_s > 0 else 0.0
     upd = got["update_k"]
     line = dict(
         metric="knapsack DP cell-updates/sec", value=cells_step / (ms_step * 1e-3), unit="cell-updates/s", n_gpus=1,
@@ -177,7 +178,8 @@ def run_schedule(args) -> int:
         config=dict(workload=f"task-queue simulation (Cases 1-4), ResNet-101-shaped: {sb.batch} candidates x "
                              f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%",
                     candidates_per_step=sb.batch, iterations=sb.iterations,
-                    cell_updates_per_step_estimated_from_sample=cells_step, seq_path=int(info.seq_path),
+                    cell_updates_per_step_estimated_from_sample=cells_step,
+                    cell_updates_swept_per_step=swept_step, seq_path=int(info.seq_path),
                     threads_per_instance=int(info.seq_threads), cells_per_thread=int(info.seq_cells_per_thread),
                     updates_per_iteration_mean=float((upd > 0).mean()),
                     buckets_per_iteration_mean=float(got["stage_count"].sum(axis=(1, 2)).mean() / sb.iterations)),
@@ -364,6 +366,13 @@ def main() -> int:
 
     ms_step = (t1 - t0) * 1e3 / args.steps
     value = cells_step / (ms_step * 1e-3)
+    # rows in LDS: the library counts the cell-updates its sweeps evaluated (C - w + 1 per swept
+    # item); the roofline is priced on that count.  For the sequential mode the same number
+    # follows from the oracle's results and the two rules (swept_step above): both are reported.
+    replayed_swept = swept_step
+    counted_swept = int(prof.swept_cell_updates) // args.steps if seq and info.seq_path in (1, 2) else None
+    if counted_swept is not None:
+        swept_step = counted_swept
     launches = int(prof.sweep_launches)
     sweep_s = float(prof.sweep_ms) * 1e-3
     algo_bytes_total = swept_step * args.steps * algo["bytes_per_cell"]
@@ -406,6 +415,7 @@ def main() -> int:
         vs_baseline=None, dtype="int32", data="synthetic",
         config=dict(workload=desc, instances_per_step=inst_step, cell_updates_per_step=cells_step,
                     cell_updates_swept_per_step=swept_step,
+                    cell_updates_swept_per_step_replayed_from_oracle=replayed_swept if calls[0].mode == 0 else None,
                     table_cells_per_step=sum(table), seq_path=int(info.seq_path),
                     threads_per_instance=int(info.seq_threads), cells_per_thread=int(info.seq_cells_per_thread),
                     lds_bytes_per_workgroup=int(info.seq_lds_bytes),

@@ -269,6 +269,10 @@ typedef struct {
                               sweep: row cells read from plus row cells written to global
                               memory by the sweeps, summed over instances and stages (a
                               pass over a row may serve two items); 0 on the other paths   */
+    int64_t swept_cell_updates; /* rows in LDS (seq_path 1 or 2): cell-updates the sweeps
+                              evaluated, C - w + 1 for every item a stage's sweep went
+                              through (stages settled without a sweep and the items after
+                              a full row add nothing); 0 on the other paths               */
 } deft_knapsack_profile_t;
 
 /* Turn HIP-event timing of solve calls on (1) or off (0); off by default.

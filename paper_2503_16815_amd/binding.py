@@ -58,7 +58,8 @@ class deft_knapsack_info_t(ctypes.Structure):
 
 class deft_knapsack_profile_t(ctypes.Structure):
     _fields_ = [("total_ms", ctypes.c_float), ("sweep_ms", ctypes.c_float), ("sweep_launches", ctypes.c_int32),
-                ("other_ms", ctypes.c_float), ("streamed_row_cells", ctypes.c_int64)]
+                ("other_ms", ctypes.c_float), ("streamed_row_cells", ctypes.c_int64),
+                ("swept_cell_updates", ctypes.c_int64)]
 
 
 _lib = None

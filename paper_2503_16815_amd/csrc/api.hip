@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <initializer_list>
 #include <new>
 #include <vector>
 
@@ -46,6 +47,7 @@ struct deft_knapsack {
     SeqGlobalPlan glob_plan{};
     void *glob_scratch = nullptr;
     unsigned long long *glob_streamed = nullptr;  // device counter read by get_profile
+    unsigned long long *lds_swept = nullptr;      // device counter read by get_profile (LDS path)
 
     void *sim_buffers = nullptr;  // task-queue simulation: allocated by its first call
 
@@ -66,6 +68,7 @@ void free_handle(deft_knapsack *h)
     if (h->keep) (void)hipFree(h->keep);
     if (h->glob_scratch) (void)hipFree(h->glob_scratch);
     if (h->glob_streamed) (void)hipFree(h->glob_streamed);
+    if (h->lds_swept) (void)hipFree(h->lds_swept);
     if (h->joint_scratch) (void)hipFree(h->joint_scratch);
     if (h->sim_buffers) (void)hipFree(h->sim_buffers);
     h->prof.destroy();
@@ -136,6 +139,15 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
             seq_lds_prepare(&h->lds_plan) == hipSuccess && seq_lds_rec_prepare(h->lds_plan) == hipSuccess) {
             h->seq_path = h->lds_plan.threads == 64 ? 1 : 2;
             st = alloc(&h->keep, h->lds_plan.scratch_bytes, &h->scratch_bytes);
+            if (st == DEFT_OK) {
+                void *c = nullptr;
+                st = alloc(&c, 8, &h->scratch_bytes);
+                h->lds_swept = static_cast<unsigned long long *>(c);
+                if (st == DEFT_OK && hipMemset(c, 0, 8) != hipSuccess) {
+                    (void)hipGetLastError();
+                    st = DEFT_ERR_DEVICE;
+                }
+            }
         } else {
             (void)hipGetLastError();
             h->seq_path = 3;
@@ -237,7 +249,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
             e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof, h->glob_streamed);
         } else {
             if (prof) prof->sweep_begin(st);
-            e = seq_lds_launch(h->lds_plan, a, h->keep, st);
+            e = seq_lds_launch(h->lds_plan, a, h->keep, st, prof ? h->lds_swept : nullptr);
             if (prof) prof->sweep_end(st);
         }
     } else if (b->mode == DEFT_MODE_GREEDY || b->mode == DEFT_MODE_GREEDY2) {
@@ -246,7 +258,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         if (prof) prof->sweep_end(st);
     } else if (probing) {
         if (prof) prof->sweep_begin(st);
-        e = seq_lds_rec_launch(h->lds_plan, a, h->keep, st);
+        e = seq_lds_rec_launch(h->lds_plan, a, h->keep, st, prof ? h->lds_swept : nullptr);
         if (prof) prof->sweep_end(st);
     } else {
         e = joint_launch(h->joint_plan, a, h->joint_scratch, st, prof);
@@ -298,7 +310,7 @@ extern "C" deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, con
 
     Profiler *prof = h->profiling ? &h->prof : nullptr;
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
-    const hipError_t e = schedule_sim_launch(h->lds_plan, a, h->sim_buffers, h->keep, st, prof);
+    const hipError_t e = schedule_sim_launch(h->lds_plan, a, h->sim_buffers, h->keep, st, prof, h->lds_swept);
     if (prof) prof->end(st);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -334,9 +346,10 @@ extern "C" deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t
     if (!h) return DEFT_ERR_INVALID_ARG;
     h->profiling = enable != 0;
     h->prof.reset();
-    if (h->glob_streamed) {
+    for (unsigned long long *counter : {h->glob_streamed, h->lds_swept}) {
+        if (!counter) continue;
         DeviceGuard g(h->cfg.device);
-        if (!g.ok || hipMemset(h->glob_streamed, 0, 8) != hipSuccess) {
+        if (!g.ok || hipMemset(counter, 0, 8) != hipSuccess) {
             (void)hipGetLastError();
             return DEFT_ERR_DEVICE;
         }
@@ -351,14 +364,17 @@ extern "C" deft_status_t deft_knapsack_get_profile(deft_knapsack_t *h, deft_knap
     if (!g.ok) return DEFT_ERR_DEVICE;
     deft_status_t rc = h->prof.read(out);   // waits for the last profiled call
     out->streamed_row_cells = 0;
-    if (rc == DEFT_OK && h->glob_streamed) {
+    out->swept_cell_updates = 0;
+    if (rc != DEFT_OK) return rc;
+    for (int which = 0; which < 2; ++which) {
+        unsigned long long *counter = which == 0 ? h->glob_streamed : h->lds_swept;
+        if (!counter) continue;
         unsigned long long v = 0;
-        if (hipMemcpy(&v, h->glob_streamed, 8, hipMemcpyDeviceToHost) != hipSuccess ||
-            hipMemset(h->glob_streamed, 0, 8) != hipSuccess) {
+        if (hipMemcpy(&v, counter, 8, hipMemcpyDeviceToHost) != hipSuccess || hipMemset(counter, 0, 8) != hipSuccess) {
             (void)hipGetLastError();
             return DEFT_ERR_DEVICE;
         }
-        out->streamed_row_cells = (int64_t)v;
+        (which == 0 ? out->streamed_row_cells : out->swept_cell_updates) = (int64_t)v;
     }
     return rc;
 }

@@ -46,12 +46,13 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
                   int32_t lds_per_wg_bytes, SeqLdsPlan *plan);
 // Sets the kernel's dynamic-LDS attribute and queries occupancy.
 hipError_t seq_lds_prepare(SeqLdsPlan *plan);
+// `swept_cells` (device, may be null): every stage adds the cell-updates its sweep evaluated.
 hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
-                          hipStream_t stream);
+                          hipStream_t stream, unsigned long long *swept_cells);
 // Algorithm 1 (recursive mode) under the same plan and scratch (seq_lds_rec.hip).
 hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan);
 hipError_t seq_lds_rec_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
-                              hipStream_t stream);
+                              hipStream_t stream, unsigned long long *swept_cells);
 
 // ---- per-call HIP-event timing (profile.hip) ---------------------------------
 class Profiler {
@@ -126,7 +127,7 @@ int64_t schedule_sim_bytes(int32_t max_batch, int32_t max_items);
 // Enqueues the whole simulation: per stage a set-up kernel, the Algorithm 1 solver of the
 // LDS path (under `plan`, with its `scratch`), a kernel that applies the answer.
 hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &args, void *sim_buffers, void *scratch,
-                               hipStream_t stream, Profiler *prof);
+                               hipStream_t stream, Profiler *prof, unsigned long long *swept_cells);
 
 // ---- the paper's greedy heuristic (greedy.hip) ----------------------------------
 // No scratch memory.  per_link: the two-link weight layout.

@@ -223,7 +223,7 @@ int64_t schedule_sim_bytes(int32_t max_batch, int32_t max_items)
 }
 
 hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &s, void *sim_buffers, void *scratch,
-                               hipStream_t st, Profiler *prof)
+                               hipStream_t st, Profiler *prof, unsigned long long *swept_cells)
 {
     const SimBuffers buf = carve(sim_buffers, s.batch, s.n_buckets);
     BatchArgs a{};
@@ -255,8 +255,8 @@ hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &s, vo
             // kernels solve them, with their shortcuts; backward stages mix plain knapsacks and
             // Algorithm 1 and go to the Algorithm 1 kernels
             a.mode = stage == 0 ? DEFT_MODE_SEQUENTIAL : DEFT_MODE_RECURSIVE;
-            const hipError_t e = stage == 0 ? seq_lds_launch(plan, a, scratch, st)
-                                            : seq_lds_rec_launch(plan, a, scratch, st);
+            const hipError_t e = stage == 0 ? seq_lds_launch(plan, a, scratch, st, prof ? swept_cells : nullptr)
+                                            : seq_lds_rec_launch(plan, a, scratch, st, prof ? swept_cells : nullptr);
             if (prof) prof->sweep_end(st);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(sim_post, grid, block, 0, st, s, buf, t, stage);

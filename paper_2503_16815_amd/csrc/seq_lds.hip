@@ -59,9 +59,10 @@ hipError_t seq_lds_prepare(SeqLdsPlan *plan)
     return plan->wg_per_cu > 0 ? hipSuccess : hipErrorInvalidConfiguration;
 }
 
-hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
+hipError_t seq_lds_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
+                          unsigned long long *swept_cells)
 {
-    return launch_variant<false>(p, a, scratch, st);
+    return launch_variant<false>(p, a, scratch, st, swept_cells);
 }
 
 }  // namespace deft

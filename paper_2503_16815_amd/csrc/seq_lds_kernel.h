@@ -384,7 +384,7 @@ __device__ __forceinline__ int sweep_dispatch(int nchunk, int32_t *row, uint32_t
 template <int T, int K, int G, int WPE, bool REC>
 __global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
 seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, OfferedItem *lists,
-               int list_stride)
+               int list_stride, unsigned long long *swept_cells)
 {
     extern __shared__ __align__(16) int32_t lds_raw[];
     static_assert(K <= 64, "at most 64 segments per wavefront");
@@ -690,7 +690,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             if (levels) {
                 if (value > best.value) best = BestLevel{value, nact, C};  // level 0: the whole list
                 value = best.value;
-                walk_from = best.length - 1;
+                walk_from = min(best.length, swept) - 1;  // what was not swept was not taken
                 walk_cap = best.remain;
             }
             if (caps_sweep && (tid & 63) < m) {
@@ -710,6 +710,15 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             tb_index[i] = load_item_index(list + i);
         }
         tb_nz[tid] = nzm;  // wavefront x, lane l: rows 64 l .. 64 l + 63
+        if (swept_cells && tid < 64) {
+            // measurement only: the cell-updates this stage's sweep evaluated, as the metric
+            // counts them (C - w + 1 per swept item)
+            unsigned long long cells = 0;
+            for (int i = tid; i < swept; i += 64) cells += (unsigned)max(C - load_item_wv(list + i).x + 1, 0);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) cells += __shfl_down(cells, off);
+            if (tid == 0) atomicAdd(swept_cells, cells);
+        }
         global_sync<T>();  // keep words (global memory) and the staged data (LDS) are visible
 
         // One wavefront walks the keep words back from (last offered item, C).  The
@@ -813,7 +822,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             for (int x = tid >> 6; x < m; x += T / 64) {
                 const int at = __builtin_amdgcn_readlane(sweep_cap, x);
                 unsigned long long chosen;
-                const int c = walk(L, nact - 1, at, chosen);
+                const int c = walk(L, swept - 1, at, chosen);
                 while (chosen) {
                     const int b = __builtin_ctzll(chosen);
                     chosen &= chosen - 1;
@@ -859,28 +868,30 @@ const Variant *variant_table()
 constexpr int kNumVariants = 7;
 
 template <int T, int K, int G, int WPE, bool REC>
-hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
+hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
+                      unsigned long long *swept_cells)
 {
     const LdsLayout lay{p.guard_cells, p.row_cells, p.lds_bytes / p.inst_per_wg / 4};
     const unsigned grid = (unsigned)((a.batch + p.inst_per_wg - 1) / p.inst_per_wg);
     uint32_t *keep = static_cast<uint32_t *>(scratch);
     OfferedItem *lists = reinterpret_cast<OfferedItem *>(static_cast<char *>(scratch) + p.keep_bytes);
     hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE, REC>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
-                       a, lay, keep, p.keep_words_per_inst, lists, p.n_pad);
+                       a, lay, keep, p.keep_words_per_inst, lists, p.n_pad, swept_cells);
     return hipGetLastError();
 }
 
 template <bool REC>
-hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
+hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
+                          unsigned long long *swept_cells)
 {
     switch (p.variant) {
-    case 0: return launch_one<64, 16, 4, 5, REC>(p, a, scratch, st);
-    case 1: return launch_one<256, 16, 4, 7, REC>(p, a, scratch, st);
-    case 2: return launch_one<256, 32, 4, 4, REC>(p, a, scratch, st);
-    case 3: return launch_one<512, 20, 1, 8, REC>(p, a, scratch, st);
-    case 4: return launch_one<512, 26, 1, 6, REC>(p, a, scratch, st);
-    case 5: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st);
-    case 6: return launch_one<1024, 38, 2, 4, REC>(p, a, scratch, st);
+    case 0: return launch_one<64, 16, 4, 5, REC>(p, a, scratch, st, swept_cells);
+    case 1: return launch_one<256, 16, 4, 7, REC>(p, a, scratch, st, swept_cells);
+    case 2: return launch_one<256, 32, 4, 4, REC>(p, a, scratch, st, swept_cells);
+    case 3: return launch_one<512, 20, 1, 8, REC>(p, a, scratch, st, swept_cells);
+    case 4: return launch_one<512, 26, 1, 6, REC>(p, a, scratch, st, swept_cells);
+    case 5: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st, swept_cells);
+    case 6: return launch_one<1024, 38, 2, 4, REC>(p, a, scratch, st, swept_cells);
     default: return hipErrorInvalidValue;
     }
 }

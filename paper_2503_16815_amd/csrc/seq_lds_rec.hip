@@ -13,9 +13,10 @@ hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan)
     return nb > 0 ? hipSuccess : hipErrorInvalidConfiguration;
 }
 
-hipError_t seq_lds_rec_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st)
+hipError_t seq_lds_rec_launch(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
+                              unsigned long long *swept_cells)
 {
-    return launch_variant<true>(p, a, scratch, st);
+    return launch_variant<true>(p, a, scratch, st, swept_cells);
 }
 
 }  // namespace deft

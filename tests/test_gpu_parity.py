@@ -209,3 +209,25 @@ def test_stage_shortcuts_randomized(binding, oracle, seed, n_max, w_hi, cap_hi, 
     full, mixed with ordinary stages in one instance; ragged n and m, random fill order."""
     kb = W.random_sequential(seed, batch=1500, n_max=n_max, m_max=6, w_hi=w_hi, v_hi=50, cap_hi=cap_hi, ties=ties)
     run(binding, oracle, kb)
+
+
+def test_swept_cell_counter_matches_the_replay_from_the_oracle(binding, oracle):
+    """The library's count of the cell-updates its sweeps evaluated (measurement only) against
+    the same number derived from the oracle's results and the two rules (stages settled without
+    a sweep, items after a full row), on shapes where both rules fire."""
+    import torch
+    import bench
+    for kb in (W.resnet101_shaped(k=3, batch=96), W.vgg19_shaped(k=4, batch=200),
+               W.random_sequential(4101, batch=300, n_max=90, m_max=5, w_hi=6, v_hi=9, cap_hi=300, ties=True)):
+        ref = oracle.solve_batch(kb, nthreads=16)
+        settled, full = bench.cells_not_swept(kb, ref, True)
+        with binding.DeftKnapsack(max_batch=kb.batch, max_items=kb.item_stride, max_knapsacks=kb.knap_stride,
+                                  max_capacity=max(1, int(kb.capacities.max()))) as h:
+            assert h.info().seq_path in (1, 2)
+            db = h.upload(kb)
+            h.set_profiling(True)
+            out = h.solve_batch(db)
+            torch.cuda.synchronize()
+            prof = h.get_profile()
+            assert_same(kb, out, ref)
+        assert int(prof.swept_cell_updates) == int(ref.touched_cells.sum()) - settled - full, kb.name
