@@ -175,6 +175,8 @@ typedef struct {
  * / required array, batch < 0, strides < 1, bad mode) return INVALID_ARG, counts
  * above the create-time limits or a mode whose limit was 0 return LIMIT, a failed
  * launch returns DEVICE; in all these cases nothing was enqueued.
+ * The call only launches kernels (no allocation, no memset, no host read of device data),
+ * so with profiling off it may be recorded into a HIP graph and replayed.
  */
 deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_batch_t *batch);
 
