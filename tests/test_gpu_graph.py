@@ -37,3 +37,26 @@ def test_solve_batch_replayed_from_a_graph(binding, oracle, max_capacity):
                 graph.replay()
                 torch.cuda.synchronize()
                 assert_same(kb, db.out, ref)
+
+
+def test_two_handles_on_two_streams_at_once(binding, oracle):
+    """Handles share nothing: solves enqueued alternately on two streams, each with its own
+    handle (one with rows in LDS, one with rows in global memory), overlap on the GPU and both
+    match the oracle."""
+    import torch
+    ka = W.resnet101_shaped(k=2, batch=600)
+    kg = W.random_sequential(5100, batch=130, n_max=40, m_max=3, w_hi=9000, v_hi=500, cap_hi=70000)
+    ra, rg = oracle.solve_batch(ka, nthreads=16), oracle.solve_batch(kg, nthreads=16)
+    sa, sg = torch.cuda.Stream(), torch.cuda.Stream()
+    with binding.DeftKnapsack(max_batch=600, max_items=314, max_knapsacks=4,
+                              max_capacity=int(ka.capacities.max())) as ha, \
+            binding.DeftKnapsack(max_batch=130, max_items=40, max_knapsacks=3, max_capacity=70000) as hg:
+        da, dg = ha.upload(ka), hg.upload(kg)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            oa = ha.solve_batch(da, sa)
+            og = hg.solve_batch(dg, sg)
+        sa.synchronize()
+        sg.synchronize()
+        assert_same(ka, oa, ra)
+        assert_same(kg, og, rg)
