@@ -20,14 +20,19 @@
 // INT_MIN (which can never win) sits below the row: for w <= guard size every
 // lane simply reads row[c - w], landing in the guard when c < w.  Heavier items
 // clamp each read index into the guard.
-// Where the row's byte offsets fit 16 bits the write-back uses
-// ds_write_addtid_b32 (address = M0 + immediate + 4 * lane), which ships no
-// address and runs at twice the rate of ds_write_b32; the reads are ordinary
-// loads, so the compiler tracks their completion itself.
+// The write-back uses ds_write_addtid_b32 (address = M0 + immediate + 4 * lane),
+// which ships no address and runs at twice the rate of ds_write_b32 (rows longer
+// than 64 KB through a second M0 base); the reads are ordinary loads, so the
+// compiler tracks their completion itself.
 //
-// After the last item of a stage the same lanes trace the selection back
-// from (last offered item, C) through the keep words just written and mark
-// the chosen items, which the next stage then leaves out.
+// After the last item of a stage one wavefront traces the selection back from
+// (last swept item, C) through the keep words just written and marks the chosen
+// items, which the next stage then leaves out.
+//
+// Not every stage is swept: the first wavefront settles stages that are offered
+// nothing, whose offered items all fit together, or that are offered at most
+// six items, and where every value equals its weight a sweep ends as soon as
+// every sum up to C can be reached.
 //
 // This header holds the kernel and its launcher as templates; seq_lds.hip instantiates
 // them for the sequential mode and seq_lds_rec.hip for Algorithm 1 (REC = true), so the
