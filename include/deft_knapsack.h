@@ -113,7 +113,7 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *                                  (0 = nowhere; also for slots >= n_items and faulted
  *                                  instances)
  *     total_value                  the value at the largest capacity
- *   fill_order is ignored.  Served by handles with seq_path 1 or 2 only (else LIMIT).
+ *   fill_order is ignored.  Served by every handle with max_capacity > 0.
  *
  * DEFT_MODE_GREEDY / DEFT_MODE_GREEDY2 (Sec. III.C, the heuristic of the paper's Solver;
  * here so that the exact modes can be compared with it on the same inputs):

@@ -210,9 +210,10 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         return DEFT_ERR_LIMIT;
     if (!two_link && h->seq_path == 0) return DEFT_ERR_LIMIT;
     if (two_link && h->joint_path == 0) return DEFT_ERR_LIMIT;
-    // Algorithm 1 and the capacity sweep run on the LDS-resident row only
-    const bool probing = b->mode == DEFT_MODE_RECURSIVE || b->mode == DEFT_MODE_CAPACITY_SWEEP;
-    if (probing && h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;
+    // Algorithm 1 runs on the LDS-resident row only; the capacity sweep also on rows in global memory
+    const bool on_lds = h->seq_path == 1 || h->seq_path == 2;
+    if (b->mode == DEFT_MODE_RECURSIVE && !on_lds) return DEFT_ERR_LIMIT;
+    const bool probing = on_lds && (b->mode == DEFT_MODE_RECURSIVE || b->mode == DEFT_MODE_CAPACITY_SWEEP);
     if (b->batch == 0) return DEFT_OK;
 
     DeviceGuard g(h->cfg.device);
@@ -244,7 +245,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
 
     hipError_t e = hipSuccess;
-    if (b->mode == DEFT_MODE_SEQUENTIAL) {
+    if (b->mode == DEFT_MODE_SEQUENTIAL || (b->mode == DEFT_MODE_CAPACITY_SWEEP && !on_lds)) {
         if (h->seq_path == 3) {
             e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof, h->glob_streamed);
         } else {

@@ -19,7 +19,8 @@ __device__ inline int check_instance(const BatchArgs &a, int inst, bool joint)
     const int n = a.n_items[inst], m = a.n_knapsacks[inst];
     uint32_t flags = 0;
     unsigned long long vs = 0;
-    const bool counts_ok = n >= 0 && n <= a.item_stride && m >= 0 && m <= a.knap_stride && (!joint || m == 2);
+    const bool counts_ok = n >= 0 && n <= a.item_stride && m >= 0 && m <= a.knap_stride && (!joint || m == 2) &&
+                           (a.mode != DEFT_MODE_CAPACITY_SWEEP || m <= 31);
     if (!counts_ok) {
         flags = 1;
     } else {
@@ -58,11 +59,13 @@ __device__ inline int check_instance(const BatchArgs &a, int inst, bool joint)
     return status;
 }
 
-// Clears every output slot of the instance and records its status.
+// Clears every output slot of the instance and records its status (assignment: no knapsack,
+// or, for the capacity sweep, the empty mask).
 __device__ inline void clear_outputs(const BatchArgs &a, int inst, int status)
 {
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int i = tid; i < a.item_stride; i += nt) a.assignment[(size_t)inst * a.item_stride + i] = -1;
+    const int none = a.mode == DEFT_MODE_CAPACITY_SWEEP ? 0 : -1;
+    for (int i = tid; i < a.item_stride; i += nt) a.assignment[(size_t)inst * a.item_stride + i] = none;
     for (int j = tid; j < a.knap_stride; j += nt) {
         a.knap_value[(size_t)inst * a.knap_stride + j] = 0;
         a.knap_load[(size_t)inst * a.knap_stride + j] = 0;

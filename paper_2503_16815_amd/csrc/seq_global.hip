@@ -87,8 +87,14 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
         return;
     }
     const int n = a.n_items[inst];
-    const int j = a.fill_order ? a.fill_order[(size_t)inst * a.knap_stride + s] : s;
-    const int C = a.capacities[(size_t)inst * a.knap_stride + j];
+    // Capacity sweep (Sec. IV.C feedback): one stage, swept at the largest of the instance's
+    // capacities; every item is offered and nothing is settled here (the smaller capacities
+    // are read off the same final row).
+    const bool caps_sweep = a.mode == DEFT_MODE_CAPACITY_SWEEP;
+    const int j = caps_sweep ? 0 : a.fill_order ? a.fill_order[(size_t)inst * a.knap_stride + s] : s;
+    int C = a.capacities[(size_t)inst * a.knap_stride + j];
+    if (caps_sweep)
+        for (int x = 1; x < m; ++x) C = max(C, a.capacities[(size_t)inst * a.knap_stride + x]);
     const int32_t *W = a.weights + (size_t)inst * a.item_stride;
     const int32_t *asg = a.assignment + (size_t)inst * a.item_stride;
     int32_t *list = act + (size_t)inst * max_items;
@@ -96,7 +102,7 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
     long long offered_weight = 0;
     for (int i0 = 0; i0 < n; i0 += 64) {
         const int i = i0 + lane;
-        const bool f = i < n && asg[i] < 0 && W[i] <= C;
+        const bool f = i < n && (caps_sweep || asg[i] < 0) && W[i] <= C;
         const unsigned long long mask = __ballot(f);
         if (f) {
             list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = i;
@@ -107,7 +113,7 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) offered_weight += __shfl_down(offered_weight, off);
     offered_weight = __shfl(offered_weight, 0);
-    if (offered_weight <= C) {
+    if (!caps_sweep && offered_weight <= C) {
         // Nothing is offered, or everything offered fits together: the DP and its walk would
         // take exactly the offered items of positive value (at every step of the walk the
         // capacity left still holds all earlier items, and a zero-value item never strictly
@@ -495,6 +501,40 @@ sg_traceback(BatchArgs a, InstState *state, const int32_t *__restrict__ act, con
     a.total_value[inst] = st->total;
 }
 
+// Capacity sweep: one thread per (instance, capacity) reads the value at its capacity off the
+// final row and walks the keep words back from (last offered item, that capacity); an item's
+// output word collects the capacities at which it is taken.
+__global__ void __launch_bounds__(64)
+sg_traceback_caps(BatchArgs a, InstState *state, const int32_t *__restrict__ act, const int32_t *rows,
+                  const uint64_t *keep, int row_len, int keep_words, int max_items)
+{
+    const int idx = blockIdx.x * 64 + threadIdx.x;
+    const int inst = idx / a.knap_stride, j = idx % a.knap_stride;
+    if (inst >= a.batch) return;
+    const InstState *st = &state[inst];
+    if (st->status != DEFT_OK || st->knap < 0 || j >= a.n_knapsacks[inst]) return;
+    const int nact = st->n_act, C = a.capacities[(size_t)inst * a.knap_stride + j];
+    const int32_t *W = a.weights + (size_t)inst * a.item_stride;
+    const int32_t *list = act + (size_t)inst * max_items;
+    int value = 0;
+    if (nact > 0) value = rows[((size_t)inst * 2 + (st->buf >= 0 ? st->buf : (nact & 1))) * row_len + C];
+    int c = C;
+    for (int q = nact - 1; q >= 0; --q) {
+        const int t = list[q];
+        const int w = W[t];
+        if (w <= c) {
+            const uint64_t word = keep[((size_t)inst * max_items + t) * keep_words + (c >> 6)];
+            if ((word >> (c & 63)) & 1ull) {
+                atomicOr(reinterpret_cast<unsigned int *>(&a.assignment[(size_t)inst * a.item_stride + t]), 1u << j);
+                c -= w;
+            }
+        }
+    }
+    a.knap_value[(size_t)inst * a.knap_stride + j] = value;
+    a.knap_load[(size_t)inst * a.knap_stride + j] = C - c;
+    if (C == st->cap) a.total_value[inst] = value;  // the largest capacity (equal ones agree)
+}
+
 }  // namespace
 
 void seq_global_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch, int32_t lds_per_wg_bytes,
@@ -529,7 +569,9 @@ hipError_t seq_global_launch(const SeqGlobalPlan &p, const BatchArgs &a, void *s
     const Scratch s = carve(p, scratch, p.max_batch);
     hipLaunchKernelGGL(sg_init, dim3(a.batch), dim3(kThreads), 0, st, a, s.state);
     const int tiles = p.row_len / kTileCells + (p.row_len % kTileCells ? 1 : 0);
-    for (int stage = 0; stage < a.knap_stride; ++stage) {
+    const bool caps_sweep = a.mode == DEFT_MODE_CAPACITY_SWEEP;
+    const int stages = caps_sweep ? 1 : a.knap_stride;
+    for (int stage = 0; stage < stages; ++stage) {
         hipLaunchKernelGGL(sg_stage_setup, dim3(a.batch), dim3(64), 0, st, a, stage, s.state, s.act,
                            p.max_items);
         if (a.batch >= p.persistent_min_batch) {
@@ -546,8 +588,14 @@ hipError_t seq_global_launch(const SeqGlobalPlan &p, const BatchArgs &a, void *s
                 if (prof) prof->sweep_end(st);
             }
         }
-        hipLaunchKernelGGL(sg_traceback, dim3((a.batch + 63) / 64), dim3(64), 0, st, a, s.state, s.act,
-                           s.rows, s.keep, p.row_len, p.keep_words, p.max_items);
+        if (caps_sweep) {
+            const unsigned walks = (unsigned)a.batch * (unsigned)a.knap_stride;
+            hipLaunchKernelGGL(sg_traceback_caps, dim3((walks + 63) / 64), dim3(64), 0, st, a, s.state, s.act, s.rows,
+                               s.keep, p.row_len, p.keep_words, p.max_items);
+        } else {
+            hipLaunchKernelGGL(sg_traceback, dim3((a.batch + 63) / 64), dim3(64), 0, st, a, s.state, s.act,
+                               s.rows, s.keep, p.row_len, p.keep_words, p.max_items);
+        }
     }
     return hipGetLastError();
 }

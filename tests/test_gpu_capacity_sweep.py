@@ -43,12 +43,19 @@ def test_status_and_degenerate(binding, oracle):
     assert refb.status.tolist() == [1, 0]
 
 
-def test_host_side_limit_on_global_rows(binding):
-    kb = W.random_capacity_sweep(9603, batch=2, n_max=5, m_max=3, w_hi=9, v_hi=9, cap_hi=20)
-    with binding.DeftKnapsack(max_batch=2, max_items=5, max_knapsacks=3, max_capacity=100000) as h:
-        with pytest.raises(binding.DeftError) as e:
-            h.solve_batch(h.upload(kb))
-        assert e.value.code == binding.DEFT_ERR_LIMIT
+def test_rows_in_global_memory(binding, oracle):
+    """Capacities beyond the LDS-resident row: the same mode on the global-row path (one sweep
+    at the largest capacity, one walk per capacity), small batch (tiled sweeps) and a batch
+    large enough for the persistent sweep."""
+    kb = W.random_capacity_sweep(9603, batch=7, n_max=40, m_max=9, w_hi=9000, v_hi=500, cap_hi=70000)
+    run(binding, oracle, kb, max_capacity=70000)
+    kt = W.random_capacity_sweep(9604, batch=160, n_max=30, m_max=5, w_hi=3000, v_hi=9, cap_hi=50000, ties=True)
+    run(binding, oracle, kt, max_capacity=50000)
+    bad = W.random_capacity_sweep(9605, batch=3, n_max=5, m_max=32, w_hi=9, v_hi=9, cap_hi=45000, ragged=False)
+    bad.n_knapsacks[1] = 31
+    bad.weights[2, 0] = 0
+    ref = run(binding, oracle, bad, max_capacity=45000)
+    assert ref.status.tolist() == [1, 0, 1]
 
 
 def test_inflation_sweep_at_paper_shape(binding, oracle):
