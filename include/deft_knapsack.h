@@ -98,8 +98,8 @@ deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knaps
  *     knap_value[1]                d of the level returned (n if nothing is scheduled)
  *     knap_load[1]                 that level's remaining time (0 if nothing is scheduled)
  *     assignment                   0 for scheduled items, else -1
- *   fill_order is ignored.  Only handles whose max_capacity fits the LDS-resident row
- *   (seq_path 1 or 2) serve this mode; others return LIMIT from the call.
+ *   fill_order is ignored.  Served by every handle with max_capacity > 0 (with rows in
+ *   global memory, seq_path 3, at one kernel launch per item).
  *
  * DEFT_MODE_CAPACITY_SWEEP (Sec. IV.C, the feedback mechanism: the Solver is called again
  * with a larger knapsack capacity, up to ten times):
@@ -220,8 +220,8 @@ deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const deft_knapsack_
  * The call enqueues everything on `stream` and returns; its first use on a handle
  * allocates the queue state (sized for max_batch x max_items; OOM if that fails).
  * Host-side errors: INVALID_ARG (NULL, batch < 0, n_buckets < 1, iterations < 1), LIMIT
- * (above the create-time limits, iterations > 4096, max_knapsacks < 2, or a handle whose
- * rows do not fit LDS: seq_path 3), DEVICE.
+ * (above the create-time limits, iterations > 4096, max_knapsacks < 2, max_capacity == 0),
+ * DEVICE.
  */
 typedef struct {
     int32_t batch;

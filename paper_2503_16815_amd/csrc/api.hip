@@ -210,10 +210,10 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         return DEFT_ERR_LIMIT;
     if (!two_link && h->seq_path == 0) return DEFT_ERR_LIMIT;
     if (two_link && h->joint_path == 0) return DEFT_ERR_LIMIT;
-    // Algorithm 1 runs on the LDS-resident row only; the capacity sweep also on rows in global memory
+    // Algorithm 1 and the capacity sweep have kernels of their own on the LDS-resident row and
+    // ride on the sequential mode's kernels when rows live in global memory
     const bool on_lds = h->seq_path == 1 || h->seq_path == 2;
-    if (b->mode == DEFT_MODE_RECURSIVE && !on_lds) return DEFT_ERR_LIMIT;
-    const bool probing = on_lds && (b->mode == DEFT_MODE_RECURSIVE || b->mode == DEFT_MODE_CAPACITY_SWEEP);
+    const bool probing = b->mode == DEFT_MODE_RECURSIVE || b->mode == DEFT_MODE_CAPACITY_SWEEP;
     if (b->batch == 0) return DEFT_OK;
 
     DeviceGuard g(h->cfg.device);
@@ -245,7 +245,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
 
     hipError_t e = hipSuccess;
-    if (b->mode == DEFT_MODE_SEQUENTIAL || (b->mode == DEFT_MODE_CAPACITY_SWEEP && !on_lds)) {
+    if (b->mode == DEFT_MODE_SEQUENTIAL || (probing && !on_lds)) {
         if (h->seq_path == 3) {
             e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof, h->glob_streamed);
         } else {
@@ -257,7 +257,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         if (prof) prof->sweep_begin(st);
         e = greedy_launch(a, two_link, st);
         if (prof) prof->sweep_end(st);
-    } else if (probing) {
+    } else if (probing) {  // on the LDS-resident row
         if (prof) prof->sweep_begin(st);
         e = seq_lds_rec_launch(h->lds_plan, a, h->keep, st, prof ? h->lds_swept : nullptr);
         if (prof) prof->sweep_end(st);
@@ -282,7 +282,7 @@ extern "C" deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, con
     if (s->batch > h->cfg.max_batch || s->n_buckets > h->cfg.max_items || s->iterations > kMaxIterations ||
         h->cfg.max_knapsacks < 2)
         return DEFT_ERR_LIMIT;
-    if (h->seq_path != 1 && h->seq_path != 2) return DEFT_ERR_LIMIT;  // Algorithm 1 needs the LDS-resident row
+    if (h->seq_path == 0) return DEFT_ERR_LIMIT;
     if (s->batch == 0) return DEFT_OK;
 
     DeviceGuard g(h->cfg.device);
@@ -311,7 +311,16 @@ extern "C" deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, con
 
     Profiler *prof = h->profiling ? &h->prof : nullptr;
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
-    const hipError_t e = schedule_sim_launch(h->lds_plan, a, h->sim_buffers, h->keep, st, prof, h->lds_swept);
+    const auto solve = [&](const BatchArgs &x) -> hipError_t {
+        if (h->seq_path == 3) return seq_global_launch(h->glob_plan, x, h->glob_scratch, st, prof, h->glob_streamed);
+        if (prof) prof->sweep_begin(st);
+        const hipError_t rc = x.mode == DEFT_MODE_SEQUENTIAL
+                                  ? seq_lds_launch(h->lds_plan, x, h->keep, st, prof ? h->lds_swept : nullptr)
+                                  : seq_lds_rec_launch(h->lds_plan, x, h->keep, st, prof ? h->lds_swept : nullptr);
+        if (prof) prof->sweep_end(st);
+        return rc;
+    };
+    const hipError_t e = schedule_sim_launch(a, h->sim_buffers, st, solve);
     if (prof) prof->end(st);
     if (e != hipSuccess) {
         (void)hipGetLastError();

@@ -20,7 +20,7 @@ __device__ inline int check_instance(const BatchArgs &a, int inst, bool joint)
     uint32_t flags = 0;
     unsigned long long vs = 0;
     const bool counts_ok = n >= 0 && n <= a.item_stride && m >= 0 && m <= a.knap_stride && (!joint || m == 2) &&
-                           (a.mode != DEFT_MODE_CAPACITY_SWEEP || m <= 31);
+                           (a.mode != DEFT_MODE_CAPACITY_SWEEP || m <= 31) && (a.mode != DEFT_MODE_RECURSIVE || m == 1);
     if (!counts_ok) {
         flags = 1;
     } else {
@@ -32,6 +32,7 @@ __device__ inline int check_instance(const BatchArgs &a, int inst, bool joint)
             const int v = V[i];
             bool bad = W[i] < 1 || v < 0;
             if (joint) bad = bad || W[a.item_stride + i] < 1;
+            if (a.mode == DEFT_MODE_RECURSIVE) bad = bad || a.drop_time[(size_t)inst * a.item_stride + i] < 0;
             if (bad) flags |= 1; else vs += (unsigned)v;
         }
         for (int j = tid; j < m; j += nt) {

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <functional>
+
 #include "../../include/deft_knapsack.h"
 
 namespace deft {
@@ -124,10 +126,11 @@ struct ScheduleArgs {
 };
 // Bytes of the handle-owned buffers (queue state and the per-stage solver problem).
 int64_t schedule_sim_bytes(int32_t max_batch, int32_t max_items);
-// Enqueues the whole simulation: per stage a set-up kernel, the Algorithm 1 solver of the
-// LDS path (under `plan`, with its `scratch`), a kernel that applies the answer.
-hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &args, void *sim_buffers, void *scratch,
-                               hipStream_t stream, Profiler *prof, unsigned long long *swept_cells);
+// Enqueues the whole simulation: per stage a set-up kernel, the solver (`solve` enqueues one
+// batch in args.mode = DEFT_MODE_SEQUENTIAL or DEFT_MODE_RECURSIVE on the handle's path), a
+// kernel that applies the answer.
+hipError_t schedule_sim_launch(const ScheduleArgs &args, void *sim_buffers, hipStream_t stream,
+                               const std::function<hipError_t(const BatchArgs &)> &solve);
 
 // ---- the paper's greedy heuristic (greedy.hip) ----------------------------------
 // No scratch memory.  per_link: the two-link weight layout.

@@ -1,14 +1,14 @@
 // The two task queues of Sec. III.B (Cases 1-4) simulated over several iterations for a
 // batch of candidate schedules, entirely on the device: per stage a small kernel turns
 // each candidate's queue state into one knapsack problem (the list, the window, and
-// whether the stage is a plain knapsack or Algorithm 1), the LDS-row solver runs on all
-// candidates at once, and a second small kernel applies the answer to the queues and
+// whether the stage is a plain knapsack or Algorithm 1), the solver runs on all candidates
+// at once, and a second small kernel applies the answer to the queues and
 // writes the stage's record.  Nothing is read back by the host between stages.
 //
-// Forward stages are plain knapsacks for every candidate and run on the sequential kernels.
+// Forward stages are plain knapsacks for every candidate and run in the sequential mode.
 // In a backward stage some candidates pose a plain knapsack and others Algorithm 1; all go
-// to the Algorithm 1 kernels, a plain knapsack as a list whose drop times exceed any
-// window, so that only the whole list has a non-negative remaining time.
+// to the recursive mode, a plain knapsack as a list whose drop times exceed any window,
+// so that only the whole list has a non-negative remaining time.
 #include "kernels.h"
 
 namespace deft {
@@ -222,8 +222,8 @@ int64_t schedule_sim_bytes(int32_t max_batch, int32_t max_items)
     return b * (8 + kStateWords * 4 + 4 + 4 + 8 + 8 + 8 + 4) + b * n * 17 + 13 * 256;
 }
 
-hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &s, void *sim_buffers, void *scratch,
-                               hipStream_t st, Profiler *prof, unsigned long long *swept_cells)
+hipError_t schedule_sim_launch(const ScheduleArgs &s, void *sim_buffers, hipStream_t st,
+                               const std::function<hipError_t(const BatchArgs &)> &solve)
 {
     const SimBuffers buf = carve(sim_buffers, s.batch, s.n_buckets);
     BatchArgs a{};
@@ -250,14 +250,11 @@ hipError_t schedule_sim_launch(const SeqLdsPlan &plan, const ScheduleArgs &s, vo
     for (int t = 0; t < s.iterations; ++t) {
         for (int stage = 0; stage < 2; ++stage) {
             hipLaunchKernelGGL(sim_prep, grid, block, 0, st, s, buf, stage);
-            if (prof) prof->sweep_begin(st);
             // forward stages are plain knapsacks for every candidate (Case 1): the sequential
-            // kernels solve them, with their shortcuts; backward stages mix plain knapsacks and
-            // Algorithm 1 and go to the Algorithm 1 kernels
+            // mode solves them, with its shortcuts; backward stages mix plain knapsacks and
+            // Algorithm 1 and go to the recursive mode
             a.mode = stage == 0 ? DEFT_MODE_SEQUENTIAL : DEFT_MODE_RECURSIVE;
-            const hipError_t e = stage == 0 ? seq_lds_launch(plan, a, scratch, st, prof ? swept_cells : nullptr)
-                                            : seq_lds_rec_launch(plan, a, scratch, st, prof ? swept_cells : nullptr);
-            if (prof) prof->sweep_end(st);
+            const hipError_t e = solve(a);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(sim_post, grid, block, 0, st, s, buf, t, stage);
         }

@@ -36,13 +36,15 @@ struct InstState {
     int32_t status, n_act, knap, cap;
     int64_t total;
     int32_t buf;   // row buffer holding the stage's final row; -1: the parity of n_act says
-    int32_t pad;
+    // Algorithm 1: the best level met so far (its value, the length of its list, its remaining time)
+    int32_t best_value, best_length, best_remain;
 };
 
 struct Scratch {
     int32_t *rows;      // [batch][2][row_len]
     uint64_t *keep;     // [batch][max_items][keep_words]
     int32_t *act;       // [batch][max_items]
+    int32_t *probe;     // [batch][max_items]  Algorithm 1: remaining time of the level that ends before entry q
     InstState *state;   // [batch]
 };
 
@@ -57,6 +59,8 @@ Scratch carve(const SeqGlobalPlan &p, void *base, int32_t max_batch)
     s.keep = reinterpret_cast<uint64_t *>(c);
     c += align256((size_t)max_batch * p.max_items * p.keep_words * 8);
     s.act = reinterpret_cast<int32_t *>(c);
+    c += align256((size_t)max_batch * p.max_items * 4);
+    s.probe = reinterpret_cast<int32_t *>(c);
     c += align256((size_t)max_batch * p.max_items * 4);
     s.state = reinterpret_cast<InstState *>(c);
     return s;
@@ -76,6 +80,43 @@ __global__ void __launch_bounds__(kThreads) sg_init(BatchArgs a, InstState *stat
 
 // Stage s: knapsack id, capacity and the ascending list of offered items
 // (not yet placed, weight <= capacity).
+// Algorithm 1 (one stage): the whole list is offered in its order, and entry q gets the
+// remaining time of the level that ends before it, R - sum of drop_time over the entries
+// from q on (-1 if negative), from a suffix sum taken 64 entries at a time from the end.
+__global__ void __launch_bounds__(64) sg_levels_setup(BatchArgs a, InstState *state, int32_t *act, int32_t *probe,
+                                                      int max_items)
+{
+    const int inst = blockIdx.x, lane = threadIdx.x;
+    InstState *st = &state[inst];
+    if (st->status != DEFT_OK) {
+        if (lane == 0) st->n_act = 0, st->knap = -1, st->buf = -1;
+        return;
+    }
+    const int n = a.n_items[inst];
+    const int C = a.capacities[(size_t)inst * a.knap_stride];
+    const int32_t *drop = a.drop_time + (size_t)inst * a.item_stride;
+    long long behind = 0;
+    for (int i0 = (n - 1) & ~63; i0 >= 0 && n > 0; i0 -= 64) {
+        const int i = i0 + lane;
+        long long x = i < n ? drop[i] : 0;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const long long y = __shfl_down(x, off);
+            if (lane + off < 64) x += y;
+        }
+        if (i < n) {
+            const long long left = (long long)C - (x + behind);
+            act[(size_t)inst * max_items + i] = i;
+            probe[(size_t)inst * max_items + i] = left < 0 ? -1 : (int)left;
+        }
+        behind += __shfl(x, 0);
+    }
+    if (lane == 0) {
+        st->n_act = n; st->knap = 0; st->cap = C; st->buf = -1;
+        st->best_value = 0; st->best_length = 0; st->best_remain = 0;
+    }
+}
+
 __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstState *state, int32_t *act,
                                                      int max_items)
 {
@@ -147,13 +188,28 @@ __global__ void __launch_bounds__(64) sg_stage_setup(BatchArgs a, int s, InstSta
 
 // Offered item q of every instance: one pass over the row.
 __global__ void __launch_bounds__(kThreads)
-sg_sweep(BatchArgs a, int q, const InstState *__restrict__ state, const int32_t *__restrict__ act,
+sg_sweep(BatchArgs a, int q, InstState *state, const int32_t *__restrict__ act, const int32_t *__restrict__ probe,
          int32_t *rows, uint64_t *keep, int row_len, int keep_words, int max_items, int tiles)
 {
     const int inst = blockIdx.x / tiles, tile = blockIdx.x % tiles;
     const InstState st = state[inst];
     if (q >= st.n_act) return;
     const int C = st.cap;
+    if (a.mode == DEFT_MODE_RECURSIVE && tile == 0 && threadIdx.x == 0 && q > 0) {
+        // Algorithm 1: the row before item q is the row of the level that ends here; a
+        // shallower level replaces the best one only when strictly greater.  (Nobody else
+        // touches the instance's best level during this launch; before the first item the
+        // row is all zero and cannot win.)
+        const int at = probe[(size_t)inst * max_items + q];
+        if (at >= 0) {
+            const int level_value = rows[((size_t)inst * 2 + (q & 1)) * row_len + at];
+            if (level_value > st.best_value) {
+                state[inst].best_value = level_value;
+                state[inst].best_length = q;
+                state[inst].best_remain = at;
+            }
+        }
+    }
     const int lane = threadIdx.x & 63;
     const int wave_base = (tile * (kThreads / 64) + (threadIdx.x >> 6)) * kWaveCells;
     if (wave_base > C) return;
@@ -483,8 +539,18 @@ sg_traceback(BatchArgs a, InstState *state, const int32_t *__restrict__ act, con
     const int32_t *list = act + (size_t)inst * max_items;
     int value = 0;
     if (nact > 0) value = rows[((size_t)inst * 2 + (st->buf >= 0 ? st->buf : (nact & 1))) * row_len + C];
-    int c = C;
-    for (int q = nact - 1; q >= 0; --q) {
+    int c = C, from = nact - 1;
+    const bool levels = a.mode == DEFT_MODE_RECURSIVE;
+    int length = nact;
+    if (levels) {  // the whole list is the last level met; the walk starts at the best level's end
+        if (value > st->best_value) { st->best_value = value; st->best_length = nact; st->best_remain = C; }
+        value = st->best_value;
+        length = st->best_length;
+        from = length - 1;
+        c = st->best_remain;
+    }
+    const int start = c;
+    for (int q = from; q >= 0; --q) {
         const int t = list[q];
         const int w = W[t];
         if (w <= c) {
@@ -496,7 +562,11 @@ sg_traceback(BatchArgs a, InstState *state, const int32_t *__restrict__ act, con
         }
     }
     a.knap_value[(size_t)inst * a.knap_stride + j] = value;
-    a.knap_load[(size_t)inst * a.knap_stride + j] = C - c;
+    a.knap_load[(size_t)inst * a.knap_stride + j] = start - c;
+    if (levels) {  // slot 1 reports the level: items left off the list, its remaining time
+        a.knap_value[(size_t)inst * a.knap_stride + 1] = a.n_items[inst] - length;
+        a.knap_load[(size_t)inst * a.knap_stride + 1] = value > 0 ? start : 0;
+    }
     st->total += value;
     a.total_value[inst] = st->total;
 }
@@ -553,7 +623,7 @@ void seq_global_plan(int32_t max_capacity, int32_t max_items, int32_t max_batch,
     p->max_batch = max_batch;
     p->scratch_bytes = (int64_t)(align256((size_t)max_batch * 2 * p->row_len * 4) +
                                  align256((size_t)max_batch * max_items * p->keep_words * 8) +
-                                 align256((size_t)max_batch * max_items * 4) +
+                                 2 * align256((size_t)max_batch * max_items * 4) +
                                  align256((size_t)max_batch * sizeof(InstState)));
 }
 
@@ -569,12 +639,16 @@ hipError_t seq_global_launch(const SeqGlobalPlan &p, const BatchArgs &a, void *s
     const Scratch s = carve(p, scratch, p.max_batch);
     hipLaunchKernelGGL(sg_init, dim3(a.batch), dim3(kThreads), 0, st, a, s.state);
     const int tiles = p.row_len / kTileCells + (p.row_len % kTileCells ? 1 : 0);
-    const bool caps_sweep = a.mode == DEFT_MODE_CAPACITY_SWEEP;
-    const int stages = caps_sweep ? 1 : a.knap_stride;
+    const bool caps_sweep = a.mode == DEFT_MODE_CAPACITY_SWEEP, levels = a.mode == DEFT_MODE_RECURSIVE;
+    const int stages = caps_sweep || levels ? 1 : a.knap_stride;
     for (int stage = 0; stage < stages; ++stage) {
-        hipLaunchKernelGGL(sg_stage_setup, dim3(a.batch), dim3(64), 0, st, a, stage, s.state, s.act,
-                           p.max_items);
-        if (a.batch >= p.persistent_min_batch) {
+        if (levels)
+            hipLaunchKernelGGL(sg_levels_setup, dim3(a.batch), dim3(64), 0, st, a, s.state, s.act, s.probe, p.max_items);
+        else
+            hipLaunchKernelGGL(sg_stage_setup, dim3(a.batch), dim3(64), 0, st, a, stage, s.state, s.act, p.max_items);
+        // Algorithm 1 reads one cell of every intermediate row, so it takes the sweeps that
+        // leave each of them in global memory (one launch per item)
+        if (a.batch >= p.persistent_min_batch && !levels) {
             if (prof) prof->sweep_begin(st);
             hipLaunchKernelGGL(sg_sweep_all, dim3((unsigned)a.batch), dim3(kAllThreads), (size_t)p.lds_bytes, st, a,
                                s.state, s.act, s.rows, s.keep, p.row_len, p.keep_words, p.max_items, p.ring_segs,
@@ -584,7 +658,8 @@ hipError_t seq_global_launch(const SeqGlobalPlan &p, const BatchArgs &a, void *s
             for (int q = 0; q < a.item_stride; ++q) {
                 if (prof) prof->sweep_begin(st);
                 hipLaunchKernelGGL(sg_sweep, dim3((unsigned)tiles * (unsigned)a.batch), dim3(kThreads), 0, st, a, q,
-                                   s.state, s.act, s.rows, s.keep, p.row_len, p.keep_words, p.max_items, tiles);
+                                   s.state, s.act, s.probe, s.rows, s.keep, p.row_len, p.keep_words, p.max_items,
+                                   tiles);
                 if (prof) prof->sweep_end(st);
             }
         }

@@ -53,15 +53,24 @@ def test_status_and_degenerate(binding, oracle):
     assert ref.status.tolist() == [0, 0, 1, 1, 2, 3, 0, 0]
 
 
+def test_rows_in_global_memory(binding, oracle):
+    """Remaining times beyond the LDS-resident row: the same mode on the global-row path (one
+    launch per item, the level read off the row each launch starts from)."""
+    kb = W.random_recursive(7201, batch=9, n_max=40, w_hi=9000, v_hi=500, cap_hi=70000, t_hi=900)
+    run(binding, oracle, kb, max_capacity=70000)
+    kt = W.random_recursive(7202, batch=140, n_max=30, w_hi=3000, v_hi=9, cap_hi=50000, t_hi=300, ties=True)
+    run(binding, oracle, kt, max_capacity=50000)
+    bad = W.random_recursive(7203, batch=4, n_max=6, w_hi=9, v_hi=9, cap_hi=45000, t_hi=3, ragged=False)
+    bad.drop_time[1, 2] = -1
+    bad.n_knapsacks[2] = 2
+    bad.n_items[3] = 0
+    ref = run(binding, oracle, bad, max_capacity=45000)
+    assert ref.status.tolist() == [0, 1, 1, 0]
+
+
 def test_host_side_errors(binding):
-    """A handle whose rows live in global memory does not serve this mode (LIMIT), and a
-    missing drop_time array is INVALID_ARG; nothing is enqueued in either case."""
-    kb = W.random_recursive(7201, batch=4, n_max=12, w_hi=9, v_hi=9, cap_hi=30, t_hi=3)
-    with binding.DeftKnapsack(max_batch=4, max_items=12, max_knapsacks=2, max_capacity=100000) as h:
-        assert h.info().seq_path == 3
-        with pytest.raises(binding.DeftError) as e:
-            h.solve_batch(h.upload(kb))
-        assert e.value.code == binding.DEFT_ERR_LIMIT
+    """A missing drop_time array is INVALID_ARG; nothing is enqueued."""
+    kb = W.random_recursive(7204, batch=4, n_max=12, w_hi=9, v_hi=9, cap_hi=30, t_hi=3)
     with binding.DeftKnapsack(max_batch=4, max_items=12, max_knapsacks=2, max_capacity=30) as h:
         db = h.upload(kb)
         db.drop_time = None

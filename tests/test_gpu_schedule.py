@@ -67,13 +67,21 @@ def test_status_and_reuse_of_one_handle(binding, oracle):
             assert_same({k: getattr(out, k).cpu().numpy() for k in FIELDS}, want)
 
 
+def test_rows_in_global_memory(binding, oracle):
+    """Windows beyond the LDS-resident row: the same simulation on the global-row path."""
+    sb = W.random_schedules(306, batch=11, n=20, iterations=6, w_hi=9000, t_hi=2000, f_hi=30000, b_hi=70000)
+    ref = oracle.simulate_batch(sb, cap_limit=70000, nthreads=11)
+    assert set(np.unique(ref.stage_case[:, :, 1])) >= {2, 3, 4}
+    assert_same(simulate(binding, sb, 70000), ref)
+
+
 def test_host_side_errors(binding):
-    sb = W.random_schedules(306, batch=2, n=5, iterations=3, w_hi=9, t_hi=3, f_hi=10, b_hi=10)
-    with binding.DeftKnapsack(max_batch=2, max_items=5, max_knapsacks=2, max_capacity=100000) as h:   # rows in global memory
+    sb = W.random_schedules(307, batch=2, n=5, iterations=3, w_hi=9, t_hi=3, f_hi=10, b_hi=10)
+    with binding.DeftKnapsack(max_batch=1, max_items=5, max_knapsacks=2, max_capacity=10) as h:      # batch above the limit
         with pytest.raises(binding.DeftError) as e:
             binding.simulate_schedule(h, binding.DeviceSchedules(sb, h.device))
         assert e.value.code == binding.DEFT_ERR_LIMIT
-    with binding.DeftKnapsack(max_batch=1, max_items=5, max_knapsacks=2, max_capacity=10) as h:      # batch above the limit
+    with binding.DeftKnapsack(max_batch=2, max_items=5, max_knapsacks=2, max_c1=10, max_c2=10) as h:  # no sequential mode
         with pytest.raises(binding.DeftError) as e:
             binding.simulate_schedule(h, binding.DeviceSchedules(sb, h.device))
         assert e.value.code == binding.DEFT_ERR_LIMIT
