@@ -314,12 +314,14 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             // of its slots changed (measured on the ResNet shape: 2.73 ms per step with groups of
             // sixteen, 2.76 with eight, 2.82 with four, 2.96 with a branch per slot, 2.88 when
             // everything is written).
-            constexpr int kGroup = 16;
-            static_assert(65536 % (kGroup * T * 4) == 0 || NB * T * 4 <= 65536, "groups do not straddle the M0 bases");
+            // (Twenty for 768 lanes, so that a group's slots all lie on one side of kSecondBase.)
+            constexpr int kGroup = T == 768 ? 20 : 16;
             SlotsDown<(NB - 1) / kGroup>::all([&](auto gc) {
                 constexpr int lo = gc.value * kGroup;
                 constexpr int hi = lo + kGroup - 1 < NB - 1 ? lo + kGroup - 1 : NB - 1;
                 constexpr uint32_t mask = ((1u << (hi - lo + 1)) - 1u) << (lo & 31);
+                static_assert((lo >> 5) == (hi >> 5), "a group's take bits sit in one word");
+                static_assert(hi * T * 4 <= 65535 || lo * T * 4 >= kSecondBase, "a group does not straddle the M0 bases");
                 if (!SKIP_UNCHANGED || (changed[lo >> 5] & mask)) {
                     if constexpr (hi * T * 4 <= 65535) {
                         m0_settle(m0w);
@@ -448,8 +450,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     // Long rows: a group of slots in which the wavefront changed nothing is not written back
     // (measured: 5 % on the ResNet shape; on short rows the test costs more than it saves).
     constexpr bool kSkipUnchanged = K >= 26;
-    constexpr int LOG_T = (T == 64) ? 6 : (T == 256) ? 8 : (T == 512) ? 9 : 10;
-    static_assert((1 << LOG_T) == T, "T must be 64, 256, 512 or 1024");
+    static_assert(T % 64 == 0 && T <= 1024, "whole wavefronts");
 
     const int sub = (T == 64) ? (int)(threadIdx.x >> 6) : 0;
     const int tid = (T == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
@@ -720,7 +721,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         const int C = stage_capacity(j);
         OfferedItem *list = inst_lists + (size_t)s * list_stride;
 
-        const int nchunk = uniform(((C >> LOG_T) + G) / G);  // G-slot chunks covering cells 0 .. C
+        const int nchunk = uniform((C / T + G) / G);  // G-slot chunks covering cells 0 .. C
         const int nact = min(uniform(misc[1]), list_stride);
         unsigned long long nzm = 0;
         BestLevel best{0, 0, 0};
@@ -818,7 +819,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 // lane L tests offered item q-d; items past the head of the list (q-d < 0) carry
                 // w = 0 and are excluded here, so cl never leaves [-5*C, C]
                 if (L >= 1 && q - d >= 0 && cl >= 0 && wd <= cl) {
-                    const int k = cl >> LOG_T, lane = cl & (T - 1), qd = q - d;
+                    const int k = cl / T, lane = cl % T, qd = q - d;  // cl >= 0 here
                     if (k < K && cl <= C) {
                         const unsigned long long nzw = tb_nz[(lane >> 6) * 64 + (qd >> 6)];
                         if ((nzw >> (qd & 63)) & 1ull) {
@@ -911,13 +912,14 @@ const Variant *variant_table()
     DEFT_VARIANT(256, 32, 4, 4, 256),   // <= 8191
     DEFT_VARIANT(512, 20, 1, 8, 128),   // <= 10239: four workgroups per CU when the row stays under 40 KB
     DEFT_VARIANT(512, 26, 1, 6, 128),   // <= 13311: with the 128-cell guard three workgroups share a CU's LDS
+    DEFT_VARIANT(768, 26, 1, 6, 128),   // <= 19967: two workgroups of twelve wavefronts share a CU when the row stays under 80 KB
     DEFT_VARIANT(1024, 26, 1, 4, 256),  // <= 26623: sixteen wavefronts on a 104 KB row
     DEFT_VARIANT(1024, 38, 2, 4, 256),  // <= 38911: 153 KB of row, the most that 160 KB of LDS holds with the guard
     };
     return table;
 }
 #undef DEFT_VARIANT
-constexpr int kNumVariants = 7;
+constexpr int kNumVariants = 8;
 
 template <int T, int K, int G, int WPE, bool REC>
 hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
@@ -942,8 +944,9 @@ hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
     case 2: return launch_one<256, 32, 4, 4, REC>(p, a, scratch, st, swept_cells);
     case 3: return launch_one<512, 20, 1, 8, REC>(p, a, scratch, st, swept_cells);
     case 4: return launch_one<512, 26, 1, 6, REC>(p, a, scratch, st, swept_cells);
-    case 5: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st, swept_cells);
-    case 6: return launch_one<1024, 38, 2, 4, REC>(p, a, scratch, st, swept_cells);
+    case 5: return launch_one<768, 26, 1, 6, REC>(p, a, scratch, st, swept_cells);
+    case 6: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st, swept_cells);
+    case 7: return launch_one<1024, 38, 2, 4, REC>(p, a, scratch, st, swept_cells);
     default: return hipErrorInvalidValue;
     }
 }

@@ -56,6 +56,7 @@ def test_tiny_single_and_bruteforce_batch(binding, oracle):
     (8000, 8191),      # 256 x 32
     (10000, 10239),    # 512 x 20
     (13000, 13055),    # 512 x 26
+    (19900, 19967),    # 768 x 26
     (20000, 26111),    # 1024 x 26
     (38900, 38911),    # 1024 x 38
 ])

@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("cap_hi,max_capacity", [
-    (700, 1023), (3000, 4095), (8000, 8191), (10000, 10239), (13000, 13055), (20000, 26111), (38900, 38911),
+    (700, 1023), (3000, 4095), (8000, 8191), (10000, 10239), (13000, 13055), (19900, 19967), (20000, 26111), (38900, 38911),
 ])
 def test_random_ragged_every_lds_variant(binding, oracle, cap_hi, max_capacity):
     """Ragged n up to 150 (three 64-entry list chunks), weights up to well above the
