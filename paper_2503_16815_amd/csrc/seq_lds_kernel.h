@@ -285,22 +285,16 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             const int level_value = uniform(probe) + (VEQW ? probe_at : 0);
             if (probe_at >= 0 && level_value > best.value) best = BestLevel{level_value, q, probe_at};
         }
-        // which slots changed anywhere in this wavefront: the take words ORed over its lanes
-        // (rotations within rows of 16 lanes, then one lane of each row)
-        uint32_t changed[NW];
+        // which groups of slots changed anywhere in this wavefront: one ballot per group over
+        // the group's bits of the take word
+        constexpr int kGroup = T == 768 ? 20 : 16;
+        constexpr int kGroups = (NB - 1) / kGroup + 1;
+        bool group_changed[kGroups];
 #pragma unroll
-        for (int x = 0; x < NW; ++x) {
-            if constexpr (!SKIP_UNCHANGED) {
-                changed[x] = 0xffffffffu;
-                continue;
-            }
-            int r = (int)bits[x];
-            r |= __builtin_amdgcn_update_dpp(0, r, 0x121, 0xf, 0xf, false);  // row_ror:1
-            r |= __builtin_amdgcn_update_dpp(0, r, 0x122, 0xf, 0xf, false);  // row_ror:2
-            r |= __builtin_amdgcn_update_dpp(0, r, 0x124, 0xf, 0xf, false);  // row_ror:4
-            r |= __builtin_amdgcn_update_dpp(0, r, 0x128, 0xf, 0xf, false);  // row_ror:8
-            changed[x] = (uint32_t)(__builtin_amdgcn_readlane(r, 0) | __builtin_amdgcn_readlane(r, 16) |
-                                    __builtin_amdgcn_readlane(r, 32) | __builtin_amdgcn_readlane(r, 48));
+        for (int g = 0; g < kGroups; ++g) {
+            const int lo = g * kGroup, hi = lo + kGroup - 1 < NB - 1 ? lo + kGroup - 1 : NB - 1;
+            const uint32_t mask = (uint32_t)(((1ull << (hi - lo + 1)) - 1ull) << (lo & 31));
+            group_changed[g] = !SKIP_UNCHANGED || __builtin_amdgcn_ballot_w64((bits[lo >> 5] & mask) != 0) != 0ull;
         }
         lds_sync<T>();  // every lane has read the old row
 
@@ -315,14 +309,12 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             // sixteen, 2.76 with eight, 2.82 with four, 2.96 with a branch per slot, 2.88 when
             // everything is written).
             // (Twenty for 768 lanes, so that a group's slots all lie on one side of kSecondBase.)
-            constexpr int kGroup = T == 768 ? 20 : 16;
             SlotsDown<(NB - 1) / kGroup>::all([&](auto gc) {
                 constexpr int lo = gc.value * kGroup;
                 constexpr int hi = lo + kGroup - 1 < NB - 1 ? lo + kGroup - 1 : NB - 1;
-                constexpr uint32_t mask = ((1u << (hi - lo + 1)) - 1u) << (lo & 31);
                 static_assert((lo >> 5) == (hi >> 5), "a group's take bits sit in one word");
                 static_assert(hi * T * 4 <= 65535 || lo * T * 4 >= kSecondBase, "a group does not straddle the M0 bases");
-                if (!SKIP_UNCHANGED || (changed[lo >> 5] & mask)) {
+                if (group_changed[gc.value]) {
                     if constexpr (hi * T * 4 <= 65535) {
                         m0_settle(m0w);
                         SlotsDownTo<hi, lo>::all([&](auto kc) { write_addtid<kc.value * T * 4>(m0w, own[kc.value]); });
@@ -344,10 +336,9 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
         // (q / 64) says whether this wavefront's part of row q exists.
         bool nz;
         if constexpr (SKIP_UNCHANGED) {
-            uint32_t any_changed = changed[0];
+            nz = false;
 #pragma unroll
-            for (int x = 1; x < NW; ++x) any_changed |= changed[x];
-            nz = any_changed != 0;
+            for (int g = 0; g < kGroups; ++g) nz = nz || group_changed[g];
         } else {
             uint32_t any_bits = bits[0];
 #pragma unroll
