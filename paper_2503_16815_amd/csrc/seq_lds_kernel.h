@@ -243,6 +243,11 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
 
     const int m0w = uniform((int)row_off + wave_first * 4);
     const int m0w2 = m0w + kSecondBase;
+    uint32_t nz_acc = 0;  // flags of the items since the last multiple of 32 (the same in every lane)
+    auto hand_over = [&](int q) {  // q: the last item whose flag nz_acc holds
+        if ((tid & 63) == (q >> 6)) nzm |= (unsigned long long)nz_acc << (q & 32);
+        nz_acc = 0;
+    };
     // One item.  HEAVY is a compile-time flag and the two kinds run in separate loops
     // below, so that the loop over the (common) light items has a single body and the
     // compiler keeps every cell in one register across iterations.
@@ -333,7 +338,8 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
         }
         // Row q of the keep table belongs to the q-th offered item.  A wavefront whose 64
         // lanes took nothing writes nothing and notes that in nzm: bit (q % 64) of lane
-        // (q / 64) says whether this wavefront's part of row q exists.
+        // (q / 64) says whether this wavefront's part of row q exists.  The flags of 32
+        // items are collected in a scalar first.
         bool nz;
         if constexpr (SKIP_UNCHANGED) {
             nz = false;
@@ -349,7 +355,8 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
 #pragma unroll
             for (int x = 0; x < NW; ++x) kp[((size_t)q * NW + x) * T + tid] = bits[x];
         }
-        if ((tid & 63) == (q >> 6)) nzm |= (unsigned long long)nz << (q & 63);
+        nz_acc |= (uint32_t)nz << (q & 31);
+        if ((q & 31) == 31) hand_over(q);
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
     };
@@ -383,19 +390,20 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             int w = __builtin_amdgcn_readlane(cur.x, q & 63);
             while (w <= light_max) {  // run of light items
                 item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (row_is_full(q)) return q + 1;
+                if (row_is_full(q)) { hand_over(q); return q + 1; }
                 if (++q >= q1) break;
                 w = __builtin_amdgcn_readlane(cur.x, q & 63);
             }
             if (q < q1) {  // one heavy item
                 item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (row_is_full(q)) return q + 1;
+                if (row_is_full(q)) { hand_over(q); return q + 1; }
                 ++q;
             }
         }
         cur = nxt;
         cur_p = nxt_p;
     }
+    if (nact > 0) hand_over(nact - 1);
     return nact;
 }
 
