@@ -43,7 +43,19 @@ enum {
 };
 
 /* Limits fixed at create time; they size the scratch memory and select the
- * kernel variants.  A limit of 0 disables the corresponding mode. */
+ * kernel variants.  A limit of 0 disables the corresponding mode.
+ *
+ * The sequential-mode kernel (lanes per instance, row cells per lane, LDS per
+ * workgroup, workgroups per compute unit) is chosen ONCE, here, from max_capacity
+ * (and max_items, whose lists must fit the row's LDS), not per call: the host
+ * never reads the capacities of a batch, which live in device memory.  Every call
+ * on the handle runs that kernel, whatever capacities it holds, so a handle
+ * created for max_capacity 38911 solves capacity-900 instances on the
+ * 1024-lane, one-workgroup-per-compute-unit kernel, several times slower than
+ * a handle created for 1023 would.  Callers with mixed batches should keep one
+ * handle per capacity class (<= 1023, 4095, 8191, 10239, 13311, 19967, 26623,
+ * 38911 cells; longer rows live in global memory) and route instances by their
+ * largest capacity.  deft_knapsack_get_info reports the choice. */
 typedef struct {
     int32_t device;        /* HIP device ordinal                                           */
     int32_t max_batch;     /* instances per call                                           */

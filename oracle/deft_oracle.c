@@ -256,10 +256,15 @@ int deft_oracle_joint2(int32_t n, int32_t item_stride, const int32_t *w1, const 
 }
 
 /*
- * Algorithm 1 (RecursiveKnapsack) for one instance, written as the recursion it is.
- * Items 0 .. n-1 are the list C_1 .. C_N in generation order; drop[i] is the time taken
- * off the remaining time when item i (the last of the current list) is left out of the
- * list.  A list solved with a negative remaining time schedules nothing.
+ * Algorithm 1 (RecursiveKnapsack) for one instance.
+ * Items 0 .. n-1 are the list in generation order; drop[i] is the time taken off the
+ * remaining time when item i, then the last of the list, is left off it.  The procedure
+ * nests: the answer for a list is the knapsack over that list unless the answer for the
+ * list without its last item is at least as good.  Unrolled from the innermost call
+ * outwards that is a walk over the prefixes of the list, shortest first: the empty list
+ * answers "nothing", and each longer prefix, solved with the remaining time it is left
+ * with, replaces the incumbent only when its sum is strictly greater.  A prefix met with
+ * a negative remaining time schedules nothing.
  * Outputs: assign[i] = 0 for scheduled items else -1; knap_value[0] / knap_load[0] =
  * value and weight scheduled; knap_value[1] = number of items dropped from the end of
  * the list at the level whose answer was returned (n if nothing is scheduled at any
@@ -267,34 +272,30 @@ int deft_oracle_joint2(int32_t n, int32_t item_stride, const int32_t *w1, const 
  */
 typedef struct { int64_t value, load, remain; int len; uint8_t *chosen; } rec_result_t;
 
-static int recursive_knapsack(int len, const int32_t *w, const int32_t *v, const int32_t *drop,
-                              int64_t remain, rec_result_t *out, int64_t *touched, int64_t *table)
+static int recursive_knapsack(int n, const int32_t *w, const int32_t *v, const int32_t *drop,
+                              int64_t remain_full, rec_result_t *out, int64_t *touched, int64_t *table)
 {
-    if (len == 0) {                              /* CommTimeList is empty: return the empty order */
-        out->value = 0; out->load = 0; out->remain = 0; out->len = 0;
-        return ST_OK;
+    out->value = 0; out->load = 0; out->remain = 0; out->len = 0;   /* the empty list's answer */
+    if (n == 0) return ST_OK;
+    uint8_t *trial = (uint8_t *)calloc((size_t)n, 1);
+    int64_t *remain = (int64_t *)calloc((size_t)n + 1, sizeof(int64_t));
+    if (!trial || !remain) { free(trial); free(remain); return ST_OOM; }
+    /* remaining time of the prefix of each length: the full time minus what the items
+     * behind the prefix take off */
+    remain[n] = remain_full;
+    for (int len = n - 1; len >= 0; --len) remain[len] = remain[len + 1] - drop[len];
+    int rc = ST_OK;
+    for (int len = 1; len <= n && rc == ST_OK; ++len) {
+        int64_t value = 0, load = 0;
+        if (remain[len] < 0) continue;
+        rc = single_stage(len, w, v, (int32_t)remain[len], &value, &load, trial, touched, table);
+        if (rc == ST_OK && value > out->value) {
+            memcpy(out->chosen, trial, (size_t)len);
+            out->value = value; out->load = load; out->remain = remain[len]; out->len = len;
+        }
     }
-    /* order1 = NaiveKnapsack(CommTimeList, remainTime) */
-    rec_result_t one = { 0, 0, remain, len, NULL };
-    one.chosen = (uint8_t *)calloc((size_t)len, 1);
-    if (!one.chosen) return ST_OOM;
-    if (remain >= 0) {
-        int rc = single_stage(len, w, v, (int32_t)remain, &one.value, &one.load, one.chosen, touched, table);
-        if (rc != ST_OK) { free(one.chosen); return rc; }
-    }
-    /* order2 = RecursiveKnapsack(CommTimeList - C_N, remainTime - T_{N-1}) */
-    rec_result_t two = { 0, 0, 0, 0, NULL };
-    two.chosen = out->chosen;                    /* the deeper levels write into the caller's buffer */
-    int rc = recursive_knapsack(len - 1, w, v, drop, remain - drop[len - 1], &two, touched, table);
-    if (rc != ST_OK) { free(one.chosen); return rc; }
-    if (one.value > two.value) {                 /* sum(order1) > sum(order2): return order1 */
-        memcpy(out->chosen, one.chosen, (size_t)len);
-        out->value = one.value; out->load = one.load; out->remain = remain; out->len = len;
-    } else {                                     /* else return order2 (already in out->chosen) */
-        out->value = two.value; out->load = two.load; out->remain = two.remain; out->len = two.len;
-    }
-    free(one.chosen);
-    return ST_OK;
+    free(trial); free(remain);
+    return rc;
 }
 
 int deft_oracle_recursive(int32_t n, int32_t item_stride, const int32_t *w, const int32_t *v,

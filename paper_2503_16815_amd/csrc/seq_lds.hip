@@ -13,19 +13,19 @@ bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks
                   int32_t lds_per_wg_bytes, SeqLdsPlan *plan)
 {
     const int32_t n_pad = (max_items + 7) & ~7;  // list entries per stage (whole 64-byte lines)
-    int only = -1;
-    if (const char *e = getenv("DEFT_SEQ_VARIANT")) only = atoi(e);  // tuning aid: force a table entry
     for (int i = 0; i < kNumVariants; ++i) {
-        if (only >= 0 && i != only) continue;
         const Variant &v = variant_table<false>()[i];
         const int guard = v.guard;
         // register slots needed by lane 0, rounded up to whole chunks
         const int64_t slots = ((int64_t)max_capacity / v.threads + v.chunk) / v.chunk * v.chunk;
         if (slots > v.cells) continue;
-        const int64_t row_cells = slots * v.threads;
         // after a stage's sweep the row's LDS stages the walk's data: two ints per list
-        // entry and one 64-bit word per lane
-        if (row_cells < 2 * (int64_t)n_pad + 2 * v.threads) continue;
+        // entry and one 64-bit word per lane; a long item list on a short row gets the LDS
+        // it needs for that, up to the variant's full row
+        int64_t row_cells = slots * v.threads;
+        const int64_t staging = 2 * (int64_t)n_pad + 2 * v.threads;
+        if (row_cells < staging) row_cells = (staging + v.threads - 1) / v.threads * v.threads;
+        if (row_cells > (int64_t)v.cells * v.threads) continue;
         const int64_t per_inst = (guard + row_cells) * 4;
         const int inst_per_wg = v.threads == 64 ? 4 : 1;
         const int64_t lds = per_inst * inst_per_wg;

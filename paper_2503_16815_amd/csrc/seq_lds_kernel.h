@@ -952,12 +952,16 @@ hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
 }
 
 // Sets the dynamic-LDS attribute of the plan's kernel and returns how many of its
-// workgroups the runtime would place on a compute unit.
+// workgroups the runtime would place on a compute unit.  The attribute belongs to the
+// kernel, not to the handle, so it is set to the most any handle on this variant can ask
+// for (the variant's full row): a later, smaller handle never lowers it under an earlier one.
 template <bool REC>
 hipError_t prepare_variant(const SeqLdsPlan &plan, int *wg_per_cu)
 {
-    const void *fn = variant_table<REC>()[plan.variant].fn;
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, plan.lds_bytes);
+    const Variant &v = variant_table<REC>()[plan.variant];
+    const void *fn = v.fn;
+    const int full_row = (v.guard + v.cells * v.threads) * 4 * plan.inst_per_wg;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, full_row);
     if (e != hipSuccess) return e;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(wg_per_cu, fn, plan.wg_threads, (size_t)plan.lds_bytes);
 }

@@ -244,6 +244,27 @@ def random_sequential(seed: int, batch: int, n_max: int, m_max: int, w_hi: int, 
     return kb
 
 
+def filling_rows(seed: int, batch: int, n_max: int, m_max: int, w_hi: int, cap_lo: int,
+                 cap_hi: int) -> KnapsackBatch:
+    """Value = weight with many light items and capacities in [cap_lo, cap_hi]: every sum up
+    to the capacity becomes reachable long before the item list ends, stage after stage
+    (the leftover of one window still overfills the next).  n in [n_max / 2, n_max], m in
+    [2, m_max], random fill order."""
+    r = _rng(seed)
+    n_items = r.integers(n_max // 2, n_max + 1, size=batch)
+    n_knap = r.integers(2, m_max + 1, size=batch)
+    w = r.integers(1, w_hi + 1, size=(batch, n_max))
+    cap = r.integers(cap_lo, cap_hi + 1, size=(batch, m_max))
+    order = np.tile(np.arange(m_max), (batch, 1))
+    for b in range(batch):
+        m = int(n_knap[b])
+        order[b, :m] = r.permutation(m)
+    kb = _sequential(f"filling_rows_{seed}", w, w.copy(), cap, order, meta={"seed": seed})
+    kb.n_items = _i32(n_items)
+    kb.n_knapsacks = _i32(n_knap)
+    return kb
+
+
 def random_joint(seed: int, batch: int, n_max: int, w_hi: int, v_hi: int, c1_hi: int,
                  c2_hi: int, ragged: bool = True) -> KnapsackBatch:
     r = _rng(seed)

@@ -212,6 +212,43 @@ def test_stage_shortcuts_randomized(binding, oracle, seed, n_max, w_hi, cap_hi, 
     run(binding, oracle, kb)
 
 
+@pytest.mark.parametrize("max_capacity,n_max,w_hi,batch", [
+    (1023, 160, 30, 64),        # wavefront-per-instance variant
+    (4095, 600, 30, 40),        # 256 x 16
+    (8191, 1160, 30, 32),       # 256 x 32
+    (10239, 1450, 30, 28),      # 512 x 20
+    (13311, 1890, 30, 24),      # 512 x 26
+    (19967, 2830, 30, 20),      # 768 x 26: write-back groups on both sides of the second add-TID base
+    (26623, 3000, 39, 16),      # 1024 x 26
+    (38911, 3000, 57, 12),      # 1024 x 38
+])
+def test_rows_that_fill_early_every_lds_variant(binding, oracle, max_capacity, n_max, w_hi, batch):
+    """Value = weight, light items, capacities in the upper half of each variant's range and two
+    or three windows in random order: every swept stage reaches "every sum up to C is reachable"
+    well before its list ends, so the sweep's early end, the write-back of a row that uses the
+    variant's highest slots, the partial keep-row flags and the walk that starts at the last
+    swept item all run together; the library's swept-cell count must equal the replay of the
+    early end from the oracle's results (which also shows that rows did fill)."""
+    import torch
+    import bench
+    kb = W.filling_rows(8000 + max_capacity, batch=batch, n_max=n_max, m_max=3, w_hi=w_hi,
+                        cap_lo=max_capacity * 55 // 100, cap_hi=max_capacity)
+    print(f"case {kb.name} batch={kb.batch} n<={n_max} max_capacity={max_capacity}", flush=True)
+    ref = oracle.solve_batch(kb, nthreads=16, cap_limit=max_capacity)
+    settled, full = bench.cells_not_swept(kb, ref, True)
+    assert full > 0.2 * int(ref.touched_cells.sum()), "the case is meant to end sweeps early"
+    with binding.DeftKnapsack(max_batch=kb.batch, max_items=kb.item_stride, max_knapsacks=kb.knap_stride,
+                              max_capacity=max_capacity) as h:
+        assert h.info().seq_path in (1, 2)
+        db = h.upload(kb)
+        h.set_profiling(True)
+        out = h.solve_batch(db)
+        torch.cuda.synchronize()
+        prof = h.get_profile()
+        assert_same(kb, out, ref)
+    assert int(prof.swept_cell_updates) == int(ref.touched_cells.sum()) - settled - full, kb.name
+
+
 def test_swept_cell_counter_matches_the_replay_from_the_oracle(binding, oracle):
     """The library's count of the cell-updates its sweeps evaluated (measurement only) against
     the same number derived from the oracle's results and the two rules (stages settled without

@@ -80,24 +80,17 @@ def test_host_side_errors(binding):
 
 
 def test_backward_stage_at_paper_shape(binding, oracle):
-    """1024 ResNet-101-shaped backward stages (314 buckets) in one call, as timed; the
-    oracle's recursion costs n DPs per instance, so it checks a sample of 12 instances
-    and the rest is checked through what holds for every answer: feasible for its own
-    level, made of that level's items only, totals consistent."""
+    """1024 ResNet-101-shaped backward stages (314 buckets) in one call, as timed: every
+    output of every instance against the oracle's recursion (n DPs per instance, a few
+    seconds on the host cores), and what holds for every answer besides: feasible for its
+    own level, made of that level's items only, totals consistent."""
     import torch
     kb = W.backward_stage_shaped()
+    ref = run(binding, oracle, kb)
+    assert (ref.status == 0).all()
     out = binding.solve(kb)
     torch.cuda.synchronize()
-    status = out.status.cpu().numpy()
     kv, kl, asg = out.knap_value.cpu().numpy(), out.knap_load.cpu().numpy(), out.assignment.cpu().numpy()
-    assert (status == 0).all()
-    sample = np.linspace(0, kb.batch - 1, 12).astype(int)
-    for b in sample:
-        one = kb.slice(int(b), int(b) + 1)
-        ref = oracle.solve_batch(one)
-        assert kv[b].tolist() == ref.knap_value[0].tolist(), b
-        assert kl[b].tolist() == ref.knap_load[0].tolist(), b
-        assert np.array_equal(asg[b], ref.assignment[0]), b
     n = kb.item_stride
     sel = asg == 0
     assert ((asg == 0) | (asg == -1)).all()

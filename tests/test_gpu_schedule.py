@@ -88,17 +88,16 @@ def test_host_side_errors(binding):
 
 
 def test_resnet101_shape_full_batch(binding, oracle):
-    """1024 candidates x 314 buckets x 8 iterations in one call, as timed.  The oracle's
-    recursion costs n DPs per backward stage, so it replays 24 sampled candidates; for
-    all of them: every iteration applied once or still waiting, no stage above its window."""
+    """1024 candidates x 314 buckets x 8 iterations in one call, as timed: every record of
+    every candidate against the oracle (n DPs per backward stage: some tens of seconds on the
+    host cores); besides, every iteration applied once or still waiting and no stage above
+    its window."""
     sb = W.resnet101_schedules()
+    print(f"case {sb.name} batch={sb.batch}", flush=True)
     got = simulate(binding, sb, int(max(sb.backward_time.max(), sb.forward_time.max())))
     assert (got["status"] == 0).all()
     assert (got["update_k"].sum(axis=1) + got["tail"].sum(axis=1) == sb.iterations).all()
     assert (got["stage_time"][:, :, 0] <= sb.forward_time[:, None]).all()
     assert (got["stage_time"][:, :, 1] <= sb.backward_time[:, None]).all()
-    rows = np.linspace(0, sb.batch - 1, 24).astype(int)
-    part = W.ScheduleBatch(name="sample", batch=len(rows), n_buckets=sb.n_buckets, iterations=sb.iterations,
-                           comm_time=sb.comm_time[rows], drop_time=sb.drop_time[rows],
-                           forward_time=sb.forward_time[rows], backward_time=sb.backward_time[rows])
-    assert_same(got, oracle.simulate_batch(part, nthreads=16), rows)
+    print("oracle replay of all candidates ...", flush=True)
+    assert_same(got, oracle.simulate_batch(sb, nthreads=16))

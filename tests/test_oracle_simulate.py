@@ -1,7 +1,8 @@
 """Pins for the oracle of the task-queue simulation (Section III.B, Cases 1-4), no GPU.
 The paper gives the cases in prose and a figure that is not part of its text, so no
-printed numbers exist to compare with; the checks are sequences worked by hand from the
-cases, closed forms, conservation of iterations, and a replay of every stage with the
+printed numbers exist to compare with; the checks are the sequence of cases and updates
+that the paper narrates for that figure (tests/golden/fig4_walkthrough.txt), sequences
+worked by hand from the cases, closed forms, conservation of iterations, and a replay of every stage with the
 enumeration solvers of tests/bruteforce.py (which checks the lists, capacities and index
 maps the oracle hands to its own solvers, not the reading of the cases)."""
 import numpy as np
@@ -37,6 +38,70 @@ def test_sequence_worked_by_hand(oracle):
     assert r.stage_time[0, :, 1].tolist() == [6, 6, 6, 6, 6, 6]
     assert r.update_k[0].tolist() == [0, 1, 1, 0, 1, 2]
     assert r.tail[0].tolist() == [1, 0]
+
+
+def _fig4_fixture():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "fig4_walkthrough.txt")
+    data, told = {}, {}
+    with open(path) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *rest = line.split()
+            if key == "narrated":
+                told[rest[0]] = [None if x == "-" else int(x) for x in rest[1:]]
+            else:
+                data[key] = [int(x) for x in rest]
+    return data, told
+
+
+def test_walk_through_of_fig4(oracle):
+    """The paper's own walk through its Fig. 4 (Section III.B, after Case 4), on an
+    eight-bucket instance: every case, leftover count and update the text states must come
+    out of the oracle's reading of the two queues.  The first two iterations worked by hand
+    (times 1 8 6 4 8 4 5 4, drop times 1 1 3 0 2 0 0 0, windows 10 / 21):
+    it 1 backward: queue empty -> Case 4.  Remaining time per list length 8..4: 21 21 21 21 19.
+      Lengths 8..5 all reach 21 and length 4 reaches 19, so the shortest list that reaches 21
+      wins: 1+8+4+8 of the first five -> four buckets sent, (6, 4, 5, 4) at positions 2 5 6 7 wait.
+    it 2 forward (10): Case 1 over (6, 4, 5, 4): 6+4 (smallest mask among the sums of 10) -> two
+      sent, (5, 4) wait: the two buckets left from the first iteration.
+    it 2 backward: 9 fits 21 -> Case 3: both go first (the first iteration is complete), 12
+      left.  Remaining time per length 8..1: 12 12 12 12 10 10 7 6; values 12 12 12 12 10 9 1 1;
+      length 5 is the shortest that reaches 12: 8+4 -> two sent; count 2 + 2 = 4, time 9 + 12.
+      Update with k = 1 at the end of iteration 2."""
+    data, told = _fig4_fixture()
+    n = data["buckets"][0]
+    iters = len(told["backward_case"])
+    r = oracle.simulate_batch(one(data["comm_time"], data["drop_time"], data["forward_window"][0],
+                                  data["backward_window"][0], iters))
+    assert r.status.tolist() == [0] and len(data["comm_time"]) == n == 8
+    case, cnt, upd = r.stage_case[0], r.stage_count[0], r.update_k[0]
+    assert case[0].tolist() == [0, 4]            # nothing to send before the first backward stage
+    for t in range(iters):
+        if told["backward_case"][t] is not None:
+            assert case[t, 1] == told["backward_case"][t], t
+        if told["forward_case"][t] is not None:
+            assert case[t, 0] == told["forward_case"][t], t
+        if told["update_k"][t] is not None:
+            assert upd[t] == told["update_k"][t], t
+        if told["left_before_backward"][t] is not None:
+            # the queue was filled by the previous backward stage (Case 4: all n new buckets
+            # minus what Algorithm 1 sent) and served by this iteration's forward stage
+            assert case[t - 1, 1] == 4 and n - cnt[t - 1, 1] - cnt[t, 0] == told["left_before_backward"][t], t
+        if told["left_after_backward"][t] is not None:
+            # the next backward stage finds the queue empty (Case 4), so what was left is
+            # exactly what the forward stage in between sent
+            assert case[t + 1, 1] == 4 and case[t + 1, 0] == 1 and cnt[t + 1, 0] == told["left_after_backward"][t], t
+        if told["merged_iterations_in_backward_list"][t] is not None:
+            # the merged list's iterations are applied together, in the update that follows
+            k = told["merged_iterations_in_backward_list"][t]
+            later = upd[t:]
+            assert case[t - 1, 1] == 2 and k in later.tolist(), t
+    # the hand-worked first two iterations, and the rest as the reading gives it
+    assert cnt[:2].tolist() == [[0, 4], [2, 4]] and r.stage_time[0, :2].tolist() == [[0, 21], [10, 21]]
+    assert case.tolist() == [[0, 4], [1, 3], [1, 3], [1, 2], [1, 4], [1, 3]]
+    assert upd.tolist() == [0, 1, 1, 0, 1, 2] and r.tail[0].tolist() == [1, 0]
 
 
 def test_forward_stage_clears_the_queue(oracle):
