@@ -254,6 +254,38 @@ typedef struct {
 
 deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, const deft_schedule_batch_t *s);
 
+/*
+ * deft_knapsack_solve_batch_static: DEFT_MODE_SEQUENTIAL for callers that cannot
+ * allocate device memory: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No handle: what a handle would own (keep table,
+ * offered-item lists) lives in one device array of DEFT_STATIC_SCRATCH_BYTES that is part
+ * of the library image; every GPU the library runs on holds its own copy until the
+ * process ends.  The call never calls hipMalloc / hipFree or any allocating routine; its
+ * first use on a device looks up that device's copy of the array and, per kernel, sets
+ * the kernel's dynamic-LDS attribute (neither allocates).  It runs the same kernels as
+ * deft_knapsack_solve_batch with rows resident in LDS and returns the same outputs.
+ *   device        HIP device ordinal (< 64) the arrays of `batch` live on
+ *   max_capacity  1 .. 38911: upper bound of every capacity in the batch; it selects
+ *                 the kernel exactly as deft_knapsack_config_t.max_capacity does, and an
+ *                 instance with a larger capacity gets status DEFT_ERR_LIMIT
+ *   batch         as for deft_knapsack_solve_batch; mode must be DEFT_MODE_SEQUENTIAL,
+ *                 drop_time is ignored
+ * Size limit: batch * item_stride * W + batch * knap_stride * ceil8(item_stride) * 16 bytes
+ * must not exceed DEFT_STATIC_SCRATCH_BYTES, where W = 4 * lanes * ceil(cells / 32) of the
+ * kernel chosen (256 bytes for max_capacity <= 1023, 1024 <= 4095 and <= 8191, 2048 <=
+ * 10239 and <= 13311, 3072 <= 19967, 4096 <= 26623, 8192 <= 38911).  Larger calls, and
+ * max_capacity above 38911, return DEFT_ERR_LIMIT with nothing enqueued.
+ * Errors otherwise as deft_knapsack_solve_batch (INVALID_ARG also for another mode, a bad
+ * device ordinal or max_capacity < 1; DEVICE when the device is not a gfx950).
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap in
+ * time (different streams, or a captured graph replayed while another call runs) race.
+ * Calls on one stream are ordered and safe; nothing in the array carries over from call
+ * to call, and nothing in it needs clearing.
+ */
+#define DEFT_STATIC_SCRATCH_BYTES (64 * 1024 * 1024)
+deft_status_t deft_knapsack_solve_batch_static(int32_t device, int32_t max_capacity,
+                                               const deft_knapsack_batch_t *batch);
+
 /* deft_knapsack_destroy: free the scratch and the handle.  NULL is a no-op. */
 void deft_knapsack_destroy(deft_knapsack_t *h);
 

@@ -22,7 +22,9 @@ DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, 
 
 EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_destroy",
            "deft_knapsack_get_info", "deft_knapsack_set_profiling", "deft_knapsack_get_profile",
-           "deft_knapsack_status_string", "deft_knapsack_simulate_schedule")
+           "deft_knapsack_status_string", "deft_knapsack_simulate_schedule",
+           "deft_knapsack_solve_batch_static")
+STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 
 
 class deft_knapsack_config_t(ctypes.Structure):
@@ -88,6 +90,9 @@ def load_library() -> ctypes.CDLL:
     lib.deft_knapsack_get_profile.argtypes = [vp, ctypes.POINTER(deft_knapsack_profile_t)]
     lib.deft_knapsack_simulate_schedule.restype = ctypes.c_int
     lib.deft_knapsack_simulate_schedule.argtypes = [vp, ctypes.POINTER(deft_schedule_batch_t)]
+    lib.deft_knapsack_solve_batch_static.restype = ctypes.c_int
+    lib.deft_knapsack_solve_batch_static.argtypes = [ctypes.c_int32, ctypes.c_int32,
+                                                     ctypes.POINTER(deft_knapsack_batch_t)]
     lib.deft_knapsack_status_string.restype = ctypes.c_char_p
     lib.deft_knapsack_status_string.argtypes = [ctypes.c_int32]
     _lib = lib
@@ -254,6 +259,19 @@ def simulate_schedule(h: "DeftKnapsack", ds: DeviceSchedules,
     if rc != DEFT_OK:
         raise DeftError("deft_knapsack_simulate_schedule", rc)
     return ds.out
+
+
+def solve_batch_static(db: DeviceBatch, max_capacity: int, device: int = 0,
+                       stream: Optional[torch.cuda.Stream] = None) -> SolveOutputs:
+    """Enqueue one sequential-mode solve through the entry point that allocates nothing
+    (no handle; the library's built-in scratch array)."""
+    if stream is None:
+        stream = torch.cuda.current_stream(torch.device("cuda", device))
+    cs = db.c_struct(stream.cuda_stream)
+    rc = load_library().deft_knapsack_solve_batch_static(device, max_capacity, ctypes.byref(cs))
+    if rc != DEFT_OK:
+        raise DeftError("deft_knapsack_solve_batch_static", rc)
+    return db.out
 
 
 def solve(kb, device: int = 0, **limits) -> SolveOutputs:
