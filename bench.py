@@ -3,9 +3,12 @@
 
 A step is one pass of the whole hot path (validation, every stage's DP sweep,
 keep-table stream, traceback, outputs) over one synthetic batch resident in
-HBM.  Prints ONE JSON line: DP cell-updates/s (touched cells, counted by the CPU
-oracle), instances/s, the LDS roofline of the sweep kernel from HIP events on
-the launch stream, and the CPU oracle timed on this machine's host cores.
+HBM.  Prints ONE JSON line: DP cell-updates/s (the cell-updates the kernels
+evaluate; the job's count as the CPU oracle performs it is beside it),
+instances/s, the LDS roofline of the sweep kernel from HIP events on the launch
+stream, and the CPU oracle timed on this machine's host cores.  The default run
+(ResNet-101 shape) also measures, in the same process, every other
+configuration (`per_config`) and the device's LDS / HBM rates (`peaks`).
 """
 from __future__ import annotations
 
@@ -85,7 +88,7 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
             calls = [W.resnet101_sweep(batch=sc(1024))]
             how = f"one call of {4 * sc(1024)} candidate schedules = {sc(1024)} perturbed profiles x k=1..4 (m=2k)"
         desc = f"ResNet-101-shaped: {how}, n=314, windows 11800/5900 +-10%, v=w"
-        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=3.0)
     elif name == "vgg19":
         if per_k_calls:
             calls = [W.vgg19_shaped(k=k, batch=sc(4096)) for k in (1, 2, 3, 4)]
@@ -94,7 +97,7 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
             calls = [W.vgg19_sweep(batch=sc(4096))]
             how = f"one call of {4 * sc(4096)} candidate schedules = {sc(4096)} profiles x k=1..4 (m=2k)"
         desc = f"VGG-19-shaped: {how}, n=38, windows 9300/3700, v=w"
-        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=3.0)
     elif name == "gpt2":
         calls = [W.gpt2_shaped(batch=sc(256))]
         desc = f"GPT-2-shaped: batch {sc(256)}, n=148, windows 381000/169000 (1 us units), v=w*U[1,4]"
@@ -107,12 +110,12 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
         calls = [W.backward_stage_shaped(batch=sc(1024))]
         desc = (f"Algorithm 1 on ResNet-101-shaped backward stages: batch {sc(1024)}, n=314, remaining time "
                 f"11800 +-10%, v=w, every level read off one sweep")
-        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=3.0)
     elif name == "inflation":
         calls = [W.inflation_sweep_shaped(batch=sc(1024))]
         desc = (f"capacity sweep on ResNet-101-shaped backward windows: batch {sc(1024)}, n=314, the window "
                 f"(11800 +-10%) and ten inflations of +5% each, v=w, all read off one sweep at the largest")
-        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=4.0)
+        algo = dict(bound="lds", bytes_per_cell=8.0, ops_per_cell=3.0)
     elif name == "tiny":
         calls = [W.tiny_bruteforce(batch=sc(64))]
         desc = f"Tiny: batch {sc(64)}, n=16, capacities 500/250"
@@ -122,9 +125,10 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
     return calls, desc, algo
 
 
-def run_schedule(args) -> int:
+def run_schedule(args):
     """The task-queue simulation (Sec. III.B, Cases 1-4) on the ResNet-101 shape: a step is one
-    call simulating every candidate for 8 iterations (16 stages, each one solver launch)."""
+    call simulating every candidate for 8 iterations (16 stages, each one solver launch).
+    Returns (line, parity)."""
     import torch
     from oracle import oracle
     from paper_2503_16815_amd import binding, workloads as W
@@ -172,67 +176,52 @@ def run_schedule(args) -> int:
     achieved = swept_step * args.steps * 8.0 / sweep_s / 1e9 if sweep_s > 0 else 0.0
     upd = got["update_k"]
     line = dict(
-        metric="knapsack DP cell-updates/sec", value=cells_step / (ms_step * 1e-3), unit="cell-updates/s", n_gpus=1,
+        metric="knapsack DP cell-updates/sec", value=swept_step / (ms_step * 1e-3), unit="cell-updates/s", n_gpus=1,
         steps=args.steps, warmup=args.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype="int32", data="synthetic",
         config=dict(workload=f"task-queue simulation (Cases 1-4), ResNet-101-shaped: {sb.batch} candidates x "
                              f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%",
+                    value_counts="cell-updates the sweeps evaluate (counted by the library)",
                     candidates_per_step=sb.batch, iterations=sb.iterations,
-                    cell_updates_per_step_estimated_from_sample=cells_step,
+                    one_sweep_cell_updates_per_step_estimated_from_sample=cells_step,
                     cell_updates_swept_per_step=swept_step, seq_path=int(info.seq_path),
                     threads_per_instance=int(info.seq_threads), cells_per_thread=int(info.seq_cells_per_thread),
                     updates_per_iteration_mean=float((upd > 0).mean()),
                     buckets_per_iteration_mean=float(got["stage_count"].sum(axis=(1, 2)).mean() / sb.iterations)),
         candidate_iterations_per_s=sb.batch * sb.iterations / (ms_step * 1e-3), parity_vs_oracle=bool(parity),
+        parity_checked=f"{len(rows)} of {sb.batch} candidates (every candidate: tests/test_gpu_schedule.py)",
         profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
                      sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
         roofline=dict(bound="lds", achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s", frac=achieved / PEAK_LDS_GBS,
                       traffic=None, kernel="seq_lds_kernel", bytes_per_cell=8.0, launches=launches,
-                      avg_launch_ms=float(prof.sweep_ms) / max(launches, 1)),
+                      avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
+                      swept_cell_updates_per_s=swept_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
+                      alu=dict(ops_per_cell=3.0, peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
+                               frac=(swept_step * args.steps * 3.0 / sweep_s) / PEAK_INT_LANE_OPS if sweep_s > 0 else 0.0)),
         cpu_baseline=None if args.no_cpu else dict(
             value=float(ref.sweep_cells.sum()) / t_cpu, unit="cell-updates/s", cores=int(ref.threads), kind="oracle",
             sample=f"{len(rows)} of the {sb.batch} candidates, all {sb.iterations} iterations, {t_cpu:.2f} s wall "
                    f"(the oracle solves Algorithm 1 level by level; the figure counts the same one-sweep cells as "
                    f"the GPU line)",
             candidate_iterations_per_s=len(rows) * sb.iterations / t_cpu))
-    print(json.dumps(line))
-    return 0 if parity else 3
+    return line, bool(parity)
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="resnet101",
-                    choices=["resnet101", "vgg19", "gpt2", "hetero", "backward", "inflation", "schedule", "tiny"])
-    ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
-    ap.add_argument("--per-k-calls", action="store_true",
-                    help="ResNet/VGG shapes: one call per k (4 calls of 1024 / 4096 instances) instead of one call "
-                         "holding the whole sweep over k")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device-to-device copy kernel, so that a counter profile of this "
-                         "command holds a row of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
-    ap.add_argument("--no-per-k", action="store_true",
-                    help="skip the extra timing of the one-call-per-k reading (profiling runs: keeps the kernel "
-                         "statistics to the headline launches)")
-    ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
-    ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (instances are independent; sharding is by "
-              "instance index and is not part of this build); use --gpus 1", file=sys.stderr)
-        return 2
+def subset(kb, rows):
+    """The instances `rows` of a batch (oracle sampling)."""
+    from paper_2503_16815_amd import workloads as W
+    pick = lambda a: None if a is None else np.ascontiguousarray(a[rows])
+    return W.KnapsackBatch(name=f"{kb.name}[sample]", mode=kb.mode, batch=len(rows), item_stride=kb.item_stride,
+                           knap_stride=kb.knap_stride, n_items=pick(kb.n_items), n_knapsacks=pick(kb.n_knapsacks),
+                           weights=pick(kb.weights), values=pick(kb.values), capacities=pick(kb.capacities),
+                           fill_order=pick(kb.fill_order), meta=dict(kb.meta), drop_time=pick(kb.drop_time))
 
+
+def run_solver(args):
+    """One workload through deft_knapsack_solve_batch.  Returns (line, parity)."""
     import torch
     from paper_2503_16815_amd import binding
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 1
-    if args.workload == "schedule":
-        return run_schedule(args)
     calls, desc, algo = make_workload(args.workload, args.batch_scale, args.per_k_calls or bool(args.only_k))
     if args.only_k:
         calls = [kb for kb in calls if kb.meta.get("k") == args.only_k]
@@ -265,11 +254,10 @@ def main() -> int:
         t_cpu += time.perf_counter() - t0
     touched = [int(r.touched_cells.sum()) for r in refs]
     table = [int(r.table_cells.sum()) for r in refs]
-    # The metric's cell-updates are the oracle's count for the whole job (touched cells of every
-    # stage).  The solver does not evaluate all of them: stages it settles without a sweep and,
-    # where every value equals its weight, the items after the row is full.  The roofline is
-    # priced on the cell-updates it does evaluate (swept_step); both counts are reported.
-    # (and, where every value equals its weight, the items that come after the row is full)
+    # The job's cell-updates are the oracle's count (touched cells of every stage).  The solver
+    # does not evaluate all of them: stages it settles without a sweep and, where every value
+    # equals its weight, the items after the row is full.  `value` and the roofline are priced
+    # on the cell-updates it does evaluate (swept_step); both counts are reported.
     not_swept = {path: [cells_not_swept(kb, r, path) for kb, r in zip(calls, refs)] for path in (False, True)}
     settled = sum(x[0] for x in not_swept[True])     # corrected below once the handle says which path runs
     after_full = sum(x[1] for x in not_swept[True])
@@ -292,9 +280,26 @@ def main() -> int:
     if not args.no_cpu:
         cpu_cells = recursion_cells if recursion_cells is not None else sum(touched)   # the oracle sweeps every stage
         cpu = dict(value=cpu_cells / t_cpu, unit="cell-updates/s", cores=int(refs[0].threads), kind="oracle",
-                   sample=f"the full step ({inst_step} instances, {cpu_cells} cell-updates), "
+                   sample=f"the full step ({inst_step} instances, {cpu_cells} cell-updates performed), "
                           f"instances split statically over {int(refs[0].threads)} threads, {t_cpu:.2f} s wall",
                    instances_per_s=inst_step / t_cpu)
+        if getattr(args, "single_thread", True):
+            # one thread, on a bounded sample of the same step (a stride through the instances)
+            per_inst = cpu_cells / max(inst_step, 1) / max(cpu["value"] / max(int(refs[0].threads), 1), 1.0)
+            want = max(1, min(inst_step, int(4.0 / max(per_inst, 1e-9))))      # about four seconds of one core
+            t1_cells, t1_time, t1_inst = 0, 0.0, 0
+            for kb in calls:
+                rows = np.unique(np.linspace(0, kb.batch - 1, max(1, want * kb.batch // inst_step)).astype(int))
+                part = subset(kb, rows)
+                t0 = time.perf_counter()
+                r1 = oracle.solve_batch(part, nthreads=1)
+                t1_time += time.perf_counter() - t0
+                t1_cells += int(r1.touched_cells.sum())
+                t1_inst += len(rows)
+            cpu["single_thread"] = dict(value=t1_cells / t1_time, unit="cell-updates/s", cores=1,
+                                        sample=f"{t1_inst} of the {inst_step} instances (evenly strided), "
+                                               f"{t1_cells} cell-updates, {t1_time:.2f} s wall",
+                                        instances_per_s=t1_inst / t1_time)
 
     # ---- GPU
     dev = torch.device("cuda", 0)
@@ -334,27 +339,6 @@ def main() -> int:
         prof = h.get_profile()
         h.set_profiling(False)
 
-        # The same candidate set as one call per k (the other way to read "a batch of 1024
-        # profiles, k = 1..4"): timed beside the headline so that both readings are on record.
-        per_k = None
-        if args.workload in ("resnet101", "vgg19") and len(calls) == 1 and plain_run and not args.no_per_k:
-            from paper_2503_16815_amd import workloads as W
-            gen, b0 = (W.resnet101_shaped, 1024) if args.workload == "resnet101" else (W.vgg19_shaped, 4096)
-            kdbs = [h.upload(gen(k=k, batch=b0)) for k in (1, 2, 3, 4)]
-            for _ in range(max(args.warmup, 1)):
-                for db in kdbs:
-                    h.solve_batch(db, stream)
-            stream.synchronize()
-            tk0 = time.perf_counter()
-            for _ in range(args.steps):
-                for db in kdbs:
-                    h.solve_batch(db, stream)
-            stream.synchronize()
-            tk1 = time.perf_counter()
-            per_k = dict(calls_per_step=4, ms_per_step=(tk1 - tk0) * 1e3 / args.steps,
-                         value=cells_step / ((tk1 - tk0) / args.steps))
-            del kdbs
-
         parity = True
         for db, ref in zip(dbs, refs):
             o = db.out
@@ -365,14 +349,14 @@ def main() -> int:
             parity &= bool(np.array_equal(o.assignment.cpu().numpy(), ref.assignment))
 
     ms_step = (t1 - t0) * 1e3 / args.steps
-    value = cells_step / (ms_step * 1e-3)
     # rows in LDS: the library counts the cell-updates its sweeps evaluated (C - w + 1 per swept
-    # item); the roofline is priced on that count.  For the sequential mode the same number
+    # item); value and roofline are priced on that count.  For the sequential mode the same number
     # follows from the oracle's results and the two rules (swept_step above): both are reported.
     replayed_swept = swept_step
     counted_swept = int(prof.swept_cell_updates) // args.steps if seq and info.seq_path in (1, 2) else None
     if counted_swept is not None:
         swept_step = counted_swept
+    value = swept_step / (ms_step * 1e-3)
     launches = int(prof.sweep_launches)
     sweep_s = float(prof.sweep_ms) * 1e-3
     algo_bytes_total = swept_step * args.steps * algo["bytes_per_cell"]
@@ -384,36 +368,44 @@ def main() -> int:
         algo = dict(algo, bytes_per_cell=algo_bytes_total / (swept_step * args.steps))
     achieved_gbs = algo_bytes_total / sweep_s / 1e9 if sweep_s > 0 else 0.0
     peak = PEAK_LDS_GBS if algo["bound"] == "lds" else PEAK_HBM_GBS
-    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter passes
-    # (FETCH_SIZE and WRITE_SIZE scaled by a copy of known size); only for the unmodified workload.
-    traffic = None
+    # HBM bytes per launch of the dominant kernel: NOT measured in this run, read from the
+    # committed rocprofv3 counter passes of this same command (FETCH_SIZE and WRITE_SIZE scaled
+    # by a copy of known size); only for the unmodified workload.
+    traffic = traffic_source = None
     kernel = "seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep_all" if seq else "jt_sweep_all")
     tf = os.path.join(ROOT, "profiles", f"{kernel}_{args.workload}_traffic.txt")
-    plain = args.batch_scale == 1.0 and not (args.per_k_calls or args.only_k or args.max_stages)
-    if plain and os.path.exists(tf):
+    if plain_run and os.path.exists(tf):
         try:
             with open(tf) as f:
                 traffic = float(json.load(f)["hbm_bytes_per_launch"])
+            traffic_source = (f"profiles/{os.path.basename(tf)}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this "
+                              f"command, committed; not measured in this run")
         except (ValueError, KeyError):
             traffic = None
     roofline = dict(
         bound=algo["bound"], achieved=achieved_gbs, peak=peak, unit="GB/s", frac=achieved_gbs / peak,
-        traffic=traffic,
+        traffic=traffic, traffic_source=traffic_source,
         kernel=kernel,
         bytes_per_cell=algo["bytes_per_cell"], launches=launches,
         avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
         algorithmic_bytes_per_launch=algo_bytes_total / max(launches, 1),
         swept_cell_updates_per_s=swept_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
-        frac_if_every_oracle_cell_counted=(cells_step * args.steps * algo["bytes_per_cell"] / sweep_s / 1e9) / peak
-        if sweep_s > 0 and algo["bound"] == "lds" else None,
         alu=dict(ops_per_cell=algo["ops_per_cell"], peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
                  frac=(swept_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
                  if sweep_s > 0 else 0.0))
+    if not seq:
+        # the table streams from HBM (the bound above); the LDS side of the same kernel, for the
+        # record: two shifted reads and one write per cell
+        roofline["lds"] = dict(bytes_per_cell=12.0, peak=PEAK_LDS_GBS,
+                               frac=(swept_step * args.steps * 12.0 / sweep_s / 1e9) / PEAK_LDS_GBS if sweep_s > 0 else 0.0)
     line = dict(
         metric="knapsack DP cell-updates/sec", value=value, unit="cell-updates/s", n_gpus=1,
         steps=args.steps, warmup=args.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype="int32", data="synthetic",
-        config=dict(workload=desc, instances_per_step=inst_step, cell_updates_per_step=cells_step,
+        config=dict(workload=desc,
+                    value_counts="cell-updates the kernels evaluate (cell_updates_swept_per_step); the job as the "
+                                 "oracle performs it holds cell_updates_per_step, see effective_cell_updates_per_s",
+                    instances_per_step=inst_step, cell_updates_per_step=cells_step,
                     cell_updates_swept_per_step=swept_step,
                     cell_updates_swept_per_step_replayed_from_oracle=replayed_swept if calls[0].mode == 0 else None,
                     table_cells_per_step=sum(table), seq_path=int(info.seq_path),
@@ -422,11 +414,106 @@ def main() -> int:
                     workgroups_per_cu=int(info.seq_workgroups_per_cu), scratch_bytes=int(info.scratch_bytes),
                     oracle_cell_updates_of_stages_settled_without_sweep=settled,
                     oracle_cell_updates_after_the_row_is_full=after_full,
-                    same_set_as_one_call_per_k=per_k, oracle_recursion_cell_updates_per_step=recursion_cells),
+                    oracle_recursion_cell_updates_per_step=recursion_cells),
+        effective_cell_updates_per_s=cells_step / (ms_step * 1e-3),
         instances_per_s=inst_step / (ms_step * 1e-3), parity_vs_oracle=parity,
         profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
                      sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
         roofline=roofline, cpu_baseline=cpu)
+    return line, parity
+
+
+def compact(line: dict) -> dict:
+    """The per-configuration record of the default run."""
+    r = line["roofline"]
+    out = dict(workload=line["config"]["workload"], steps=line["steps"], ms_per_step=line["ms_per_step"],
+               cell_updates_evaluated_per_step=line["config"]["cell_updates_swept_per_step"],
+               value=line["value"], unit=line["unit"],
+               kernel=r["kernel"], kernel_launches_per_step=r["launches"] / max(line["steps"], 1),
+               kernel_ms_per_step=line["profile"]["sweep_ms_per_step"],
+               roofline=dict(bound=r["bound"], bytes_per_cell=r["bytes_per_cell"], achieved=r["achieved"], peak=r["peak"],
+                             unit=r["unit"], frac=r["frac"], alu_frac=r["alu"]["frac"],
+                             alu_ops_per_cell=r["alu"]["ops_per_cell"]),
+               parity_vs_oracle=line["parity_vs_oracle"])
+    if "lds" in r:
+        out["roofline"]["lds_frac_at_12_bytes_per_cell"] = r["lds"]["frac"]
+    for key in ("instances_per_s", "candidate_iterations_per_s", "effective_cell_updates_per_s", "parity_checked"):
+        if key in line:
+            out[key] = line[key]
+    if line.get("cpu_baseline"):
+        out["cpu_baseline"] = {k: line["cpu_baseline"][k] for k in ("value", "unit", "cores", "sample")}
+    return out
+
+
+def measured_peaks() -> dict:
+    """Nominal peaks used for the rooflines beside what the library's calibration kernels reach
+    on this device (LDS: the sweep's access mix; HBM: a 1 GiB copy)."""
+    from paper_2503_16815_amd import binding
+    p = binding.measure_peaks(0)
+    return dict(
+        nominal=dict(lds_gbs=PEAK_LDS_GBS, hbm_gbs=PEAK_HBM_GBS, int32_lane_ops_per_s=PEAK_INT_LANE_OPS,
+                     basis=f"{N_CU} CUs x {LDS_BYTES_PER_CLK_PER_CU} B/clk/CU x {CLOCK_HZ / 1e9} GHz; HBM3E 8 TB/s; "
+                           f"{N_CU} CUs x 64 lanes x {CLOCK_HZ / 1e9} GHz"),
+        measured=dict(lds_read_gbs=float(p.lds_read_gbs), lds_read_write_gbs=float(p.lds_read_write_gbs),
+                      hbm_copy_gbs=float(p.hbm_copy_gbs), hbm_write_gbs=float(p.hbm_write_gbs),
+                      lds_read_write_bytes_per_clk_per_cu_at_nominal_clock=float(p.lds_read_write_gbs) * 1e9 / CLOCK_HZ / N_CU,
+                      compute_units=int(p.compute_units), clock_mhz_reported=int(p.clock_mhz_reported),
+                      how="deft_knapsack_measure_peaks: 4-byte conflict-free LDS reads; one shifted 4-byte read + one "
+                          "lane-addressed 4-byte write per cell; 1 GiB copy and fill kernels; best of three launches"))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet101",
+                    choices=["resnet101", "vgg19", "gpt2", "hetero", "backward", "inflation", "schedule", "tiny"])
+    ap.add_argument("--batch-scale", type=float, default=1.0, help="scale the batch (debug only)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
+    ap.add_argument("--per-k-calls", action="store_true",
+                    help="ResNet/VGG shapes: one call per k (4 calls of 1024 / 4096 instances) instead of one call "
+                         "holding the whole sweep over k")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel, so that a counter profile of this "
+                         "command holds a row of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--no-per-config", "--no-per-k", dest="no_per_config", action="store_true",
+                    help="default workload only: skip the other configurations and the peak calibration "
+                         "(profiling runs: keeps the kernel statistics to the headline launches)")
+    ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
+    ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (instances are independent; sharding is by "
+              "instance index and is not part of this build); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    run = run_schedule if args.workload == "schedule" else run_solver
+    line, parity = run(args)
+    headline = (args.workload == "resnet101" and args.batch_scale == 1.0 and
+                not (args.per_k_calls or args.only_k or args.max_stages or args.no_per_config))
+    if headline:
+        # every other configuration, measured in this same process: fewer steps, same code path
+        per_config = {}
+        for name, extra in (("tiny", {}), ("resnet101_one_call_per_k", dict(workload="resnet101", per_k_calls=True)),
+                            ("vgg19", {}), ("gpt2", {}), ("hetero", {}), ("backward", {}), ("inflation", {}),
+                            ("schedule", {})):
+            sub = argparse.Namespace(**vars(args))
+            sub.workload = name
+            sub.steps, sub.warmup, sub.single_thread = max(3, min(args.steps, 5)), 2, False
+            for k, v in extra.items():
+                setattr(sub, k, v)
+            one, ok = (run_schedule if sub.workload == "schedule" else run_solver)(sub)
+            per_config[name] = compact(one)
+            parity = parity and ok
+        line["per_config"] = per_config
+        line["parity_vs_oracle_every_config"] = bool(parity)
+        line["peaks"] = measured_peaks()
     print(json.dumps(line))
     return 0 if parity else 3
 

@@ -330,6 +330,22 @@ deft_status_t deft_knapsack_set_profiling(deft_knapsack_t *h, int32_t enable);
  * INVALID_ARG if profiling is off or no call has been made since. */
 deft_status_t deft_knapsack_get_profile(deft_knapsack_t *h, deft_knapsack_profile_t *out);
 
+/* What the device delivers, measured: for the benchmark's report of nominal and
+ * measured peaks.  Allocates and frees 2 GiB of device memory, launches on the default
+ * stream and waits; takes about a second. */
+typedef struct {
+    float lds_read_gbs;        /* conflict-free 4-byte LDS reads, every compute unit busy       */
+    float lds_read_write_gbs;  /* the DP sweep's mix: one shifted 4-byte read and one 4-byte
+                                  write (addressed by lane) per cell; bytes read + written      */
+    float hbm_copy_gbs;        /* 1 GiB device-to-device copy kernel; bytes read + written      */
+    float hbm_write_gbs;       /* 1 GiB fill kernel                                             */
+    int32_t compute_units;
+    int32_t clock_mhz_reported; /* the runtime's maximum shader clock                           */
+} deft_knapsack_peaks_t;
+
+/* INVALID_ARG (NULL, bad ordinal), DEVICE (not a gfx950, runtime failure), OOM. */
+deft_status_t deft_knapsack_measure_peaks(int32_t device, deft_knapsack_peaks_t *out);
+
 /* Static string for a status code ("DEFT_OK", ...); never NULL. */
 const char *deft_knapsack_status_string(int32_t status);
 

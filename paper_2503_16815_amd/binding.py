@@ -23,7 +23,7 @@ DEFT_OK, DEFT_ERR_INVALID_ARG, DEFT_ERR_LIMIT, DEFT_ERR_OVERFLOW, DEFT_ERR_OOM, 
 EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_destroy",
            "deft_knapsack_get_info", "deft_knapsack_set_profiling", "deft_knapsack_get_profile",
            "deft_knapsack_status_string", "deft_knapsack_simulate_schedule",
-           "deft_knapsack_solve_batch_static")
+           "deft_knapsack_solve_batch_static", "deft_knapsack_measure_peaks")
 STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 
 
@@ -64,6 +64,12 @@ class deft_knapsack_profile_t(ctypes.Structure):
                 ("swept_cell_updates", ctypes.c_int64)]
 
 
+class deft_knapsack_peaks_t(ctypes.Structure):
+    _fields_ = [("lds_read_gbs", ctypes.c_float), ("lds_read_write_gbs", ctypes.c_float),
+                ("hbm_copy_gbs", ctypes.c_float), ("hbm_write_gbs", ctypes.c_float),
+                ("compute_units", ctypes.c_int32), ("clock_mhz_reported", ctypes.c_int32)]
+
+
 _lib = None
 
 
@@ -93,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     lib.deft_knapsack_solve_batch_static.restype = ctypes.c_int
     lib.deft_knapsack_solve_batch_static.argtypes = [ctypes.c_int32, ctypes.c_int32,
                                                      ctypes.POINTER(deft_knapsack_batch_t)]
+    lib.deft_knapsack_measure_peaks.restype = ctypes.c_int
+    lib.deft_knapsack_measure_peaks.argtypes = [ctypes.c_int32, ctypes.POINTER(deft_knapsack_peaks_t)]
     lib.deft_knapsack_status_string.restype = ctypes.c_char_p
     lib.deft_knapsack_status_string.argtypes = [ctypes.c_int32]
     _lib = lib
@@ -259,6 +267,15 @@ def simulate_schedule(h: "DeftKnapsack", ds: DeviceSchedules,
     if rc != DEFT_OK:
         raise DeftError("deft_knapsack_simulate_schedule", rc)
     return ds.out
+
+
+def measure_peaks(device: int = 0) -> deft_knapsack_peaks_t:
+    """LDS and HBM rates measured by the library's calibration kernels."""
+    peaks = deft_knapsack_peaks_t()
+    rc = load_library().deft_knapsack_measure_peaks(device, ctypes.byref(peaks))
+    if rc != DEFT_OK:
+        raise DeftError("deft_knapsack_measure_peaks", rc)
+    return peaks
 
 
 def solve_batch_static(db: DeviceBatch, max_capacity: int, device: int = 0,

@@ -48,7 +48,7 @@ def test_binding_struct_layouts_match_header():
     fields = re.findall(r"\**\s*([a-z_0-9]+)\s*;", body)
     assert fields == [f[0] for f in b.deft_schedule_batch_t._fields_]
     assert ctypes.sizeof(b.deft_schedule_batch_t) == 4 * 4 + 11 * 8
-    for name in ("deft_knapsack_info_t", "deft_knapsack_profile_t", "deft_knapsack_config_t"):
+    for name in ("deft_knapsack_info_t", "deft_knapsack_profile_t", "deft_knapsack_config_t", "deft_knapsack_peaks_t"):
         body = re.search(r"typedef struct \{([^}]*)\} " + name + ";", hdr).group(1)
         fields = re.findall(r"\**\s*([a-z_0-9]+)\s*;", body)
         assert fields == [f[0] for f in getattr(b, name)._fields_], name
