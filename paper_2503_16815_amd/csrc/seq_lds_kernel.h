@@ -485,6 +485,11 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     if (tid < kMiscInts) misc[tid] = 0;
     for (int i = kMiscInts + tid; i < lay.guard_cells; i += T) misc[i] = INT_MIN;
     lds_sync<T>();
+    // Kept in registers for the whole kernel, so that the stage loop below never waits on
+    // memory for them: lane j of every wavefront holds capacity j and the j-th entry of the
+    // fill order (at most 64 knapsacks), and lane i of the first wavefront holds weight and
+    // value of item i (the first 64 items; longer lists reload the rest from the cache).
+    int cap_l = 0, ord_l = tid & 63, w_first = 0, v_first = 0;
     {
         uint32_t flags = 0;
         unsigned long long vs = 0;
@@ -493,8 +498,13 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         if (!counts_ok) {
             flags = 1;
         } else {
+            if ((tid & 63) < m) {
+                cap_l = cap[tid & 63];
+                if (ord) ord_l = ord[tid & 63];
+            }
             for (int i = tid; i < n; i += T) {
                 const int w = W[i], v = V[i];
+                if (i < 64) { w_first = w; v_first = v; }  // i == tid here: the first wavefront's lanes
                 if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
                 if (v != w) flags |= 4;
                 if constexpr (REC) {
@@ -502,10 +512,10 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 }
             }
             for (int j = tid; j < m; j += T) {
-                const int c = cap[j];
+                const int c = cap_l;
                 if (c < 0) flags |= 1; else if (c > a.max_capacity) flags |= 2;
                 if (ord) {
-                    const int o = ord[j];
+                    const int o = ord_l;
                     if (o < 0 || o >= m) {
                         flags |= 1;
                     } else {
@@ -546,16 +556,26 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     unsigned long long placed = 0;
     long long total = 0;
     const int stages = caps_sweep ? min(m, 1) : m;
-    auto stage_knapsack = [&](int s) { return uniform(ord ? ord[s] : s); };
-    auto stage_capacity = [&](int j) {
-        int C = uniform(cap[j]);
-        if constexpr (REC) {
-            if (caps_sweep) {  // one sweep at the largest capacity serves them all
-                for (int x = 1; x < m; ++x) C = max(C, uniform(cap[x]));
-            }
+    // (an out-of-range order entry was rejected above, so s and j are below 64 here)
+    auto stage_knapsack = [&](int s) { return __builtin_amdgcn_readlane(ord_l, s); };
+    int cap_max = 0;  // capacity sweep: one sweep at the largest capacity serves them all
+    if constexpr (REC) {
+        if (caps_sweep) {
+            cap_max = (tid & 63) < m ? cap_l : 0;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) cap_max = max(cap_max, __shfl_xor(cap_max, off));
+            cap_max = uniform(cap_max);
         }
-        return C;
+    }
+    auto stage_capacity = [&](int j) {
+        if constexpr (REC) {
+            if (caps_sweep) return cap_max;
+        }
+        return __builtin_amdgcn_readlane(cap_l, j);
     };
+    // weight and value of item i0 + lane, as the first wavefront's stage loop reads them
+    auto item_w = [&](int i0, int i) { return i >= n ? 0 : i0 == 0 ? w_first : W[i]; };
+    auto item_v = [&](int i0, int i) { return i >= n ? 0 : i0 == 0 ? v_first : V[i]; };
     int s = 0;
     while (true) {
         // The first wavefront prepares stages one after the other, settling those that need
@@ -600,8 +620,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 long long offered_weight = 0;
                 for (int i0 = 0; i0 < n; i0 += 64) {
                     const int i = i0 + tid;
-                    const int w = i < n ? W[i] : 0;
-                    const int v = i < n ? V[i] : 0;
+                    const int w = item_w(i0, i);
+                    const int v = item_v(i0, i);
                     const bool open = i < n && ((placed >> (i0 >> 6)) & 1ull) == 0;
                     const bool f = open && w <= C;
                     unplaced += __popcll(__ballot(open));
@@ -632,8 +652,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                         long long vsum = 0, lsum = 0;
                         for (int i0 = 0; i0 < n; i0 += 64) {
                             const int i = i0 + tid;
-                            const int w = i < n ? W[i] : 0;
-                            const int v = i < n ? V[i] : 0;
+                            const int w = item_w(i0, i);
+                            const int v = item_v(i0, i);
                             if (i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C && v > 0) {
                                 placed |= 1ull << (i0 >> 6);
                                 out_asg[i] = j;
@@ -663,8 +683,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                         int got = 0;
                         for (int i0 = 0; i0 < n; i0 += 64) {
                             const int i = i0 + tid;
-                            const int w = i < n ? W[i] : 0;
-                            const int v = i < n ? V[i] : 0;
+                            const int w = item_w(i0, i);
+                            const int v = item_v(i0, i);
                             unsigned long long mask =
                                 __ballot(i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C);
                             while (mask) {
@@ -747,7 +767,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 walk_cap = best.remain;
             }
             if (caps_sweep && (tid & 63) < m) {
-                sweep_cap = cap[tid & 63];
+                sweep_cap = cap_l;
                 sweep_value = row[sweep_cap] + (veqw ? sweep_cap : 0);
             }
         }
