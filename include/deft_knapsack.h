@@ -64,14 +64,29 @@ typedef struct {
     int32_t max_capacity;  /* sequential mode: largest capacity (0 = mode unused)          */
     int32_t max_c1;        /* joint mode: largest capacity of link 0 (0 = mode unused)     */
     int32_t max_c2;        /* joint mode: largest capacity of link 1                       */
-    uint32_t flags;        /* must be 0                                                    */
+    uint32_t flags;        /* 0, or DEFT_FLAG_VALUES_ARE_WEIGHTS                           */
 } deft_knapsack_config_t;
+
+/*
+ * DEFT_FLAG_VALUES_ARE_WEIGHTS: the caller promises that in every instance given to this
+ * handle each item's value equals its weight - the paper's own objective (Sec. III.B,
+ * Problem 1: the profit of a bucket is its communication time).  Requires 1 <= max_capacity
+ * <= 26623 (create returns DEFT_ERR_LIMIT otherwise, also when max_items is too long for the
+ * smaller rows' LDS).  The sequential-layout modes (SEQUENTIAL, RECURSIVE, CAPACITY_SWEEP,
+ * deft_knapsack_simulate_schedule) then run kernels that keep the DP row as 16-bit cells
+ * (row[c] - c lies in [-c, 0]), two per 32-bit word: half the LDS per instance, half the LDS
+ * instructions and packed 16-bit arithmetic per cell.  Results are bit-identical to those of a
+ * handle without the flag.  An instance that breaks the promise (some value != its weight)
+ * gets status DEFT_ERR_INVALID_ARG like any other bad input.  The joint and greedy modes are
+ * not affected.
+ */
+#define DEFT_FLAG_VALUES_ARE_WEIGHTS 1u
 
 /*
  * deft_knapsack_create: validate the limits, check that the device is a
  * gfx950, allocate the scratch (keep / choice tables, large rows) on
  * cfg->device and return a handle in *out.
- * Errors: INVALID_ARG (NULL, non-positive limits, flags != 0), LIMIT (limits
+ * Errors: INVALID_ARG (NULL, non-positive limits, unknown flag bits), LIMIT (limits
  * beyond what the library supports), OOM, DEVICE.  *out is NULL on error.
  */
 deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg, deft_knapsack_t **out);

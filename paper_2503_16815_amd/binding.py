@@ -25,6 +25,7 @@ EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_d
            "deft_knapsack_status_string", "deft_knapsack_simulate_schedule",
            "deft_knapsack_solve_batch_static", "deft_knapsack_measure_peaks")
 STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
+FLAG_VALUES_ARE_WEIGHTS = 1
 
 
 class deft_knapsack_config_t(ctypes.Structure):
@@ -168,12 +169,12 @@ class DeftKnapsack:
     """Owner of one deft_knapsack_t handle."""
 
     def __init__(self, max_batch: int, max_items: int, max_knapsacks: int, max_capacity: int = 0,
-                 max_c1: int = 0, max_c2: int = 0, device: int = 0):
+                 max_c1: int = 0, max_c2: int = 0, device: int = 0, flags: int = 0):
         self._lib = load_library()
         self._h = ctypes.c_void_p()
         self.device = torch.device("cuda", device)
         cfg = deft_knapsack_config_t(device, max_batch, max_items, max_knapsacks, max_capacity, max_c1,
-                                     max_c2, 0)
+                                     max_c2, flags)
         rc = self._lib.deft_knapsack_create(ctypes.byref(cfg), ctypes.byref(self._h))
         if rc != DEFT_OK:
             self._h = ctypes.c_void_p()

@@ -19,6 +19,7 @@ constexpr int32_t kMaxBatch = 1 << 20;
 constexpr int32_t kMaxCapacity = 1 << 24;
 constexpr int32_t kMaxJointCapacity = 4095;
 constexpr int32_t kMaxIterations = 4096;
+constexpr int32_t kMaxPacked16Capacity = 26623;  // the longest row of 16-bit cells that is compiled
 
 struct DeviceGuard {
     int prev = -1;
@@ -98,7 +99,7 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
 {
     if (out) *out = nullptr;
     if (!cfg || !out) return DEFT_ERR_INVALID_ARG;
-    if (cfg->flags != 0 || cfg->device < 0 || cfg->max_batch < 1 || cfg->max_items < 1 ||
+    if ((cfg->flags & ~(uint32_t)DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0 || cfg->device < 0 || cfg->max_batch < 1 || cfg->max_items < 1 ||
         cfg->max_knapsacks < 1 || cfg->max_capacity < 0 || cfg->max_c1 < 0 || cfg->max_c2 < 0)
         return DEFT_ERR_INVALID_ARG;
     const bool want_seq = cfg->max_capacity > 0;
@@ -109,6 +110,8 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
         cfg->max_c2 > kMaxJointCapacity)
         return DEFT_ERR_LIMIT;
     if (want_joint && cfg->max_knapsacks < 2) return DEFT_ERR_INVALID_ARG;
+    const bool packed16 = (cfg->flags & DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0;
+    if (packed16 && (!want_seq || cfg->max_capacity > kMaxPacked16Capacity)) return DEFT_ERR_LIMIT;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess) {
@@ -135,7 +138,8 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
     if (want_seq) {
         const int lds_wg = (int)prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin
                                                                 : (int)prop.sharedMemPerBlock;
-        if (seq_lds_plan(cfg->max_capacity, cfg->max_items, cfg->max_knapsacks, cfg->max_batch, lds_wg, &h->lds_plan) &&
+        if (seq_lds_plan(cfg->max_capacity, cfg->max_items, cfg->max_knapsacks, cfg->max_batch, lds_wg, packed16,
+                         &h->lds_plan) &&
             seq_lds_prepare(&h->lds_plan) == hipSuccess && seq_lds_rec_prepare(h->lds_plan) == hipSuccess) {
             h->seq_path = h->lds_plan.threads == 64 ? 1 : 2;
             st = alloc(&h->keep, h->lds_plan.scratch_bytes, &h->scratch_bytes);
@@ -148,6 +152,9 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
                     st = DEFT_ERR_DEVICE;
                 }
             }
+        } else if (packed16) {
+            (void)hipGetLastError();
+            st = DEFT_ERR_LIMIT;   // (an item list too long for the packed row's LDS)
         } else {
             (void)hipGetLastError();
             h->seq_path = 3;

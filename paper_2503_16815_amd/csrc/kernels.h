@@ -27,6 +27,7 @@ struct BatchArgs {
 // instances per workgroup; otherwise one workgroup).  Each lane keeps
 // `cells_per_thread` row cells in registers.
 struct SeqLdsPlan {
+    int32_t packed16;          // 1: rows of 16-bit cells (values equal weights, capacities <= 26623)
     int32_t variant;           // index into the compiled (threads, cells_per_thread) table
     int32_t threads;           // T
     int32_t cells_per_thread;  // K
@@ -44,13 +45,22 @@ struct SeqLdsPlan {
 };
 
 // Picks the variant for the limits; returns false when no LDS variant fits.
+// packed16: the kernels with rows of 16-bit cells (every value equals its weight).
 bool seq_lds_plan(int32_t max_capacity, int32_t max_items, int32_t max_knapsacks, int32_t max_batch,
-                  int32_t lds_per_wg_bytes, SeqLdsPlan *plan);
+                  int32_t lds_per_wg_bytes, bool packed16, SeqLdsPlan *plan);
 // Sets the kernel's dynamic-LDS attribute and queries occupancy.
 hipError_t seq_lds_prepare(SeqLdsPlan *plan);
 // `swept_cells` (device, may be null): every stage adds the cell-updates its sweep evaluated.
 hipError_t seq_lds_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
                           hipStream_t stream, unsigned long long *swept_cells);
+// The kernels with rows of 16-bit cells (seq_lds_p16.hip, seq_lds_p16_rec.hip); the launchers
+// above forward to them when the plan says packed16.
+hipError_t seq_lds_p16_prepare(const SeqLdsPlan &plan, int *wg_per_cu);
+hipError_t seq_lds_p16_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
+                              hipStream_t stream, unsigned long long *swept_cells);
+hipError_t seq_lds_p16_rec_prepare(const SeqLdsPlan &plan);
+hipError_t seq_lds_p16_rec_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
+                                  hipStream_t stream, unsigned long long *swept_cells);
 // Algorithm 1 (recursive mode) under the same plan and scratch (seq_lds_rec.hip).
 hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan);
 hipError_t seq_lds_rec_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,

@@ -423,6 +423,227 @@ __device__ __forceinline__ int sweep_dispatch(int nchunk, int32_t *row, uint32_t
     return 0;
 }
 
+// ---- rows of 16-bit cells (P16 kernels) -----------------------------------------------
+// Where every value equals its weight (the paper's Problem 1) the row is kept as
+// row[c] - c, which lies in [-c, 0]: with capacities up to 32766 it fits 16 bits.  The P16
+// kernels store two cells per 32-bit word, in registers and in LDS: word (j * T + t) holds
+// cell (2j * T + t) in its low half and cell ((2j + 1) * T + t) in its high half, so lane t
+// owns "pair j" = register slots 2j and 2j + 1.  Half the LDS per instance (more workgroups
+// per compute unit), half the LDS instructions per cell, and packed 16-bit arithmetic:
+//   cand pair = row pair shifted by w cells; diff = own - cand (negative where the item is
+//   taken: both lie in [-32767, 0], so the difference cannot overflow); own = max(own, cand);
+//   the two sign bits of diff are shifted into the keep word.
+// Every LDS access stays an aligned 32-bit one.  With s = t - w = -a * T + r (0 <= r < T) slot
+// k of lane t needs logical slot k - a of column r.  For even a that is a whole stored pair;
+// for odd a it is the high half of one stored word and the low half of the next, which one
+// byte permute assembles.  A light item (w <= T) has a in {0, 1}; every lane then reads words
+// j * T + r for j = -1 .. NP-1 (the word at j = -1 lies in the guard zone, T words holding
+// -32767 in both halves, which no cell can fall below), and a wavefront whose lanes all have
+// a = 0 (its first lane is at or above w: most wavefronts, for the usual light items) skips
+// the permutes and the guard read.  Heavy items compute a per lane and clamp each word index
+// into the guard.
+// The keep word of (item, lane) holds pair j's low-half bit at bit j and its high-half bit at
+// bit 16 + j (at most 16 pairs per lane).
+constexpr int kGuard16 = (int)0x80018001;  // -32767 in both halves
+
+__device__ __forceinline__ uint32_t pk_sub_i16(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_pk_sub_i16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+__device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_pk_max_i16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+// acc = 2 * acc + (sign bit of each half of diff, at bits 0 and 16)
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t shift_in_signs(uint32_t acc, uint32_t diff)
+{
+    const ushort2_t s = __builtin_bit_cast(ushort2_t, diff) >> (ushort2_t)(15);
+    return (acc << 1) | __builtin_bit_cast(uint32_t, s);
+}
+// Cell c of a packed row (sign-extended).
+template <int T>
+__device__ __forceinline__ int row16_cell(const int32_t *row, int c)
+{
+    const int k = c / T, t = c - k * T;
+    const int word = row[(k >> 1) * T + t];
+    return (int)(int16_t)((uint32_t)word >> ((k & 1) * 16));
+}
+
+// All offered items of one stage on a packed row of NP pairs per lane (cells 0 .. 2 NP T - 1
+// >= C).  Same contract as sweep_stage (VEQW only): returns the number of items swept.
+template <int T, int NP, bool REC, bool SKIP_UNCHANGED>
+__device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, int tid, int nact, const OfferedItem *list,
+                                                uint32_t *kp, unsigned long long &nzm, BestLevel &best, int C,
+                                                int32_t *unfinished)
+{
+    constexpr bool STOP_WHEN_FULL = !REC;
+    constexpr int kCheckEvery = 8;
+    static_assert(NP >= 1 && NP <= 16, "the take bits of a lane fit one keep word");
+    const int wave_first = tid & ~63;
+    const int lane = tid & 63;
+    auto load_chunk = [&](int first) {
+        return first + lane < nact ? load_item_wv(list + first + lane) : make_int2(0, 0);
+    };
+    auto load_probe_chunk = [&](int first) {
+        return REC && first + lane < nact ? load_item_pad(list + first + lane) : -1;
+    };
+    int2 cur = load_chunk(0);
+    int cur_p = load_probe_chunk(0);
+    uint32_t own[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        own[j] = ((uint32_t)(-(2 * j * T + tid)) & 0xffffu) | ((uint32_t)(-((2 * j + 1) * T + tid)) << 16);
+        row[j * T + tid] = (int32_t)own[j];
+    }
+    lds_sync<T>();  // initial row visible to every lane
+
+    const int m0w = uniform((int)row_off + wave_first * 4);
+    uint32_t nz_acc = 0;
+    auto hand_over = [&](int q) {
+        if ((tid & 63) == (q >> 6)) nzm |= (unsigned long long)nz_acc << (q & 32);
+        nz_acc = 0;
+    };
+    constexpr uint32_t kSelSame = 0x07060504u;   // the stored pair itself
+    constexpr uint32_t kSelCross = 0x05040302u;  // high half of the word below, low half of this one
+    // KIND 0: whole wavefront at or above w (no permutes); 1: light item, mixed lanes; 2: heavy item
+    auto item = [&](auto kind_tag, int q, int w) {
+        constexpr int KIND = decltype(kind_tag)::value;
+        uint32_t acc = 0;
+        uint32_t cand[NP];
+        int probe_at = -1, probe = 0;
+        if constexpr (REC) {
+            probe_at = __builtin_amdgcn_readlane(cur_p, q & 63);
+            probe = row16_cell<T>(row, max(probe_at, 0));
+        }
+        if constexpr (KIND == 0) {
+            const int32_t *src = row + (tid - w);
+#pragma unroll
+            for (int j = NP - 1; j >= 0; --j) cand[j] = (uint32_t)src[j * T];
+        } else if constexpr (KIND == 1) {
+            const int below = tid < w ? 1 : 0;
+            const int32_t *src = row + (tid - w + below * T);
+            const uint32_t sel = below ? kSelCross : kSelSame;
+            uint32_t d[NP + 1];
+#pragma unroll
+            for (int j = NP; j >= 0; --j) d[j] = (uint32_t)src[(j - 1) * T];  // d[j] = word j - 1
+#pragma unroll
+            for (int j = NP - 1; j >= 0; --j) cand[j] = __builtin_amdgcn_perm(d[j + 1], d[j], sel);
+        } else {
+            const int a = tid < w ? (w - tid + T - 1) / T : 0;
+            const int r = tid - w + a * T, e = a >> 1;
+            const uint32_t sel = (a & 1) ? kSelCross : kSelSame;
+#pragma unroll
+            for (int j = NP - 1; j >= 0; --j) {
+                const uint32_t hi = (uint32_t)row[max(j - e, -1) * T + r];
+                const uint32_t lo = (uint32_t)row[max(j - e - 1, -1) * T + r];
+                cand[j] = __builtin_amdgcn_perm(hi, lo, sel);
+            }
+        }
+#pragma unroll
+        for (int j = NP - 1; j >= 0; --j) {
+            const uint32_t diff = pk_sub_i16(own[j], cand[j]);
+            own[j] = pk_max_i16(own[j], cand[j]);
+            acc = shift_in_signs(acc, diff);  // pair j ends at bits j and 16 + j
+        }
+        if constexpr (REC) {
+            const int level_value = uniform(probe) + probe_at;
+            if (probe_at >= 0 && level_value > best.value) best = BestLevel{level_value, q, probe_at};
+        }
+        constexpr int kGroup = 8;  // pairs per write-back group
+        constexpr int kGroups = (NP - 1) / kGroup + 1;
+        bool group_changed[kGroups];
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            const int lo = g * kGroup, hi = lo + kGroup - 1 < NP - 1 ? lo + kGroup - 1 : NP - 1;
+            const uint32_t m = ((1u << (hi - lo + 1)) - 1u) << lo;
+            group_changed[g] = !SKIP_UNCHANGED || __builtin_amdgcn_ballot_w64((acc & (m | (m << 16))) != 0) != 0ull;
+        }
+        lds_sync<T>();  // every lane has read the old row
+
+        SlotsDown<(NP - 1) / kGroup>::all([&](auto gc) {
+            constexpr int lo = gc.value * kGroup;
+            constexpr int hi = lo + kGroup - 1 < NP - 1 ? lo + kGroup - 1 : NP - 1;
+            static_assert(hi * T * 4 <= 65535, "the add-TID offset reaches every pair");
+            if (group_changed[gc.value]) {
+                m0_settle(m0w);
+                SlotsDownTo<hi, lo>::all([&](auto jc) { write_addtid<jc.value * T * 4>(m0w, (int)own[jc.value]); });
+            }
+        });
+        bool nz;
+        if constexpr (SKIP_UNCHANGED) {
+            nz = false;
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) nz = nz || group_changed[g];
+        } else {
+            nz = __builtin_amdgcn_ballot_w64(acc != 0) != 0ull;
+        }
+        if (nz) kp[(size_t)q * T + tid] = acc;
+        nz_acc |= (uint32_t)nz << (q & 31);
+        if ((q & 31) == 31) hand_over(q);
+        wait_lds();
+        lds_sync<T>();  // the new row is visible
+    };
+    auto row_is_full = [&](int q) -> bool {
+        if constexpr (!STOP_WHEN_FULL) {
+            return false;
+        } else {
+            if ((q % kCheckEvery) != kCheckEvery - 1) return false;
+            uint32_t any = 0;
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {  // the cells above C (in the top two pairs at most) do not count
+                uint32_t m = 0xffffffffu;
+                if (j >= NP - 2) m = (2 * j * T + tid <= C ? 0xffffu : 0u) | ((2 * j + 1) * T + tid <= C ? 0xffff0000u : 0u);
+                any |= own[j] & m;
+            }
+            const bool wave_full = __builtin_amdgcn_ballot_w64(any != 0) == 0ull;
+            if constexpr (T == 64) {
+                return wave_full;
+            } else {
+                if (!wave_full && (tid & 63) == 0) *unfinished = q + 1;
+                lds_sync<T>();
+                return uniform(*unfinished) != q + 1;
+            }
+        }
+    };
+
+    for (int q0 = 0; q0 < nact; q0 += 64) {
+        const int2 nxt = load_chunk(q0 + 64);
+        const int nxt_p = load_probe_chunk(q0 + 64);
+        const int q1 = min(q0 + 64, nact);
+        for (int q = q0; q < q1; ++q) {
+            const int w = __builtin_amdgcn_readlane(cur.x, q & 63);
+            if (w <= wave_first) item(std::integral_constant<int, 0>{}, q, w);
+            else if (w <= T) item(std::integral_constant<int, 1>{}, q, w);
+            else item(std::integral_constant<int, 2>{}, q, w);
+            if (row_is_full(q)) { hand_over(q); return q + 1; }
+        }
+        cur = nxt;
+        cur_p = nxt_p;
+    }
+    if (nact > 0) hand_over(nact - 1);
+    return nact;
+}
+
+// Picks the sweep_stage_p16 instance for the stage's pair count (1 .. N).
+template <int T, bool REC, bool SKIP_UNCHANGED, int N>
+__device__ __forceinline__ int sweep_dispatch_p16(int npair, int32_t *row, uint32_t row_off, int tid, int nact,
+                                                   const OfferedItem *list, uint32_t *kp, unsigned long long &nzm,
+                                                   BestLevel &best, int C, int32_t *unfinished)
+{
+    if (npair == N) {
+        return sweep_stage_p16<T, N, REC, SKIP_UNCHANGED>(row, row_off, tid, nact, list, kp, nzm, best, C, unfinished);
+    } else if constexpr (N > 1) {
+        return sweep_dispatch_p16<T, REC, SKIP_UNCHANGED, N - 1>(npair, row, row_off, tid, nact, list, kp, nzm, best, C,
+                                                                 unfinished);
+    }
+    return 0;
+}
+
 // WPE = wavefronts per SIMD the register budget is held to (LDS allows that many).
 // REC = false: the sequential mode.  REC = true: the modes that read more than row[C] off
 // one sweep, chosen by a.mode at run time:
@@ -431,11 +652,14 @@ __device__ __forceinline__ int sweep_dispatch(int nchunk, int32_t *row, uint32_t
 //   the capacity sweep (Sec. IV.C feedback): one sweep at the largest of the instance's
 //   capacities, then the value at each capacity is a cell of the final row and each
 //   capacity gets a walk of its own, the wavefronts of the instance sharing the walks.
-template <int T, int K, int G, int WPE, bool REC>
+// P16: rows of 16-bit cells (see sweep_stage_p16); every instance must have values equal to
+// its weights, which the handle's creator promised, and one that has not is refused.
+template <int T, int K, int G, int WPE, bool REC, bool P16>
 __global__ void __launch_bounds__(T == 64 ? 256 : T, WPE)
 seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_per_inst, OfferedItem *lists,
                int list_stride, unsigned long long *swept_cells)
 {
+    static_assert(!P16 || (K % 2 == 0 && K <= 32 && K * T <= 32767), "packed rows: whole pairs, one keep word, 16-bit cells");
     extern __shared__ __align__(16) int32_t lds_raw[];
     static_assert(K <= 64, "at most 64 segments per wavefront");
     constexpr int NW = (K + 31) / 32;
@@ -483,7 +707,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
 
     // ---- per-instance validation -------------------------------------------
     if (tid < kMiscInts) misc[tid] = 0;
-    for (int i = kMiscInts + tid; i < lay.guard_cells; i += T) misc[i] = INT_MIN;
+    for (int i = kMiscInts + tid; i < lay.guard_cells; i += T) misc[i] = P16 ? kGuard16 : INT_MIN;
     lds_sync<T>();
     // Kept in registers for the whole kernel, so that the stage loop below never waits on
     // memory for them: lane j of every wavefront holds capacity j and the j-th entry of the
@@ -506,7 +730,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 const int w = W[i], v = V[i];
                 if (i < 64) { w_first = w; v_first = v; }  // i == tid here: the first wavefront's lanes
                 if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
-                if (v != w) flags |= 4;
+                if (v != w) flags |= P16 ? 5 : 4;
                 if constexpr (REC) {
                     if (levels && drop[i] < 0) flags |= 1;
                 }
@@ -747,14 +971,22 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         BestLevel best{0, 0, 0};
         const int light_max = lay.guard_cells - kMiscInts;
         int swept;
-        if (veqw)
+        if constexpr (P16)
+            swept = sweep_dispatch_p16<T, REC, kSkipUnchanged, K / 2>(uniform((C / T + 2) / 2), row, row_off, tid, nact, list, kp,
+                                                                      nzm, best, C, &misc[7]);
+        else if (veqw)
             swept = sweep_dispatch<T, G, NW, ADDTID, true, REC, kSkipUnchanged, NCH>(nchunk, row, row_off, light_max, tid, nact, list,
                                                                      kp, nzm, best, C, &misc[7]);
         else
             swept = sweep_dispatch<T, G, NW, ADDTID, false, REC, kSkipUnchanged, NCH>(nchunk, row, row_off, light_max, tid, nact, list,
                                                                       kp, nzm, best, C, &misc[7]);
 
-        int value = uniform(row[C]) + (veqw ? C : 0);
+        // the value at capacity c as the final row holds it
+        auto row_value = [&](int c) {
+            if constexpr (P16) return row16_cell<T>(row, c) + c;
+            else return row[c] + (veqw ? c : 0);
+        };
+        int value = uniform(row_value(C));
         // where the walk starts: the last offered item at the full capacity, or (Algorithm 1)
         // the last item of the best level at that level's remaining time
         int walk_from = swept - 1, walk_cap = C;  // items that were not swept were not taken
@@ -768,7 +1000,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             }
             if (caps_sweep && (tid & 63) < m) {
                 sweep_cap = cap_l;
-                sweep_value = row[sweep_cap] + (veqw ? sweep_cap : 0);
+                sweep_value = row_value(sweep_cap);
             }
         }
 
@@ -845,7 +1077,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                         if ((nzw >> (qd & 63)) & 1ull) {
                             const uint32_t word = __hip_atomic_load(&kp[((size_t)qd * NW + (k >> 5)) * T + lane],
                                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            bit = (word >> (k & 31)) & 1u;
+                            bit = (word >> (P16 ? (k & 1) * 16 + (k >> 1) : (k & 31))) & 1u;
                         }
                     } else {
                         broken = true;
@@ -922,7 +1154,7 @@ struct Variant {
 };
 
 #define DEFT_VARIANT(T, K, G, WPE, GUARD) \
-    { T, K, G, GUARD, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, G, WPE, REC>) }
+    { T, K, G, GUARD, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, G, WPE, REC, false>) }
 template <bool REC>
 const Variant *variant_table()
 {
@@ -941,7 +1173,30 @@ const Variant *variant_table()
 #undef DEFT_VARIANT
 constexpr int kNumVariants = 8;
 
-template <int T, int K, int G, int WPE, bool REC>
+// Rows of 16-bit cells: the same lane and slot counts (the 38-slot one is out of the 16-bit
+// range); the guard zone is one pair row (T words) above 64 words that hold the scratch ints,
+// and the register budget always allows the 8 wavefronts per SIMD that the smaller rows leave
+// room for (two workgroups of 12 or 16 wavefronts for the two largest).
+#define DEFT_VARIANT16(T, K, WPE) \
+    { T, K, 2, T + 64, reinterpret_cast<const void *>(&seq_lds_kernel<T, K, 2, WPE, REC, true>) }
+template <bool REC>
+const Variant *variant_table16()
+{
+    static const Variant table[] = {
+    DEFT_VARIANT16(64, 16, 8),     // capacity <= 1023
+    DEFT_VARIANT16(256, 16, 8),    // <= 4095
+    DEFT_VARIANT16(256, 32, 8),    // <= 8191
+    DEFT_VARIANT16(512, 20, 8),    // <= 10239
+    DEFT_VARIANT16(512, 26, 8),    // <= 13311: 29 KB per workgroup, four workgroups of eight wavefronts per CU
+    DEFT_VARIANT16(768, 26, 6),    // <= 19967: two workgroups of twelve wavefronts
+    DEFT_VARIANT16(1024, 26, 8),   // <= 26623: two workgroups of sixteen wavefronts
+    };
+    return table;
+}
+#undef DEFT_VARIANT16
+constexpr int kNumVariants16 = 7;
+
+template <int T, int K, int G, int WPE, bool REC, bool P16>
 hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
                       unsigned long long *swept_cells)
 {
@@ -949,7 +1204,7 @@ hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hi
     const unsigned grid = (unsigned)((a.batch + p.inst_per_wg - 1) / p.inst_per_wg);
     uint32_t *keep = static_cast<uint32_t *>(scratch);
     OfferedItem *lists = reinterpret_cast<OfferedItem *>(static_cast<char *>(scratch) + p.keep_bytes);
-    hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE, REC>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
+    hipLaunchKernelGGL((seq_lds_kernel<T, K, G, WPE, REC, P16>), dim3(grid), dim3(p.wg_threads), (size_t)p.lds_bytes, st,
                        a, lay, keep, p.keep_words_per_inst, lists, p.n_pad, swept_cells);
     return hipGetLastError();
 }
@@ -959,14 +1214,30 @@ hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
                           unsigned long long *swept_cells)
 {
     switch (p.variant) {
-    case 0: return launch_one<64, 16, 4, 5, REC>(p, a, scratch, st, swept_cells);
-    case 1: return launch_one<256, 16, 4, 7, REC>(p, a, scratch, st, swept_cells);
-    case 2: return launch_one<256, 32, 4, 4, REC>(p, a, scratch, st, swept_cells);
-    case 3: return launch_one<512, 20, 1, 8, REC>(p, a, scratch, st, swept_cells);
-    case 4: return launch_one<512, 26, 1, 6, REC>(p, a, scratch, st, swept_cells);
-    case 5: return launch_one<768, 26, 1, 6, REC>(p, a, scratch, st, swept_cells);
-    case 6: return launch_one<1024, 26, 1, 4, REC>(p, a, scratch, st, swept_cells);
-    case 7: return launch_one<1024, 38, 2, 4, REC>(p, a, scratch, st, swept_cells);
+    case 0: return launch_one<64, 16, 4, 5, REC, false>(p, a, scratch, st, swept_cells);
+    case 1: return launch_one<256, 16, 4, 7, REC, false>(p, a, scratch, st, swept_cells);
+    case 2: return launch_one<256, 32, 4, 4, REC, false>(p, a, scratch, st, swept_cells);
+    case 3: return launch_one<512, 20, 1, 8, REC, false>(p, a, scratch, st, swept_cells);
+    case 4: return launch_one<512, 26, 1, 6, REC, false>(p, a, scratch, st, swept_cells);
+    case 5: return launch_one<768, 26, 1, 6, REC, false>(p, a, scratch, st, swept_cells);
+    case 6: return launch_one<1024, 26, 1, 4, REC, false>(p, a, scratch, st, swept_cells);
+    case 7: return launch_one<1024, 38, 2, 4, REC, false>(p, a, scratch, st, swept_cells);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <bool REC>
+hipError_t launch_variant16(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
+                            unsigned long long *swept_cells)
+{
+    switch (p.variant) {
+    case 0: return launch_one<64, 16, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 1: return launch_one<256, 16, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 2: return launch_one<256, 32, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 3: return launch_one<512, 20, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 4: return launch_one<512, 26, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 5: return launch_one<768, 26, 2, 6, REC, true>(p, a, scratch, st, swept_cells);
+    case 6: return launch_one<1024, 26, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
     default: return hipErrorInvalidValue;
     }
 }
@@ -975,12 +1246,14 @@ hipError_t launch_variant(const SeqLdsPlan &p, const BatchArgs &a, void *scratch
 // workgroups the runtime would place on a compute unit.  The attribute belongs to the
 // kernel, not to the handle, so it is set to the most any handle on this variant can ask
 // for (the variant's full row): a later, smaller handle never lowers it under an earlier one.
-template <bool REC>
+template <bool REC, bool P16>
 hipError_t prepare_variant(const SeqLdsPlan &plan, int *wg_per_cu)
 {
-    const Variant &v = variant_table<REC>()[plan.variant];
+    const Variant *table;
+    if constexpr (P16) table = variant_table16<REC>(); else table = variant_table<REC>();
+    const Variant &v = table[plan.variant];
     const void *fn = v.fn;
-    const int full_row = (v.guard + v.cells * v.threads) * 4 * plan.inst_per_wg;
+    const int full_row = (v.guard + (P16 ? v.cells / 2 : v.cells) * v.threads) * 4 * plan.inst_per_wg;
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, full_row);
     if (e != hipSuccess) return e;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(wg_per_cu, fn, plan.wg_threads, (size_t)plan.lds_bytes);

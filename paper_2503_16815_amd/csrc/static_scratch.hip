@@ -110,7 +110,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch_static(int32_t device, int32_
     // the same plan a handle with these limits would get; rows that need global memory,
     // and batches whose keep table and lists exceed the array, are refused
     SeqLdsPlan plan{};
-    if (!seq_lds_plan(max_capacity, b->item_stride, b->knap_stride, b->batch, d->lds_per_wg, &plan))
+    if (!seq_lds_plan(max_capacity, b->item_stride, b->knap_stride, b->batch, d->lds_per_wg, false, &plan))
         return DEFT_ERR_LIMIT;
     if (plan.scratch_bytes > kStaticScratchBytes) return DEFT_ERR_LIMIT;
     if (plan.variant < 0 || plan.variant >= kVariants) return DEFT_ERR_DEVICE;

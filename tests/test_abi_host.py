@@ -79,7 +79,9 @@ def test_create_rejects_bad_configs_without_a_device(lib):
 
     assert create(None, ctypes.byref(h)) == 1
     assert create(ctypes.byref(Cfg(**ok)), None) == 1
-    assert rc(flags=1) == 1
+    assert rc(flags=2) == 1                              # an unknown flag bit
+    assert rc(flags=1, max_capacity=26624) == 2          # 16-bit rows end at 26623 cells
+    assert rc(flags=1, max_capacity=0, max_c1=10, max_c2=10) == 2   # the flag needs the sequential layout
     assert rc(max_batch=0) == 1
     assert rc(max_items=0) == 1
     assert rc(max_knapsacks=0) == 1
@@ -106,6 +108,12 @@ def test_solve_and_misc_reject_null_handles(lib):
     assert lib.deft_knapsack_get_profile(None, None) == 1
     lib.deft_knapsack_destroy.argtypes = [ctypes.c_void_p]
     lib.deft_knapsack_destroy(None)                      # NULL-safe
+    lib.deft_knapsack_solve_batch_static.restype = ctypes.c_int
+    lib.deft_knapsack_solve_batch_static.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    assert lib.deft_knapsack_solve_batch_static(0, 100, None) == 1
+    lib.deft_knapsack_measure_peaks.restype = ctypes.c_int
+    lib.deft_knapsack_measure_peaks.argtypes = [ctypes.c_int32, ctypes.c_void_p]
+    assert lib.deft_knapsack_measure_peaks(0, None) == 1
 
 
 def test_bench_refuses_more_than_one_gpu():
