@@ -147,8 +147,9 @@ def run_schedule(args):
     t_cpu = time.perf_counter() - t0
     dev = torch.device("cuda", 0)
     stream = torch.cuda.Stream(device=dev)
+    packed16 = bool(getattr(args, "packed16", False))
     with binding.DeftKnapsack(device=0, max_batch=sb.batch, max_items=sb.n_buckets, max_knapsacks=2,
-                              max_capacity=cap) as h:
+                              max_capacity=cap, flags=1 if packed16 else 0) as h:
         info = h.info()
         ds = binding.DeviceSchedules(sb, dev)
         torch.cuda.synchronize(dev)
@@ -235,6 +236,13 @@ def run_solver(args):
     cap = max(int(kb.capacities.max()) for kb in calls)
     limits = dict(max_batch=max(kb.batch for kb in calls), max_items=max(kb.item_stride for kb in calls),
                   max_knapsacks=max(kb.knap_stride for kb in calls))
+    packed16 = bool(getattr(args, "packed16", False))
+    if packed16:
+        limits["flags"] = 1
+        desc += " [rows of 16-bit cells]"
+        # two 16-bit cells per LDS word and per packed instruction: 2 B read + 2 B written per cell;
+        # perm (lanes below the shift only), sub, max, shift, shift-or per pair of cells
+        algo = dict(bound="alu", bytes_per_cell=4.0, ops_per_cell=2.5)
     if seq:
         limits["max_capacity"] = cap
     else:
@@ -367,7 +375,7 @@ def run_solver(args):
         algo_bytes_total = int(prof.streamed_row_cells) * 4.0 + swept_step * args.steps / 8.0
         algo = dict(algo, bytes_per_cell=algo_bytes_total / (swept_step * args.steps))
     achieved_gbs = algo_bytes_total / sweep_s / 1e9 if sweep_s > 0 else 0.0
-    peak = PEAK_LDS_GBS if algo["bound"] == "lds" else PEAK_HBM_GBS
+    peak = PEAK_HBM_GBS if algo["bound"] == "hbm" else PEAK_LDS_GBS
     # HBM bytes per launch of the dominant kernel: NOT measured in this run, read from the
     # committed rocprofv3 counter passes of this same command (FETCH_SIZE and WRITE_SIZE scaled
     # by a copy of known size); only for the unmodified workload.
@@ -393,6 +401,15 @@ def run_solver(args):
         alu=dict(ops_per_cell=algo["ops_per_cell"], peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
                  frac=(swept_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
                  if sweep_s > 0 else 0.0))
+    if algo["bound"] == "alu":
+        # rows of 16-bit cells: the vector ALU is the nearer bound (64 / 2.5 = 25.6 cells per clock
+        # and CU against 128 B / 4 B = 32 for LDS), so it is the one the fraction is taken against;
+        # the LDS side is kept beside it
+        ops = swept_step * args.steps * algo["ops_per_cell"] / sweep_s if sweep_s > 0 else 0.0
+        roofline.update(lds=dict(bytes_per_cell=algo["bytes_per_cell"], achieved=achieved_gbs, peak=PEAK_LDS_GBS,
+                                 unit="GB/s", frac=achieved_gbs / PEAK_LDS_GBS),
+                        achieved=ops / 1e12, peak=PEAK_INT_LANE_OPS / 1e12, unit="T lane-op/s",
+                        frac=ops / PEAK_INT_LANE_OPS, bytes_per_cell=algo["bytes_per_cell"])
     if not seq:
         # the table streams from HBM (the bound above); the LDS side of the same kernel, for the
         # record: two shifted reads and one write per cell
@@ -480,6 +497,9 @@ def main() -> int:
     ap.add_argument("--no-per-config", "--no-per-k", dest="no_per_config", action="store_true",
                     help="default workload only: skip the other configurations and the peak calibration "
                          "(profiling runs: keeps the kernel statistics to the headline launches)")
+    ap.add_argument("--packed16", action="store_true",
+                    help="value-equals-weight workloads: create the handle with DEFT_FLAG_VALUES_ARE_WEIGHTS "
+                         "(rows of 16-bit cells)")
     ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
     ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()

@@ -458,12 +458,17 @@ __device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b)
     asm("v_pk_max_i16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
     return d;
 }
-// acc = 2 * acc + (sign bit of each half of diff, at bits 0 and 16)
+// acc = 2 * acc + (sign bit of each half of diff, at bits 0 and 16).  The shift of the
+// halves is left to the compiler (it knows the operand modifiers a packed inline constant
+// needs); the shift-or is pinned, because the compiler otherwise regroups the chain of them
+// into a tree of separate shifts and three-way ors that costs half an instruction more per pair.
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t shift_in_signs(uint32_t acc, uint32_t diff)
 {
     const ushort2_t s = __builtin_bit_cast(ushort2_t, diff) >> (ushort2_t)(15);
-    return (acc << 1) | __builtin_bit_cast(uint32_t, s);
+    uint32_t out;
+    asm("v_lshl_or_b32 %0, %1, 1, %2" : "=v"(out) : "v"(acc), "v"(__builtin_bit_cast(uint32_t, s)));
+    return out;
 }
 // Cell c of a packed row (sign-extended).
 template <int T>
@@ -484,7 +489,7 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
     constexpr bool STOP_WHEN_FULL = !REC;
     constexpr int kCheckEvery = 8;
     static_assert(NP >= 1 && NP <= 16, "the take bits of a lane fit one keep word");
-    const int wave_first = tid & ~63;
+    const int wave_first = uniform(tid & ~63);
     const int lane = tid & 63;
     auto load_chunk = [&](int first) {
         return first + lane < nact ? load_item_wv(list + first + lane) : make_int2(0, 0);
@@ -680,6 +685,15 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     const int tid = (T == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
     const int inst = (T == 64) ? (int)blockIdx.x * 4 + sub : (int)blockIdx.x;
     if (inst >= a.batch) return;  // whole wavefront (T == 64) or never (grid == batch)
+    // One wavefront of the instance does everything that is serial: the stage set-up, the
+    // stages settled without a sweep, the walk.  Its instructions all issue on the one SIMD
+    // it lives on, next to that SIMD's share of the sweeps; which wavefront it is rotates
+    // with the instance, so that the workgroups sharing a compute unit spread this work over
+    // its SIMDs instead of piling it onto the first.
+    constexpr int kSerialChoices = T / 64 < 4 ? T / 64 : 4;
+    const int serial_wave = (T == 64) ? 0 : (int)(blockIdx.x % kSerialChoices);
+    const bool serial = (tid >> 6) == serial_wave;
+    const int sl = tid & 63;  // lane within the wavefront
 
     int32_t *misc = lds_raw + (size_t)sub * lay.ints_per_inst;
     int32_t *row = misc + lay.guard_cells;
@@ -711,7 +725,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     lds_sync<T>();
     // Kept in registers for the whole kernel, so that the stage loop below never waits on
     // memory for them: lane j of every wavefront holds capacity j and the j-th entry of the
-    // fill order (at most 64 knapsacks), and lane i of the first wavefront holds weight and
+    // fill order (at most 64 knapsacks), and lane i of the serial wavefront holds weight and
     // value of item i (the first 64 items; longer lists reload the rest from the cache).
     int cap_l = 0, ord_l = tid & 63, w_first = 0, v_first = 0;
     {
@@ -728,7 +742,6 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             }
             for (int i = tid; i < n; i += T) {
                 const int w = W[i], v = V[i];
-                if (i < 64) { w_first = w; v_first = v; }  // i == tid here: the first wavefront's lanes
                 if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
                 if (v != w) flags |= P16 ? 5 : 4;
                 if constexpr (REC) {
@@ -776,7 +789,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     }
 
     // ---- stages ----------------------------------------------------------------
-    // Items already placed: bit (i / 64) of lane (i % 64) of the first wavefront.
+    if (serial && sl < n) { w_first = W[sl]; v_first = V[sl]; }
+    // Items already placed: bit (i / 64) of lane (i % 64) of the serial wavefront.
     unsigned long long placed = 0;
     long long total = 0;
     const int stages = caps_sweep ? min(m, 1) : m;
@@ -797,16 +811,17 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         }
         return __builtin_amdgcn_readlane(cap_l, j);
     };
-    // weight and value of item i0 + lane, as the first wavefront's stage loop reads them
+    // weight and value of item i0 + lane, as the serial wavefront's stage loop reads them
     auto item_w = [&](int i0, int i) { return i >= n ? 0 : i0 == 0 ? w_first : W[i]; };
     auto item_v = [&](int i0, int i) { return i >= n ? 0 : i0 == 0 ? v_first : V[i]; };
     int s = 0;
     while (true) {
-        // The first wavefront prepares stages one after the other, settling those that need
+        // The serial wavefront prepares stages one after the other, settling those that need
         // no sweep on its own, until it reaches one that does; only then do the other
         // wavefronts of the instance join in.  misc[1] = that stage's offered-item count
         // (negative: every stage is done), misc[6] = the stage.
-        if (tid < 64) {
+        if (serial) {
+            const int tid = sl;  // (the lane: this block addresses items as i0 + lane)
             int cnt = -1;
             for (; s < stages; ++s) {
                 const int j = stage_knapsack(s);
@@ -1101,8 +1116,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             return c;
         };
         if (!caps_sweep) {
-            if (tid < 64) {
-                const int L = tid;
+            if (serial) {
+                const int L = sl;
                 unsigned long long chosen;
                 const int c = walk(L, walk_from, walk_cap, chosen);
                 placed |= chosen;
@@ -1144,7 +1159,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         ++s;
     }
 
-    if (tid == 0) a.total_value[inst] = total;
+    if (serial && sl == 0) a.total_value[inst] = total;
 }
 
 struct Variant {
@@ -1186,6 +1201,7 @@ const Variant *variant_table16()
     DEFT_VARIANT16(64, 16, 8),     // capacity <= 1023
     DEFT_VARIANT16(256, 16, 8),    // <= 4095
     DEFT_VARIANT16(256, 32, 8),    // <= 8191
+    DEFT_VARIANT16(320, 30, 8),    // <= 9599: 21 KB per workgroup, six workgroups of five wavefronts per CU
     DEFT_VARIANT16(512, 20, 8),    // <= 10239
     DEFT_VARIANT16(512, 26, 8),    // <= 13311: 29 KB per workgroup, four workgroups of eight wavefronts per CU
     DEFT_VARIANT16(768, 26, 6),    // <= 19967: two workgroups of twelve wavefronts
@@ -1194,7 +1210,7 @@ const Variant *variant_table16()
     return table;
 }
 #undef DEFT_VARIANT16
-constexpr int kNumVariants16 = 7;
+constexpr int kNumVariants16 = 8;
 
 template <int T, int K, int G, int WPE, bool REC, bool P16>
 hipError_t launch_one(const SeqLdsPlan &p, const BatchArgs &a, void *scratch, hipStream_t st,
@@ -1234,10 +1250,11 @@ hipError_t launch_variant16(const SeqLdsPlan &p, const BatchArgs &a, void *scrat
     case 0: return launch_one<64, 16, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
     case 1: return launch_one<256, 16, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
     case 2: return launch_one<256, 32, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
-    case 3: return launch_one<512, 20, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
-    case 4: return launch_one<512, 26, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
-    case 5: return launch_one<768, 26, 2, 6, REC, true>(p, a, scratch, st, swept_cells);
-    case 6: return launch_one<1024, 26, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 3: return launch_one<320, 30, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 4: return launch_one<512, 20, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 5: return launch_one<512, 26, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
+    case 6: return launch_one<768, 26, 2, 6, REC, true>(p, a, scratch, st, swept_cells);
+    case 7: return launch_one<1024, 26, 2, 8, REC, true>(p, a, scratch, st, swept_cells);
     default: return hipErrorInvalidValue;
     }
 }

@@ -17,6 +17,7 @@ VARIANTS = [
     (700, 1023),       # one wavefront per instance
     (3000, 4095),      # 256 x 16
     (8000, 8191),      # 256 x 32
+    (9500, 9599),      # 320 x 30 (five wavefronts)
     (10000, 10239),    # 512 x 20
     (13000, 13311),    # 512 x 26
     (19900, 19967),    # 768 x 26
@@ -36,7 +37,7 @@ def test_random_ragged_every_variant(binding, oracle, cap_hi, max_capacity):
 
 
 @pytest.mark.parametrize("max_capacity,n_max,w_hi,batch", [
-    (1023, 160, 30, 64), (4095, 600, 30, 40), (8191, 1160, 30, 32), (10239, 1450, 30, 28), (13311, 1890, 30, 24),
+    (1023, 160, 30, 64), (4095, 600, 30, 40), (8191, 1160, 30, 32), (9599, 1360, 30, 28), (10239, 1450, 30, 28), (13311, 1890, 30, 24),
     (19967, 2830, 30, 20), (26623, 3000, 39, 16),
 ])
 def test_rows_that_fill_early_every_variant(binding, oracle, max_capacity, n_max, w_hi, batch):
