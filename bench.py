@@ -174,14 +174,17 @@ def run_schedule(args):
     sweep_s = float(prof.sweep_ms) * 1e-3
     launches = int(prof.sweep_launches)
     swept_step = int(prof.swept_cell_updates) // args.steps   # counted by the library: what the sweeps evaluated
-    achieved = swept_step * args.steps * 8.0 / sweep_s / 1e9 if sweep_s > 0 else 0.0
+    bytes_per_cell, ops_per_cell = (4.0, 2.0) if packed16 else (8.0, 3.0)
+    achieved = swept_step * args.steps * bytes_per_cell / sweep_s / 1e9 if sweep_s > 0 else 0.0
+    ops = swept_step * args.steps * ops_per_cell / sweep_s if sweep_s > 0 else 0.0
     upd = got["update_k"]
     line = dict(
         metric="knapsack DP cell-updates/sec", value=swept_step / (ms_step * 1e-3), unit="cell-updates/s", n_gpus=1,
         steps=args.steps, warmup=args.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype="int32", data="synthetic",
         config=dict(workload=f"task-queue simulation (Cases 1-4), ResNet-101-shaped: {sb.batch} candidates x "
-                             f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%",
+                             f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%"
+                             + (" [rows of 16-bit cells]" if packed16 else ""),
                     value_counts="cell-updates the sweeps evaluate (counted by the library)",
                     candidates_per_step=sb.batch, iterations=sb.iterations,
                     one_sweep_cell_updates_per_step_estimated_from_sample=cells_step,
@@ -193,12 +196,18 @@ def run_schedule(args):
         parity_checked=f"{len(rows)} of {sb.batch} candidates (every candidate: tests/test_gpu_schedule.py)",
         profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
                      sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
-        roofline=dict(bound="lds", achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s", frac=achieved / PEAK_LDS_GBS,
-                      traffic=None, kernel="seq_lds_kernel", bytes_per_cell=8.0, launches=launches,
+        roofline=dict(bound="alu" if packed16 else "lds",
+                      achieved=ops / 1e12 if packed16 else achieved,
+                      peak=PEAK_INT_LANE_OPS / 1e12 if packed16 else PEAK_LDS_GBS,
+                      unit="T lane-op/s" if packed16 else "GB/s",
+                      frac=ops / PEAK_INT_LANE_OPS if packed16 else achieved / PEAK_LDS_GBS,
+                      traffic=None, kernel="seq_lds_kernel", bytes_per_cell=bytes_per_cell, launches=launches,
                       avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
                       swept_cell_updates_per_s=swept_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
-                      alu=dict(ops_per_cell=3.0, peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
-                               frac=(swept_step * args.steps * 3.0 / sweep_s) / PEAK_INT_LANE_OPS if sweep_s > 0 else 0.0)),
+                      lds=dict(bytes_per_cell=bytes_per_cell, achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s",
+                               frac=achieved / PEAK_LDS_GBS),
+                      alu=dict(ops_per_cell=ops_per_cell, peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
+                               frac=ops / PEAK_INT_LANE_OPS)),
         cpu_baseline=None if args.no_cpu else dict(
             value=float(ref.sweep_cells.sum()) / t_cpu, unit="cell-updates/s", cores=int(ref.threads), kind="oracle",
             sample=f"{len(rows)} of the {sb.batch} candidates, all {sb.iterations} iterations, {t_cpu:.2f} s wall "
@@ -241,8 +250,9 @@ def run_solver(args):
         limits["flags"] = 1
         desc += " [rows of 16-bit cells]"
         # two 16-bit cells per LDS word and per packed instruction: 2 B read + 2 B written per cell;
-        # perm (lanes below the shift only), sub, max, shift, shift-or per pair of cells
-        algo = dict(bound="alu", bytes_per_cell=4.0, ops_per_cell=2.5)
+        # subtract, max, shift, shift-or per pair of cells = 2 vector instructions per cell (lanes
+        # below the item's shift add a byte permute per pair; priced at the least any lane needs)
+        algo = dict(bound="alu", bytes_per_cell=4.0, ops_per_cell=2.0)
     if seq:
         limits["max_capacity"] = cap
     else:
@@ -402,9 +412,9 @@ def run_solver(args):
                  frac=(swept_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
                  if sweep_s > 0 else 0.0))
     if algo["bound"] == "alu":
-        # rows of 16-bit cells: the vector ALU is the nearer bound (64 / 2.5 = 25.6 cells per clock
-        # and CU against 128 B / 4 B = 32 for LDS), so it is the one the fraction is taken against;
-        # the LDS side is kept beside it
+        # rows of 16-bit cells: the vector ALU bound (64 lanes / 2 instructions = 32 cells per clock
+        # and CU) and the LDS bound (128 B / 4 B = 32) coincide; the counters say the ALU is the
+        # busier unit, so the fraction is stated against it, with the LDS side beside it
         ops = swept_step * args.steps * algo["ops_per_cell"] / sweep_s if sweep_s > 0 else 0.0
         roofline.update(lds=dict(bytes_per_cell=algo["bytes_per_cell"], achieved=achieved_gbs, peak=PEAK_LDS_GBS,
                                  unit="GB/s", frac=achieved_gbs / PEAK_LDS_GBS),
@@ -452,8 +462,8 @@ def compact(line: dict) -> dict:
                              unit=r["unit"], frac=r["frac"], alu_frac=r["alu"]["frac"],
                              alu_ops_per_cell=r["alu"]["ops_per_cell"]),
                parity_vs_oracle=line["parity_vs_oracle"])
-    if "lds" in r:
-        out["roofline"]["lds_frac_at_12_bytes_per_cell"] = r["lds"]["frac"]
+    if "lds" in r and r["bound"] != "lds":
+        out["roofline"][f"lds_frac_at_{r['lds']['bytes_per_cell']:g}_bytes_per_cell"] = r["lds"]["frac"]
     for key in ("instances_per_s", "candidate_iterations_per_s", "effective_cell_updates_per_s", "parity_checked"):
         if key in line:
             out[key] = line[key]
@@ -472,11 +482,13 @@ def measured_peaks() -> dict:
                      basis=f"{N_CU} CUs x {LDS_BYTES_PER_CLK_PER_CU} B/clk/CU x {CLOCK_HZ / 1e9} GHz; HBM3E 8 TB/s; "
                            f"{N_CU} CUs x 64 lanes x {CLOCK_HZ / 1e9} GHz"),
         measured=dict(lds_read_gbs=float(p.lds_read_gbs), lds_read_write_gbs=float(p.lds_read_write_gbs),
-                      hbm_copy_gbs=float(p.hbm_copy_gbs), hbm_write_gbs=float(p.hbm_write_gbs),
+                      hbm_copy_gbs=float(p.hbm_copy_gbs), hbm_read_gbs=float(p.hbm_read_gbs),
+                      hbm_write_gbs=float(p.hbm_write_gbs),
                       lds_read_write_bytes_per_clk_per_cu_at_nominal_clock=float(p.lds_read_write_gbs) * 1e9 / CLOCK_HZ / N_CU,
                       compute_units=int(p.compute_units), clock_mhz_reported=int(p.clock_mhz_reported),
                       how="deft_knapsack_measure_peaks: 4-byte conflict-free LDS reads; one shifted 4-byte read + one "
-                          "lane-addressed 4-byte write per cell; 1 GiB copy and fill kernels; best of three launches"))
+                          "lane-addressed 4-byte write per cell; 1 GiB streaming copy, read and fill kernels (16-byte accesses, four "
+                          "in flight per lane); best of three launches"))
 
 
 def main() -> int:
@@ -522,9 +534,17 @@ def main() -> int:
         per_config = {}
         for name, extra in (("tiny", {}), ("resnet101_one_call_per_k", dict(workload="resnet101", per_k_calls=True)),
                             ("vgg19", {}), ("gpt2", {}), ("hetero", {}), ("backward", {}), ("inflation", {}),
-                            ("schedule", {})):
+                            ("schedule", {}),
+                            # the value-equals-weight workloads again on handles created with
+                            # DEFT_FLAG_VALUES_ARE_WEIGHTS (rows of 16-bit cells), priced on their own roofline
+                            ("resnet101_rows16", dict(workload="resnet101", packed16=True)),
+                            ("resnet101_one_call_per_k_rows16", dict(workload="resnet101", per_k_calls=True, packed16=True)),
+                            ("vgg19_rows16", dict(workload="vgg19", packed16=True)),
+                            ("backward_rows16", dict(workload="backward", packed16=True)),
+                            ("inflation_rows16", dict(workload="inflation", packed16=True)),
+                            ("schedule_rows16", dict(workload="schedule", packed16=True))):
             sub = argparse.Namespace(**vars(args))
-            sub.workload = name
+            sub.workload, sub.no_cpu = name, args.no_cpu or "rows16" in name
             sub.steps, sub.warmup, sub.single_thread = max(3, min(args.steps, 5)), 2, False
             for k, v in extra.items():
                 setattr(sub, k, v)

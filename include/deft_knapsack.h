@@ -353,6 +353,7 @@ typedef struct {
     float lds_read_write_gbs;  /* the DP sweep's mix: one shifted 4-byte read and one 4-byte
                                   write (addressed by lane) per cell; bytes read + written      */
     float hbm_copy_gbs;        /* 1 GiB device-to-device copy kernel; bytes read + written      */
+    float hbm_read_gbs;        /* 1 GiB read-only kernel                                        */
     float hbm_write_gbs;       /* 1 GiB fill kernel                                             */
     int32_t compute_units;
     int32_t clock_mhz_reported; /* the runtime's maximum shader clock                           */

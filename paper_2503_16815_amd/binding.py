@@ -67,7 +67,8 @@ class deft_knapsack_profile_t(ctypes.Structure):
 
 class deft_knapsack_peaks_t(ctypes.Structure):
     _fields_ = [("lds_read_gbs", ctypes.c_float), ("lds_read_write_gbs", ctypes.c_float),
-                ("hbm_copy_gbs", ctypes.c_float), ("hbm_write_gbs", ctypes.c_float),
+                ("hbm_copy_gbs", ctypes.c_float), ("hbm_read_gbs", ctypes.c_float),
+                ("hbm_write_gbs", ctypes.c_float),
                 ("compute_units", ctypes.c_int32), ("clock_mhz_reported", ctypes.c_int32)]
 
 

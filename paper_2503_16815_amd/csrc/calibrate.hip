@@ -62,15 +62,43 @@ __global__ void __launch_bounds__(kLdsThreads) lds_read_write_kernel(int *out, i
     out[blockIdx.x * kLdsThreads + tid] = acc;
 }
 
-__global__ void __launch_bounds__(256) copy_kernel(const int4 *__restrict__ src, int4 *__restrict__ dst, size_t n)
+typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr int kUnroll = 4;  // 16-byte accesses in flight per lane
+
+// Streaming copy: four 16-byte non-temporal loads, then four stores, per lane and trip.
+__global__ void __launch_bounds__(256) copy_kernel(const v4i *__restrict__ src, v4i *__restrict__ dst, size_t n)
 {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+    const size_t stride = (size_t)gridDim.x * 256 * kUnroll;
+    for (size_t i = (size_t)blockIdx.x * 256 * kUnroll + threadIdx.x; i + 256 * (kUnroll - 1) < n; i += stride) {
+        v4i v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(&src[i + 256 * u]);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(v[u], &dst[i + 256 * u]);
+    }
 }
 
-__global__ void __launch_bounds__(256) fill_kernel(int4 *dst, size_t n)
+__global__ void __launch_bounds__(256) read_kernel(const v4i *__restrict__ src, int *out, size_t n)
 {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
-        dst[i] = make_int4(1, 2, 3, 4);
+    const size_t stride = (size_t)gridDim.x * 256 * kUnroll;
+    int acc = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 * kUnroll + threadIdx.x; i + 256 * (kUnroll - 1) < n; i += stride) {
+        v4i v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = src[i + 256 * u];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345678) out[0] = acc;  // (keeps the loads alive; the fill pattern never sums to this)
+}
+
+__global__ void __launch_bounds__(256) fill_kernel(v4i *dst, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * 256 * kUnroll;
+    for (size_t i = (size_t)blockIdx.x * 256 * kUnroll + threadIdx.x; i + 256 * (kUnroll - 1) < n; i += stride) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) dst[i + 256 * u] = v4i{1, 2, 3, 4};
+    }
 }
 
 template <class F>
@@ -107,7 +135,7 @@ extern "C" deft_status_t deft_knapsack_measure_peaks(int32_t device, deft_knapsa
 
     deft_status_t rc = DEFT_OK;
     int *sink = nullptr;
-    int4 *a = nullptr, *b = nullptr;
+    v4i *a = nullptr, *b = nullptr;
     const int wgs = cus * 8;
     const size_t copy_bytes = (size_t)1 << 30, n16 = copy_bytes / 16;
     if (hipMalloc(&sink, (size_t)wgs * kLdsThreads * 4) != hipSuccess || hipMalloc(&a, copy_bytes) != hipSuccess ||
@@ -134,17 +162,24 @@ extern "C" deft_status_t deft_knapsack_measure_peaks(int32_t device, deft_knapsa
             if (ms < best) best = ms;
         }
         out->lds_read_write_gbs = (float)((double)wgs * kLdsThreads * 32.0 * iters / (best * 1e-3) / 1e9);
-        hipLaunchKernelGGL(fill_kernel, dim3(cus * 16), dim3(256), 0, nullptr, a, n16);
-        hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, nullptr, a, b, n16);
+        const dim3 grid((unsigned)cus * 32), block(256);
+        hipLaunchKernelGGL(fill_kernel, grid, block, 0, nullptr, a, n16);
+        hipLaunchKernelGGL(copy_kernel, grid, block, 0, nullptr, a, b, n16);
         best = 1e30f;
         for (int r = 0; r < 3 && ok; ++r) {
-            ok = timed([&] { hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, nullptr, a, b, n16); }, &ms);
+            ok = timed([&] { hipLaunchKernelGGL(copy_kernel, grid, block, 0, nullptr, a, b, n16); }, &ms);
             if (ms < best) best = ms;
         }
         out->hbm_copy_gbs = (float)(2.0 * copy_bytes / (best * 1e-3) / 1e9);
         best = 1e30f;
         for (int r = 0; r < 3 && ok; ++r) {
-            ok = timed([&] { hipLaunchKernelGGL(fill_kernel, dim3(cus * 16), dim3(256), 0, nullptr, b, n16); }, &ms);
+            ok = timed([&] { hipLaunchKernelGGL(read_kernel, grid, block, 0, nullptr, a, sink, n16); }, &ms);
+            if (ms < best) best = ms;
+        }
+        out->hbm_read_gbs = (float)((double)copy_bytes / (best * 1e-3) / 1e9);
+        best = 1e30f;
+        for (int r = 0; r < 3 && ok; ++r) {
+            ok = timed([&] { hipLaunchKernelGGL(fill_kernel, grid, block, 0, nullptr, b, n16); }, &ms);
             if (ms < best) best = ms;
         }
         out->hbm_write_gbs = (float)((double)copy_bytes / (best * 1e-3) / 1e9);
