@@ -178,6 +178,14 @@ struct SlotsDownTo {
     }
 };
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// acc |= 1 << bit on the scalar unit (acc is the same in every lane; written this way the
+// compiler keeps it in a scalar register instead of spending vector instructions on it).
+__device__ __forceinline__ void scalar_set_bit(uint32_t &acc, int bit)
+{
+    uint32_t a = (uint32_t)__builtin_amdgcn_readfirstlane((int)acc);
+    asm("s_bitset1_b32 %0, %1" : "+s"(a) : "s"(__builtin_amdgcn_readfirstlane(bit)));
+    acc = a;
+}
 
 // LDS of one instance: [8 ints of scratch][guard_cells - 8 ints of INT_MIN][row_cells].
 // The scratch words are the lowest cells of the guard zone; an item counts as light
@@ -352,10 +360,11 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             nz = __builtin_amdgcn_ballot_w64(any_bits != 0) != 0ull;
         }
         if (nz) {
+            uint32_t *kq = kp + (size_t)q * (NW * T);  // scalar base, lane offsets that never change
 #pragma unroll
-            for (int x = 0; x < NW; ++x) kp[((size_t)q * NW + x) * T + tid] = bits[x];
+            for (int x = 0; x < NW; ++x) kq[x * T + tid] = bits[x];
+            scalar_set_bit(nz_acc, q & 31);
         }
-        nz_acc |= (uint32_t)nz << (q & 31);
         if ((q & 31) == 31) hand_over(q);
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
@@ -587,8 +596,11 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
         } else {
             nz = __builtin_amdgcn_ballot_w64(acc != 0) != 0ull;
         }
-        if (nz) kp[(size_t)q * T + tid] = acc;
-        nz_acc |= (uint32_t)nz << (q & 31);
+        if (nz) {
+            uint32_t *kq = kp + (size_t)q * T;  // scalar base, a lane offset that never changes
+            kq[tid] = acc;
+            scalar_set_bit(nz_acc, q & 31);
+        }
         if ((q & 31) == 31) hand_over(q);
         wait_lds();
         lds_sync<T>();  // the new row is visible
