@@ -125,6 +125,19 @@ def make_workload(name: str, batch_scale: float, per_k_calls: bool):
     return calls, desc, algo
 
 
+def calibration_copy(dev) -> None:
+    """One plain 1 GiB fill and one 1 GiB device-to-device copy: rows of known HBM traffic in a
+    counter profile of this command, to scale FETCH_SIZE / WRITE_SIZE by."""
+    import torch
+    src = torch.empty(1 << 28, dtype=torch.int32, device=dev)
+    src.fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize(dev)
+    dst.copy_(src)            # the calibration row: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize(dev)
+    del src, dst
+
+
 def run_schedule(args):
     """The task-queue simulation (Sec. III.B, Cases 1-4) on the ResNet-101 shape: a step is one
     call simulating every candidate for 8 iterations (16 stages, each one solver launch).
@@ -153,6 +166,8 @@ def run_schedule(args):
         info = h.info()
         ds = binding.DeviceSchedules(sb, dev)
         torch.cuda.synchronize(dev)
+        if getattr(args, "calibrate_copy", False):
+            calibration_copy(dev)
         for _ in range(args.warmup):
             binding.simulate_schedule(h, ds, stream)
         stream.synchronize()
@@ -336,13 +351,7 @@ def run_solver(args):
                 h.solve_batch(db, stream)
 
         if args.calibrate_copy:
-            src = torch.empty(1 << 28, dtype=torch.int32, device=dev)
-            src.fill_(1)
-            dst = torch.empty_like(src)
-            torch.cuda.synchronize(dev)
-            dst.copy_(src)            # the calibration row: reads 1 GiB, writes 1 GiB
-            torch.cuda.synchronize(dev)
-            del src, dst
+            calibration_copy(dev)
         for _ in range(args.warmup):
             step()
         stream.synchronize()
