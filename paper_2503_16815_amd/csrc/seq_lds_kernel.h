@@ -224,6 +224,10 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
 {
     constexpr bool STOP_WHEN_FULL = VEQW && !REC;
     constexpr int kCheckEvery = 8;
+    // What follows from the lane index alone (a slot's initial value and LDS address, for every
+    // slot count instantiated) is cheap to compute here; left visible to the compiler it is all
+    // computed at kernel entry instead, parked in scratch memory and fetched back per stage.
+    asm volatile("" : "+v"(tid));
     constexpr int D = NB < 12 ? NB : 12;  // slots the reads run ahead of the arithmetic (<= 15 LDS ops in flight)
     const int wave_first = tid & ~63;     // first lane of this wavefront within the instance
     // VEQW (every value equals its weight, the paper's Problem 1): the row is kept as
@@ -498,6 +502,7 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
     constexpr bool STOP_WHEN_FULL = !REC;
     constexpr int kCheckEvery = 8;
     static_assert(NP >= 1 && NP <= 16, "the take bits of a lane fit one keep word");
+    asm volatile("" : "+v"(tid));  // (as in sweep_stage: keeps the per-lane constants out of kernel entry)
     const int wave_first = uniform(tid & ~63);
     const int lane = tid & 63;
     auto load_chunk = [&](int first) {
