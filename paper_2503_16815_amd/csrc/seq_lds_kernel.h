@@ -87,6 +87,24 @@ __device__ __forceinline__ void global_sync()
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Sum / maximum over the 64 lanes of a wavefront whose lanes are all active, the result in
+// every lane.  Data-parallel primitives only (two exchanges inside each group of four
+// lanes, two rotations inside each row of sixteen, then the four row results are read out):
+// no LDS access, whose latency under the sweeps of the neighbouring workgroups is what the
+// serial wavefront would otherwise wait for, several times per stage.
+template <class Op>
+__device__ __forceinline__ int wave_reduce(int x, Op op)
+{
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0x124, 0xf, 0xf, false));  // row_ror:4
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0x128, 0xf, 0xf, false));  // row_ror:8
+    return op(op(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+              op(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+}
+__device__ __forceinline__ int wave_sum(int x) { return wave_reduce(x, [](int a, int b) { return a + b; }); }
+__device__ __forceinline__ int wave_max(int x) { return wave_reduce(x, [](int a, int b) { return max(a, b); }); }
+
 // bits = 2 * bits + (cand > own): compare into vcc, add-with-carry.
 __device__ __forceinline__ uint32_t shift_in_take(uint32_t bits, int cand, int own)
 {
@@ -873,7 +891,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 // offered items: not yet placed and able to fit at all, ascending index
                 cnt = 0;
                 int unplaced = 0;
-                long long offered_weight = 0;
+                int offered_weight = 0;  // per lane at most 64 items of at most 2^24 each
                 for (int i0 = 0; i0 < n; i0 += 64) {
                     const int i = i0 + tid;
                     const int w = item_w(i0, i);
@@ -901,11 +919,11 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 // settled here, without a sweep.  (Not for the capacity sweep: its other
                 // capacities are smaller.)
                 if (!caps_sweep) {
-#pragma unroll
-                    for (int off = 32; off > 0; off >>= 1) offered_weight += __shfl_down(offered_weight, off);
-                    offered_weight = __shfl(offered_weight, 0);
+                    // (a lane's share is clamped just above the largest capacity, so that the
+                    // wavefront's sum stays in range and still exceeds C whenever the true sum does)
+                    offered_weight = wave_sum(min(offered_weight, (1 << 24) + 1));
                     if (offered_weight <= C) {
-                        long long vsum = 0, lsum = 0;
+                        int vsum = 0, lsum = 0;  // values sum to less than 2^31, weights to at most C
                         for (int i0 = 0; i0 < n; i0 += 64) {
                             const int i = i0 + tid;
                             const int w = item_w(i0, i);
@@ -917,14 +935,11 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                                 lsum += w;
                             }
                         }
-#pragma unroll
-                        for (int off = 32; off > 0; off >>= 1) {
-                            vsum += __shfl_down(vsum, off);
-                            lsum += __shfl_down(lsum, off);
-                        }
+                        vsum = wave_sum(vsum);
+                        lsum = wave_sum(lsum);
                         if (tid == 0) {
-                            out_kv[j] = (int)vsum;
-                            out_kl[j] = (int)lsum;
+                            out_kv[j] = vsum;
+                            out_kl[j] = lsum;
                             total += vsum;
                         }
                         cnt = -1;  // tells every wavefront that the stage is done
@@ -953,20 +968,15 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                                 ++got;
                             }
                         }
-                        long long ws = 0, vs = 0;
+                        int ws = 0, vs = 0;  // six weights of at most 2^24; values sum to less than 2^31
 #pragma unroll
                         for (int t = 0; t < kEnumItems; ++t)
                             if ((tid >> t) & 1) { ws += wq[t]; vs += vq[t]; }
                         const bool feasible = tid < (1 << cnt) && ws <= C;
-                        long long best_value = feasible ? vs : -1;
-#pragma unroll
-                        for (int off = 32; off > 0; off >>= 1) {
-                            const long long other = __shfl_xor(best_value, off);
-                            best_value = other > best_value ? other : best_value;
-                        }
+                        const int best_value = wave_max(feasible ? vs : -1);
                         // (the empty subset is always feasible, so the ballot is never empty)
                         const int pick = __builtin_ctzll(__ballot(feasible && vs == best_value));
-                        const long long load = __shfl(ws, pick);
+                        const int load = __builtin_amdgcn_readlane(ws, pick);
 #pragma unroll
                         for (int t = 0; t < kEnumItems; ++t) {
                             if ((pick >> t) & 1) {
@@ -975,8 +985,8 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                             }
                         }
                         if (tid == 0) {
-                            out_kv[j] = (int)best_value;
-                            out_kl[j] = (int)load;
+                            out_kv[j] = best_value;
+                            out_kl[j] = load;
                             total += best_value;
                         }
                         cnt = -1;
