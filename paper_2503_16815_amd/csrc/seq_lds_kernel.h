@@ -102,6 +102,19 @@ __device__ __forceinline__ int wave_reduce(int x, Op op)
     return op(op(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
               op(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
+// Suffix sums over the wavefront (all lanes active): lane l gets x[l] + x[l+1] + ... + x[63].
+// Shifts inside each row of sixteen lanes (zeros come in from beyond the row), then the totals
+// of the rows above are added in.
+__device__ __forceinline__ int wave_suffix_sum(int x, int lane)
+{
+    x += __builtin_amdgcn_update_dpp(0, x, 0x101, 0xf, 0xf, true);  // row_shl:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x102, 0xf, 0xf, true);  // row_shl:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x104, 0xf, 0xf, true);  // row_shl:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x108, 0xf, 0xf, true);  // row_shl:8
+    const int t1 = __builtin_amdgcn_readlane(x, 16), t2 = __builtin_amdgcn_readlane(x, 32),
+              t3 = __builtin_amdgcn_readlane(x, 48);
+    return x + (lane < 16 ? t1 : 0) + (lane < 32 ? t2 : 0) + (lane < 48 ? t3 : 0);
+}
 __device__ __forceinline__ int wave_sum(int x) { return wave_reduce(x, [](int a, int b) { return a + b; }); }
 __device__ __forceinline__ int wave_max(int x) { return wave_reduce(x, [](int a, int b) { return max(a, b); }); }
 
@@ -868,22 +881,21 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                     // positions).  Entry i gets P_i = R - sum of drop[t] over t >= i, the remaining
                     // time of the level that ends before item i, from a suffix sum taken 64 items
                     // at a time from the end of the list.
-                    long long behind = 0;  // sum of drop over the chunks already done (uniform)
+                    // Only "how far below C" matters, and C is at most 2^24: a drop time is
+                    // clamped just above that and so is the running sum, which keeps everything
+                    // in 32 bits and exact wherever the remaining time is not negative.
+                    constexpr int kOver = (1 << 24) + 1;
+                    int behind = 0;  // sum of drop over the chunks already done (uniform)
                     for (int i0 = (n - 1) & ~63; i0 >= 0 && n > 0; i0 -= 64) {
                         const int i = i0 + tid;
-                        long long x = i < n ? drop[i] : 0;
-#pragma unroll
-                        for (int off = 1; off < 64; off <<= 1) {
-                            const long long y = __shfl_down(x, off);
-                            if (tid + off < 64) x += y;
-                        }
+                        const int x = wave_suffix_sum(i < n ? min(drop[i], kOver) : 0, tid);
                         if (i < n) {
-                            const long long left = (long long)C - (x + behind);
+                            const int left = C - min(x + behind, kOver);
                             OfferedItem e;
-                            e.w = W[i]; e.v = V[i]; e.index = i; e.pad = left < 0 ? -1 : (int)left;
+                            e.w = W[i]; e.v = V[i]; e.index = i; e.pad = left < 0 ? -1 : left;
                             list[i] = e;
                         }
-                        behind += __shfl(x, 0);
+                        behind = min(behind + __builtin_amdgcn_readlane(x, 0), kOver);
                     }
                     cnt = n;
                     break;
