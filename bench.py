@@ -539,7 +539,7 @@ def main() -> int:
     headline = (args.workload == "resnet101" and args.batch_scale == 1.0 and
                 not (args.per_k_calls or args.only_k or args.max_stages or args.no_per_config))
     if headline:
-        # every other configuration, measured in this same process: fewer steps, same code path
+        # every other configuration, measured in this same process, same code path
         per_config = {}
         for name, extra in (("tiny", {}), ("resnet101_one_call_per_k", dict(workload="resnet101", per_k_calls=True)),
                             ("vgg19", {}), ("gpt2", {}), ("hetero", {}), ("backward", {}), ("inflation", {}),
@@ -554,7 +554,7 @@ def main() -> int:
                             ("schedule_rows16", dict(workload="schedule", packed16=True))):
             sub = argparse.Namespace(**vars(args))
             sub.workload, sub.no_cpu = name, args.no_cpu or "rows16" in name
-            sub.steps, sub.warmup, sub.single_thread = max(3, min(args.steps, 5)), 2, False
+            sub.steps, sub.warmup, sub.single_thread = max(3, min(args.steps, 20)), 3, False
             for k, v in extra.items():
                 setattr(sub, k, v)
             one, ok = (run_schedule if sub.workload == "schedule" else run_solver)(sub)

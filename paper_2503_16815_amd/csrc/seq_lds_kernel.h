@@ -768,6 +768,14 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
     OfferedItem *inst_lists = uniform_ptr(lists + (size_t)inst * a.knap_stride * list_stride);
 
     // ---- per-instance validation -------------------------------------------
+    // The first T items and the capacities are fetched here, before n and m have arrived
+    // and been checked (the arrays are item_stride / knap_stride long whatever the counts
+    // say), so that one memory round trip serves both.
+    const bool pre_item = tid < a.item_stride, pre_knap = (tid & 63) < a.knap_stride;
+    const int w_pre = pre_item ? W[tid] : 0, v_pre = pre_item ? V[tid] : 0;
+    const int d_pre = REC && levels && pre_item ? drop[tid] : 0;
+    const int cap_pre = pre_knap ? cap[tid & 63] : 0;
+    const int ord_pre = ord && pre_knap ? ord[tid & 63] : (tid & 63);
     if (tid < kMiscInts) misc[tid] = 0;
     for (int i = kMiscInts + tid; i < lay.guard_cells; i += T) misc[i] = P16 ? kGuard16 : INT_MIN;
     lds_sync<T>();
@@ -785,15 +793,16 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
             flags = 1;
         } else {
             if ((tid & 63) < m) {
-                cap_l = cap[tid & 63];
-                if (ord) ord_l = ord[tid & 63];
+                cap_l = cap_pre;
+                ord_l = ord_pre;
             }
             for (int i = tid; i < n; i += T) {
-                const int w = W[i], v = V[i];
+                const bool pre = i == tid;  // the first round: fetched above
+                const int w = pre ? w_pre : W[i], v = pre ? v_pre : V[i];
                 if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
                 if (v != w) flags |= P16 ? 5 : 4;
                 if constexpr (REC) {
-                    if (levels && drop[i] < 0) flags |= 1;
+                    if (levels && (pre ? d_pre : drop[i]) < 0) flags |= 1;
                 }
             }
             for (int j = tid; j < m; j += T) {
@@ -811,8 +820,17 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                 }
             }
         }
-        if (flags) atomicOr(reinterpret_cast<uint32_t *>(&misc[0]), flags);
-        if (vs) atomicAdd(reinterpret_cast<unsigned long long *>(&misc[2]), vs);
+        // one LDS atomic per wavefront (every lane is here: the branches above are uniform or
+        // closed); a lane's value sum is below 2^35, summed in three 16-bit-wide parts
+        const uint32_t wave_flags = (__ballot(flags & 1) ? 1u : 0u) | (__ballot(flags & 2) ? 2u : 0u) |
+                                    (__ballot(flags & 4) ? 4u : 0u);
+        const unsigned long long wave_vs = (unsigned long long)(unsigned)wave_sum((int)(vs & 0xffffu)) +
+                                           ((unsigned long long)(unsigned)wave_sum((int)((vs >> 16) & 0xffffu)) << 16) +
+                                           ((unsigned long long)(unsigned)wave_sum((int)(vs >> 32)) << 32);
+        if ((tid & 63) == 0) {
+            if (wave_flags) atomicOr(reinterpret_cast<uint32_t *>(&misc[0]), wave_flags);
+            if (wave_vs) atomicAdd(reinterpret_cast<unsigned long long *>(&misc[2]), wave_vs);
+        }
     }
     lds_sync<T>();
     int status = DEFT_OK;
