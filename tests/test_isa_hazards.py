@@ -3,7 +3,7 @@ not apply to inline asm: between a scalar write of M0 and an add-TID LDS access
 (ds_read_addtid_b32 / ds_write_addtid_b32) there must be at least one other instruction.
 seq_lds_kernel.h relies on the compiler to place and merge the M0 writes ("{m0}" operands) and
 on m0_settle() to supply the wait state; this test compiles the file to assembly and
-verifies that every run of add-TID accesses is so protected, in both files that
+verifies that every run of add-TID accesses is so protected, in the four files that
 instantiate the kernels.  No GPU needed."""
 import os
 import re
@@ -13,7 +13,7 @@ import tempfile
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SRCS = [os.path.join(ROOT, "paper_2503_16815_amd", "csrc", f) for f in ("seq_lds.hip", "seq_lds_rec.hip")]
+SRCS = [os.path.join(ROOT, "paper_2503_16815_amd", "csrc", f) for f in ("seq_lds.hip", "seq_lds_rec.hip", "seq_lds_p16.hip", "seq_lds_p16_rec.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 M0_WRITE = re.compile(r"^\s*s_\w+\s+m0\s*,")          # any scalar instruction whose destination is m0
@@ -34,7 +34,7 @@ def instructions(asm_text):
 def test_m0_write_is_never_directly_followed_by_an_addtid_access():
     with tempfile.TemporaryDirectory() as tmp:
         jobs = []
-        for src in SRCS:   # both compilations at once
+        for src in SRCS:   # all compilations at once
             out = os.path.join(tmp, os.path.basename(src) + ".s")
             cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fno-gpu-rdc", "-Xclang", "-target-feature",
                    "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
