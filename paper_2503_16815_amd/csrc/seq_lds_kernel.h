@@ -69,10 +69,9 @@ __device__ __forceinline__ void lds_sync()
 }
 
 // Makes what the lanes of the instance wrote to global memory (keep words, item
-// lists) visible to its other lanes.  All of them run on one compute unit, so
-// workgroup scope is enough: the stores have reached L2 when the wait ends, and the
-// readers go to L2 (scalar loads, and vector loads that bypass L1).  A wider scope
-// would write back and invalidate L2 at every call.
+// lists) visible to its other lanes.  All of them run on one compute unit and share its
+// vector L1, so workgroup scope is enough, for the fence and for the reads that follow it.
+// A wider scope would write back and invalidate L2 at every call.
 template <int T>
 __device__ __forceinline__ void global_sync()
 {
@@ -134,22 +133,26 @@ typedef __attribute__((address_space(3))) int32_t lds_i32;
 struct __attribute__((aligned(16))) OfferedItem {
     int32_t w, v, index, pad;
 };
-// Reads the first or second half of a list entry from L2, past the vector L1.  The
-// lists are written and read inside one launch, and the scalar cache is not a way
-// to read them: it can still hold a line from an earlier launch.
+// Reads the first or second half of a list entry.  The lists (and the keep words) are
+// written and read inside one launch by wavefronts of one workgroup, which share a compute
+// unit and its vector L1: workgroup scope is all the ordering these reads need (after
+// global_sync's release, barrier and acquire at the same scope).  A wider scope makes every
+// such read go past the L2 of its chip to the memory side, which the walk's chain of
+// dependent reads pays for round by round.  The scalar cache is not a way to read them: it
+// can still hold a line from an earlier launch.
 __device__ __forceinline__ int2 load_item_wv(const OfferedItem *e)
 {
     const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(e), __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
     return make_int2((int)(uint32_t)u, (int)(uint32_t)(u >> 32));
 }
 __device__ __forceinline__ int load_item_index(const OfferedItem *e)
 {
-    return __hip_atomic_load(&e->index, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(&e->index, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 __device__ __forceinline__ int load_item_pad(const OfferedItem *e)
 {
-    return __hip_atomic_load(&e->pad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(&e->pad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 // Algorithm 1 (REC kernels): the best level seen so far.  A level is a prefix of the
 // list (its length) solved with the remaining time that is left once the items behind
@@ -1148,7 +1151,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                         const unsigned long long nzw = tb_nz[(lane >> 6) * 64 + (qd >> 6)];
                         if ((nzw >> (qd & 63)) & 1ull) {
                             const uint32_t word = __hip_atomic_load(&kp[((size_t)qd * NW + (k >> 5)) * T + lane],
-                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                             bit = (word >> (P16 ? (k & 1) * 16 + (k >> 1) : (k & 31))) & 1u;
                         }
                     } else {
