@@ -189,7 +189,7 @@ def run_schedule(args):
     sweep_s = float(prof.sweep_ms) * 1e-3
     launches = int(prof.sweep_launches)
     swept_step = int(prof.swept_cell_updates) // args.steps   # counted by the library: what the sweeps evaluated
-    bytes_per_cell, ops_per_cell = (4.0, 2.0) if packed16 else (8.0, 3.0)
+    bytes_per_cell, ops_per_cell = (4.0, 1.75) if packed16 else (8.0, 3.0)
     achieved = swept_step * args.steps * bytes_per_cell / sweep_s / 1e9 if sweep_s > 0 else 0.0
     ops = swept_step * args.steps * ops_per_cell / sweep_s if sweep_s > 0 else 0.0
     upd = got["update_k"]
@@ -211,16 +211,10 @@ def run_schedule(args):
         parity_checked=f"{len(rows)} of {sb.batch} candidates (every candidate: tests/test_gpu_schedule.py)",
         profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
                      sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
-        roofline=dict(bound="alu" if packed16 else "lds",
-                      achieved=ops / 1e12 if packed16 else achieved,
-                      peak=PEAK_INT_LANE_OPS / 1e12 if packed16 else PEAK_LDS_GBS,
-                      unit="T lane-op/s" if packed16 else "GB/s",
-                      frac=ops / PEAK_INT_LANE_OPS if packed16 else achieved / PEAK_LDS_GBS,
+        roofline=dict(bound="lds", achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s", frac=achieved / PEAK_LDS_GBS,
                       traffic=None, kernel="seq_lds_kernel", bytes_per_cell=bytes_per_cell, launches=launches,
                       avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
                       swept_cell_updates_per_s=swept_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
-                      lds=dict(bytes_per_cell=bytes_per_cell, achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s",
-                               frac=achieved / PEAK_LDS_GBS),
                       alu=dict(ops_per_cell=ops_per_cell, peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
                                frac=ops / PEAK_INT_LANE_OPS)),
         cpu_baseline=None if args.no_cpu else dict(
@@ -264,10 +258,12 @@ def run_solver(args):
     if packed16:
         limits["flags"] = 1
         desc += " [rows of 16-bit cells]"
-        # two 16-bit cells per LDS word and per packed instruction: 2 B read + 2 B written per cell;
-        # subtract, max, shift, shift-or per pair of cells = 2 vector instructions per cell (lanes
-        # below the item's shift add a byte permute per pair; priced at the least any lane needs)
-        algo = dict(bound="alu", bytes_per_cell=4.0, ops_per_cell=2.0)
+        # two 16-bit cells per LDS word and per packed instruction: 2 B read + 2 B written per cell
+        # (LDS bound 128 B / 4 B = 32 cells per clock and CU); subtract and max per pair of cells,
+        # permute + shift + bit-field insert per two pairs = 1.75 vector instructions per cell (ALU
+        # bound 64 / 1.75 = 36.6; lanes below the item's shift add a byte permute per pair): LDS is
+        # the nearer bound and the one the fraction is taken against
+        algo = dict(bound="lds", bytes_per_cell=4.0, ops_per_cell=1.75)
     if seq:
         limits["max_capacity"] = cap
     else:
@@ -420,15 +416,6 @@ def run_solver(args):
         alu=dict(ops_per_cell=algo["ops_per_cell"], peak_lane_ops_per_s=PEAK_INT_LANE_OPS,
                  frac=(swept_step * args.steps * algo["ops_per_cell"] / sweep_s) / PEAK_INT_LANE_OPS
                  if sweep_s > 0 else 0.0))
-    if algo["bound"] == "alu":
-        # rows of 16-bit cells: the vector ALU bound (64 lanes / 2 instructions = 32 cells per clock
-        # and CU) and the LDS bound (128 B / 4 B = 32) coincide; the counters say the ALU is the
-        # busier unit, so the fraction is stated against it, with the LDS side beside it
-        ops = swept_step * args.steps * algo["ops_per_cell"] / sweep_s if sweep_s > 0 else 0.0
-        roofline.update(lds=dict(bytes_per_cell=algo["bytes_per_cell"], achieved=achieved_gbs, peak=PEAK_LDS_GBS,
-                                 unit="GB/s", frac=achieved_gbs / PEAK_LDS_GBS),
-                        achieved=ops / 1e12, peak=PEAK_INT_LANE_OPS / 1e12, unit="T lane-op/s",
-                        frac=ops / PEAK_INT_LANE_OPS, bytes_per_cell=algo["bytes_per_cell"])
     if not seq:
         # the table streams from HBM (the bound above); the LDS side of the same kernel, for the
         # record: two shifted reads and one write per cell
@@ -471,7 +458,7 @@ def compact(line: dict) -> dict:
                              unit=r["unit"], frac=r["frac"], alu_frac=r["alu"]["frac"],
                              alu_ops_per_cell=r["alu"]["ops_per_cell"]),
                parity_vs_oracle=line["parity_vs_oracle"])
-    if "lds" in r and r["bound"] != "lds":
+    if "lds" in r:
         out["roofline"][f"lds_frac_at_{r['lds']['bytes_per_cell']:g}_bytes_per_cell"] = r["lds"]["frac"]
     for key in ("instances_per_s", "candidate_iterations_per_s", "effective_cell_updates_per_s", "parity_checked"):
         if key in line:
@@ -546,6 +533,7 @@ def main() -> int:
                             ("schedule", {}),
                             # the value-equals-weight workloads again on handles created with
                             # DEFT_FLAG_VALUES_ARE_WEIGHTS (rows of 16-bit cells), priced on their own roofline
+                            # (4 LDS bytes per cell instead of 8)
                             ("resnet101_rows16", dict(workload="resnet101", packed16=True)),
                             ("resnet101_one_call_per_k_rows16", dict(workload="resnet101", per_k_calls=True, packed16=True)),
                             ("vgg19_rows16", dict(workload="vgg19", packed16=True)),

@@ -489,8 +489,10 @@ __device__ __forceinline__ int sweep_dispatch(int nchunk, int32_t *row, uint32_t
 // a = 0 (its first lane is at or above w: most wavefronts, for the usual light items) skips
 // the permutes and the guard read.  Heavy items compute a per lane and clamp each word index
 // into the guard.
-// The keep word of (item, lane) holds pair j's low-half bit at bit j and its high-half bit at
-// bit 16 + j (at most 16 pairs per lane).
+// The keep word of (item, lane) holds the take bit of slot k at bit 8 (k mod 4) + 7 - (k div 4)
+// (at most 32 slots per lane): the sign bytes of two pairs' differences are gathered by one
+// byte permute and their top bits dropped into bit 7 of the four bytes of the word, which
+// moves down by one bit per two pairs (pairs 2i and 2i + 1 make step i, taken from the top).
 constexpr int kGuard16 = (int)0x80018001;  // -32767 in both halves
 
 __device__ __forceinline__ uint32_t pk_sub_i16(uint32_t a, uint32_t b)
@@ -505,18 +507,19 @@ __device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b)
     asm("v_pk_max_i16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
     return d;
 }
-// acc = 2 * acc + (sign bit of each half of diff, at bits 0 and 16).  The shift of the
-// halves is left to the compiler (it knows the operand modifiers a packed inline constant
-// needs); the shift-or is pinned, because the compiler otherwise regroups the chain of them
-// into a tree of separate shifts and three-way ors that costs half an instruction more per pair.
-typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t shift_in_signs(uint32_t acc, uint32_t diff)
+// One step of the keep word: the word moves down by one bit and the sign bits of the four
+// halves of (diff_hi, diff_lo) - the differences of pairs 2i + 1 and 2i - land in bit 7 of
+// bytes 3, 2 (pair 2i + 1: high half, low half) and 1, 0 (pair 2i).  Three instructions for two
+// pairs; the bit-field insert is pinned (the compiler would otherwise split it).
+__device__ __forceinline__ uint32_t shift_in_signs(uint32_t acc, uint32_t diff_hi, uint32_t diff_lo, uint32_t top_bits)
 {
-    const ushort2_t s = __builtin_bit_cast(ushort2_t, diff) >> (ushort2_t)(15);
+    const uint32_t sign_bytes = __builtin_amdgcn_perm(diff_hi, diff_lo, 0x07050301u);
     uint32_t out;
-    asm("v_lshl_or_b32 %0, %1, 1, %2" : "=v"(out) : "v"(acc), "v"(__builtin_bit_cast(uint32_t, s)));
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(out) : "s"(top_bits), "v"(sign_bytes), "v"(acc >> 1));
     return out;
 }
+// Bit of slot k in a keep word of the packed kernels.
+__device__ __forceinline__ int keep_bit16(int k) { return (k & 3) * 8 + 7 - (k >> 2); }
 // Cell c of a packed row (sign-extended).
 template <int T>
 __device__ __forceinline__ int row16_cell(const int32_t *row, int c)
@@ -597,11 +600,17 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
                 cand[j] = __builtin_amdgcn_perm(hi, lo, sel);
             }
         }
+        const uint32_t top_bits = (uint32_t)uniform((int)0x80808080u);  // (a scalar operand of the insert)
 #pragma unroll
-        for (int j = NP - 1; j >= 0; --j) {
-            const uint32_t diff = pk_sub_i16(own[j], cand[j]);
-            own[j] = pk_max_i16(own[j], cand[j]);
-            acc = shift_in_signs(acc, diff);  // pair j ends at bits j and 16 + j
+        for (int i = (NP - 1) / 2; i >= 0; --i) {  // step i: pairs 2i + 1 (if there is one) and 2i
+            uint32_t diff_hi = 0;
+            if (2 * i + 1 < NP) {
+                diff_hi = pk_sub_i16(own[2 * i + 1], cand[2 * i + 1]);
+                own[2 * i + 1] = pk_max_i16(own[2 * i + 1], cand[2 * i + 1]);
+            }
+            const uint32_t diff_lo = pk_sub_i16(own[2 * i], cand[2 * i]);
+            own[2 * i] = pk_max_i16(own[2 * i], cand[2 * i]);
+            acc = shift_in_signs(acc, diff_hi, diff_lo, top_bits);  // step i ends at bit 7 - i of each byte
         }
         if constexpr (REC) {
             const int level_value = uniform(probe) + probe_at;
@@ -612,9 +621,9 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
         bool group_changed[kGroups];
 #pragma unroll
         for (int g = 0; g < kGroups; ++g) {
-            const int lo = g * kGroup, hi = lo + kGroup - 1 < NP - 1 ? lo + kGroup - 1 : NP - 1;
-            const uint32_t m = ((1u << (hi - lo + 1)) - 1u) << lo;
-            group_changed[g] = !SKIP_UNCHANGED || __builtin_amdgcn_ballot_w64((acc & (m | (m << 16))) != 0) != 0ull;
+            // pairs 8g .. 8g + 7 are steps 4g .. 4g + 3: bits 7 - 4g .. 4 - 4g of every byte
+            const uint32_t m = (0xF0u >> (4 * g)) * 0x01010101u;
+            group_changed[g] = !SKIP_UNCHANGED || __builtin_amdgcn_ballot_w64((acc & m) != 0) != 0ull;
         }
         lds_sync<T>();  // every lane has read the old row
 
@@ -1152,7 +1161,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
                         if ((nzw >> (qd & 63)) & 1ull) {
                             const uint32_t word = __hip_atomic_load(&kp[((size_t)qd * NW + (k >> 5)) * T + lane],
                                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                            bit = (word >> (P16 ? (k & 1) * 16 + (k >> 1) : (k & 31))) & 1u;
+                            bit = (word >> (P16 ? keep_bit16(k) : (k & 31))) & 1u;
                         }
                     } else {
                         broken = true;
