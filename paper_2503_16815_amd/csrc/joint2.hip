@@ -222,7 +222,9 @@ jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uin
                             m1[j] = __ballot(cand1 > best);
                             best = max(best, cand1);
                             m0[j] &= ~m1[j];
-                            if (FULL || col < ncol) out[j * 64] = best;
+                            // (streaming store: the new table is next read a whole table's worth of
+                            // traffic per compute unit later; measured 9.1 -> 8.4 ms on the two-link batch)
+                            if (FULL || col < ncol) __builtin_nontemporal_store(best, &out[j * 64]);
                         }
                     }
                     // lanes 0..7 store the eight ballot words of the tile's four segments (bits of
