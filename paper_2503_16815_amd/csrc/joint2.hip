@@ -139,20 +139,20 @@ jt_sweep_all(BatchArgs a, const InstState *__restrict__ state, int32_t *tab, uin
         auto load_rows = [&](int lo, int slot_lo) {
             if (first) return;
             const int nr = min(R, nrow - lo);
-            int r = 0, part = wave;  // part: 256 columns, 16 bytes per lane
-            while (true) {
-                while (part >= ntile) { part -= ntile; ++r; }
-                if (r >= nr) break;
+            // whole rows, dealt round-robin to the loading wavefronts; a row is ntile parts of
+            // 256 columns, 16 bytes per lane.  Kept lean: a loading wavefront shares its SIMD with
+            // computing ones, so the instructions it spends per load bound the rate it loads at.
+            for (int r = wave; r < nr; r += kLoadWaves) {
                 int slot = slot_lo + r;
                 if (slot >= ring_rows) slot -= ring_rows;
-                const int col = part * 256 + lane * 4;
+                const int32_t *g = src + (size_t)(lo + r) * pitch + lane * 4;
+                int32_t *l = ring + (size_t)slot * lds_pitch;
                 // a lane's four columns may run past the instance's last column, never past the
                 // row pitch of the table or of the ring (both are multiples of four)
-                if (col < ncol) {
-                    __builtin_amdgcn_global_load_lds((global_ci32 *)(src + (size_t)(lo + r) * pitch + col),
-                                                     (lds_i32 *)(ring + (size_t)slot * lds_pitch + part * 256), 16, 0, 0);
+                for (int part = 0; part < ntile; ++part) {
+                    if (part * 256 + lane * 4 < ncol)
+                        __builtin_amdgcn_global_load_lds((global_ci32 *)(g + part * 256), (lds_i32 *)(l + part * 256), 16, 0, 0);
                 }
-                part += kLoadWaves;
             }
         };
 
