@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(kThreads) jt_init(BatchArgs a, InstState *stat
 
 constexpr int kSweepThreads = 1024;  // one workgroup per instance
 constexpr int kSweepWaves = kSweepThreads / 64;
-constexpr int kLoadWaves = 2;        // wavefronts that only move old rows from global memory into LDS
+constexpr int kLoadWaves = 3;        // wavefronts that only move old rows from global memory into LDS
 constexpr int kComputeWaves = kSweepWaves - kLoadWaves;
 
 // Block hand-over barriers.  A loading wavefront arrives when its LDS-direct loads have
