@@ -33,7 +33,7 @@ PEAK_INT_LANE_OPS = N_CU * 64 * CLOCK_HZ                              # 39.3e12 
 PEAK_HBM_GBS = 8000.0
 
 
-def cells_not_swept(kb, ref, lds_path: bool):
+def cells_not_swept(kb, ref, lds_path: bool, enumerate_small: bool = True):
     """Touched cells (as the oracle counts them) that the solver never evaluates, for a
     sequential-mode batch; returns (settled, full):
     settled - stages settled without a DP sweep: the offered items (not placed by an earlier
@@ -59,7 +59,7 @@ def cells_not_swept(kb, ref, lds_path: bool):
         cap = kb.capacities[rows, j].astype(np.int64)[:, None]
         offered = n & ~placed & (w <= cap) & live[:, None]
         fits = (w * offered).sum(axis=1) <= cap[:, 0]
-        if lds_path:
+        if lds_path and enumerate_small:
             fits |= offered.sum(axis=1) <= 6
         settled += int((np.maximum(cap - w + 1, 0) * offered)[fits].sum())
         if lds_path:
@@ -162,7 +162,7 @@ def run_schedule(args):
     stream = torch.cuda.Stream(device=dev)
     packed16 = bool(getattr(args, "packed16", False))
     with binding.DeftKnapsack(device=0, max_batch=sb.batch, max_items=sb.n_buckets, max_knapsacks=2,
-                              max_capacity=cap, flags=1 if packed16 else 0) as h:
+                              max_capacity=cap, flags=2 if getattr(args, "subset_sum", False) else 1 if packed16 else 0) as h:
         info = h.info()
         ds = binding.DeviceSchedules(sb, dev)
         torch.cuda.synchronize(dev)
@@ -249,7 +249,8 @@ def run_solver(args):
         for kb in calls:
             kb.n_knapsacks[:] = np.minimum(kb.n_knapsacks, args.max_stages)
         desc += f" [n_knapsacks clamped to {args.max_stages}]"
-    plain_run = args.batch_scale == 1.0 and not (args.per_k_calls or args.only_k or args.max_stages)
+    plain_run = args.batch_scale == 1.0 and not (args.per_k_calls or args.only_k or args.max_stages or
+                                                 getattr(args, "packed16", False) or getattr(args, "subset_sum", False))
     seq = calls[0].mode != 1
     cap = max(int(kb.capacities.max()) for kb in calls)
     limits = dict(max_batch=max(kb.batch for kb in calls), max_items=max(kb.item_stride for kb in calls),
@@ -264,6 +265,14 @@ def run_solver(args):
         # bound 64 / 1.75 = 36.6; lanes below the item's shift add a byte permute per pair): LDS is
         # the nearer bound and the one the fraction is taken against
         algo = dict(bound="lds", bytes_per_cell=4.0, ops_per_cell=1.75)
+    subset_sum = bool(getattr(args, "subset_sum", False))
+    if subset_sum:
+        limits["flags"] = 2
+        desc += " [bit-set rows]"
+        # one bit per cell: two 4-byte words read and one written per 32 cells, four vector instructions
+        # per 32 cells; a latency-bound kernel (one wavefront per instance), stated against the LDS peak
+        # at its own bytes for the record
+        algo = dict(bound="lds", bytes_per_cell=0.375, ops_per_cell=0.125)
     if seq:
         limits["max_capacity"] = cap
     else:
@@ -288,6 +297,7 @@ def run_solver(args):
     # equals its weight, the items after the row is full.  `value` and the roofline are priced
     # on the cell-updates it does evaluate (swept_step); both counts are reported.
     not_swept = {path: [cells_not_swept(kb, r, path) for kb, r in zip(calls, refs)] for path in (False, True)}
+    not_swept["bits"] = [cells_not_swept(kb, r, True, enumerate_small=False) for kb, r in zip(calls, refs)]
     settled = sum(x[0] for x in not_swept[True])     # corrected below once the handle says which path runs
     after_full = sum(x[1] for x in not_swept[True])
     cells_step = sum(touched)
@@ -336,8 +346,9 @@ def run_solver(args):
     with binding.DeftKnapsack(device=0, **limits) as h:
         info = h.info()
         if seq and calls[0].mode == 0:
-            settled = sum(x[0] for x in not_swept[info.seq_path in (1, 2)])
-            after_full = sum(x[1] for x in not_swept[info.seq_path in (1, 2)])
+            rules = "bits" if info.seq_path == 4 else info.seq_path in (1, 2)
+            settled = sum(x[0] for x in not_swept[rules])
+            after_full = sum(x[1] for x in not_swept[rules])
             swept_step = cells_step - settled - after_full
         dbs = [h.upload(kb) for kb in calls]
         torch.cuda.synchronize(dev)
@@ -395,7 +406,8 @@ def run_solver(args):
     # committed rocprofv3 counter passes of this same command (FETCH_SIZE and WRITE_SIZE scaled
     # by a copy of known size); only for the unmodified workload.
     traffic = traffic_source = None
-    kernel = "seq_lds_kernel" if (seq and info.seq_path in (1, 2)) else ("sg_sweep_all" if seq else "jt_sweep_all")
+    kernel = ("seq_bits_kernel" if (seq and info.seq_path == 4 and calls[0].mode == 0) else
+              "seq_lds_kernel" if (seq and info.seq_path in (1, 2, 4)) else ("sg_sweep_all" if seq else "jt_sweep_all"))
     tf = os.path.join(ROOT, "profiles", f"{kernel}_{args.workload}_traffic.txt")
     if plain_run and os.path.exists(tf):
         try:
@@ -508,6 +520,9 @@ def main() -> int:
     ap.add_argument("--packed16", action="store_true",
                     help="value-equals-weight workloads: create the handle with DEFT_FLAG_VALUES_ARE_WEIGHTS "
                          "(rows of 16-bit cells)")
+    ap.add_argument("--subset-sum", action="store_true",
+                    help="value-equals-weight workloads: create the handle with DEFT_FLAG_SUBSET_SUM (sequential "
+                         "mode on bit-set rows, one wavefront per instance)")
     ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
     ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()
@@ -539,9 +554,14 @@ def main() -> int:
                             ("vgg19_rows16", dict(workload="vgg19", packed16=True)),
                             ("backward_rows16", dict(workload="backward", packed16=True)),
                             ("inflation_rows16", dict(workload="inflation", packed16=True)),
-                            ("schedule_rows16", dict(workload="schedule", packed16=True))):
+                            ("schedule_rows16", dict(workload="schedule", packed16=True)),
+                            # the sequential-mode workloads on handles created with DEFT_FLAG_SUBSET_SUM
+                            # (bit-set rows, one wavefront per instance)
+                            ("resnet101_bitset", dict(workload="resnet101", subset_sum=True)),
+                            ("resnet101_one_call_per_k_bitset", dict(workload="resnet101", per_k_calls=True, subset_sum=True)),
+                            ("vgg19_bitset", dict(workload="vgg19", subset_sum=True))):
             sub = argparse.Namespace(**vars(args))
-            sub.workload, sub.no_cpu = name, args.no_cpu or "rows16" in name
+            sub.workload, sub.no_cpu = name, args.no_cpu or "rows16" in name or "bitset" in name
             sub.steps, sub.warmup, sub.single_thread = max(3, min(args.steps, 20)), 3, False
             for k, v in extra.items():
                 setattr(sub, k, v)

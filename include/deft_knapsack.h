@@ -64,7 +64,7 @@ typedef struct {
     int32_t max_capacity;  /* sequential mode: largest capacity (0 = mode unused)          */
     int32_t max_c1;        /* joint mode: largest capacity of link 0 (0 = mode unused)     */
     int32_t max_c2;        /* joint mode: largest capacity of link 1                       */
-    uint32_t flags;        /* 0, or DEFT_FLAG_VALUES_ARE_WEIGHTS                           */
+    uint32_t flags;        /* 0, DEFT_FLAG_VALUES_ARE_WEIGHTS or DEFT_FLAG_SUBSET_SUM      */
 } deft_knapsack_config_t;
 
 /*
@@ -81,6 +81,21 @@ typedef struct {
  * not affected.
  */
 #define DEFT_FLAG_VALUES_ARE_WEIGHTS 1u
+
+/*
+ * DEFT_FLAG_SUBSET_SUM: the same promise (every value equals its weight; an instance that
+ * breaks it gets DEFT_ERR_INVALID_ARG), 1 <= max_capacity <= 65535.  DEFT_MODE_SEQUENTIAL
+ * calls (and the forward stages of deft_knapsack_simulate_schedule) then run kernels that
+ * treat a window as the subset-sum problem it is (Sec. III.B, Problem 1 with profit = time):
+ * the DP row is the set of reachable sums, one bit per cell, an item is one shift-and-or
+ * of the set (32 cells per instruction), and the canonical selection - the one the exact DP
+ * walks back, smallest mask among the optima - is read off a per-cell record of the first
+ * item that reached each sum.  One wavefront per instance, everything in LDS, no scratch
+ * memory.  Results are bit-identical to those of a handle without flags.  The other
+ * sequential-layout modes run as under DEFT_FLAG_VALUES_ARE_WEIGHTS when max_capacity <=
+ * 26623 and on the 32-bit rows above that.  deft_knapsack_get_info reports seq_path 4.
+ */
+#define DEFT_FLAG_SUBSET_SUM 2u
 
 /*
  * deft_knapsack_create: validate the limits, check that the device is a
@@ -309,7 +324,8 @@ void deft_knapsack_destroy(deft_knapsack_t *h);
 typedef struct {
     int64_t scratch_bytes;     /* device memory owned by the handle                        */
     int32_t seq_path;          /* 0 none, 1 wavefront-per-instance LDS, 2 workgroup-per-
-                                  instance LDS, 3 rows in global memory                    */
+                                  instance LDS, 3 rows in global memory, 4 bit-set rows
+                                  (DEFT_FLAG_SUBSET_SUM; what SEQUENTIAL calls run on)     */
     int32_t seq_threads;       /* threads cooperating on one instance                      */
     int32_t seq_cells_per_thread;
     int32_t seq_lds_bytes;     /* LDS per workgroup                                        */

@@ -26,6 +26,7 @@ EXPORTS = ("deft_knapsack_create", "deft_knapsack_solve_batch", "deft_knapsack_d
            "deft_knapsack_solve_batch_static", "deft_knapsack_measure_peaks")
 STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 FLAG_VALUES_ARE_WEIGHTS = 1
+FLAG_SUBSET_SUM = 2
 
 
 class deft_knapsack_config_t(ctypes.Structure):

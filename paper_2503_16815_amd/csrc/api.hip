@@ -20,6 +20,7 @@ constexpr int32_t kMaxCapacity = 1 << 24;
 constexpr int32_t kMaxJointCapacity = 4095;
 constexpr int32_t kMaxIterations = 4096;
 constexpr int32_t kMaxPacked16Capacity = 26623;  // the longest row of 16-bit cells that is compiled
+constexpr int32_t kMaxSubsetSumCapacity = 65535;  // the longest bit-set row that is compiled
 
 struct DeviceGuard {
     int prev = -1;
@@ -49,6 +50,9 @@ struct deft_knapsack {
     void *glob_scratch = nullptr;
     unsigned long long *glob_streamed = nullptr;  // device counter read by get_profile
     unsigned long long *lds_swept = nullptr;      // device counter read by get_profile (LDS path)
+
+    bool use_bits = false;        // SEQUENTIAL mode runs the bit-set kernels (DEFT_FLAG_SUBSET_SUM)
+    SeqBitsPlan bits_plan{};
 
     void *sim_buffers = nullptr;  // task-queue simulation: allocated by its first call
 
@@ -99,7 +103,7 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
 {
     if (out) *out = nullptr;
     if (!cfg || !out) return DEFT_ERR_INVALID_ARG;
-    if ((cfg->flags & ~(uint32_t)DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0 || cfg->device < 0 || cfg->max_batch < 1 || cfg->max_items < 1 ||
+    if ((cfg->flags & ~(uint32_t)(DEFT_FLAG_VALUES_ARE_WEIGHTS | DEFT_FLAG_SUBSET_SUM)) != 0 || cfg->device < 0 || cfg->max_batch < 1 || cfg->max_items < 1 ||
         cfg->max_knapsacks < 1 || cfg->max_capacity < 0 || cfg->max_c1 < 0 || cfg->max_c2 < 0)
         return DEFT_ERR_INVALID_ARG;
     const bool want_seq = cfg->max_capacity > 0;
@@ -110,8 +114,14 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
         cfg->max_c2 > kMaxJointCapacity)
         return DEFT_ERR_LIMIT;
     if (want_joint && cfg->max_knapsacks < 2) return DEFT_ERR_INVALID_ARG;
-    const bool packed16 = (cfg->flags & DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0;
-    if (packed16 && (!want_seq || cfg->max_capacity > kMaxPacked16Capacity)) return DEFT_ERR_LIMIT;
+    const bool subset_sum = (cfg->flags & DEFT_FLAG_SUBSET_SUM) != 0;
+    if (subset_sum && (!want_seq || cfg->max_capacity > kMaxSubsetSumCapacity)) return DEFT_ERR_LIMIT;
+    // the other sequential-layout modes of a subset-sum handle run on rows of 16-bit cells where
+    // those reach, on the 32-bit rows beyond
+    const bool packed16 = (cfg->flags & DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0 ||
+                          (subset_sum && cfg->max_capacity <= kMaxPacked16Capacity);
+    if ((cfg->flags & DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0 && (!want_seq || cfg->max_capacity > kMaxPacked16Capacity))
+        return DEFT_ERR_LIMIT;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess) {
@@ -175,6 +185,18 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
                     }
                 }
             }
+        }
+    }
+    if (st == DEFT_OK && subset_sum) {
+        const int lds_wg = (int)prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin
+                                                                : (int)prop.sharedMemPerBlock;
+        if (!seq_bits_plan(cfg->max_capacity, cfg->max_items, lds_wg, &h->bits_plan)) {
+            st = DEFT_ERR_LIMIT;  // (an item list too long for the LDS beside the row)
+        } else if (seq_bits_prepare(h->bits_plan) != hipSuccess) {
+            (void)hipGetLastError();
+            st = DEFT_ERR_DEVICE;
+        } else {
+            h->use_bits = true;
         }
     }
     if (st == DEFT_OK && want_joint) {
@@ -252,7 +274,11 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
 
     hipError_t e = hipSuccess;
-    if (b->mode == DEFT_MODE_SEQUENTIAL || (probing && !on_lds)) {
+    if (b->mode == DEFT_MODE_SEQUENTIAL && h->use_bits) {
+        if (prof) prof->sweep_begin(st);
+        e = seq_bits_launch(h->bits_plan, a, st);
+        if (prof) prof->sweep_end(st);
+    } else if (b->mode == DEFT_MODE_SEQUENTIAL || (probing && !on_lds)) {
         if (h->seq_path == 3) {
             e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof, h->glob_streamed);
         } else {
@@ -319,6 +345,12 @@ extern "C" deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, con
     Profiler *prof = h->profiling ? &h->prof : nullptr;
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
     const auto solve = [&](const BatchArgs &x) -> hipError_t {
+        if (h->use_bits && x.mode == DEFT_MODE_SEQUENTIAL) {
+            if (prof) prof->sweep_begin(st);
+            const hipError_t rc = seq_bits_launch(h->bits_plan, x, st);
+            if (prof) prof->sweep_end(st);
+            return rc;
+        }
         if (h->seq_path == 3) return seq_global_launch(h->glob_plan, x, h->glob_scratch, st, prof, h->glob_streamed);
         if (prof) prof->sweep_begin(st);
         const hipError_t rc = x.mode == DEFT_MODE_SEQUENTIAL
@@ -352,6 +384,13 @@ extern "C" deft_status_t deft_knapsack_get_info(const deft_knapsack_t *h, deft_k
     } else if (h->seq_path == 3) {
         info->seq_threads = h->glob_plan.threads;
         info->seq_cells_per_thread = h->glob_plan.cells_per_thread;
+    }
+    if (h->use_bits) {  // what SEQUENTIAL calls run on
+        info->seq_path = 4;
+        info->seq_threads = 64;
+        info->seq_cells_per_thread = h->bits_plan.words_per_lane * 32;
+        info->seq_lds_bytes = h->bits_plan.lds_bytes;
+        info->seq_workgroups_per_cu = 0;
     }
     info->joint_path = h->joint_path;
     info->compute_units = h->compute_units;

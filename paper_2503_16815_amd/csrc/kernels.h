@@ -66,6 +66,21 @@ hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan);
 hipError_t seq_lds_rec_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
                               hipStream_t stream, unsigned long long *swept_cells);
 
+// ---- sequential mode, value = weight, one bit per cell (seq_bits.hip) -----------
+// One wavefront per instance; the reachable sums as a bit set in registers and LDS, the
+// selection from a per-cell "first item that reached this sum" array in LDS.  No scratch.
+struct SeqBitsPlan {
+    int32_t variant;         // index into the compiled words-per-lane table
+    int32_t words_per_lane;  // K: capacities up to 2048 K - 1
+    int32_t row_words;       // 64 K
+    int32_t first_ints;      // LDS ints of the 16-bit per-cell array
+    int32_t n_pad;           // entries of the stage's item list in LDS
+    int32_t lds_bytes;       // dynamic LDS per workgroup (= per instance)
+};
+bool seq_bits_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_wg_bytes, SeqBitsPlan *plan);
+hipError_t seq_bits_prepare(const SeqBitsPlan &plan);
+hipError_t seq_bits_launch(const SeqBitsPlan &plan, const BatchArgs &args, hipStream_t stream);
+
 // ---- per-call HIP-event timing (profile.hip) ---------------------------------
 class Profiler {
 public:

@@ -1,0 +1,313 @@
+// Sequential multiple-knapsack solve for instances whose values equal their weights (the
+// paper's Problem 1: a bucket's profit is its communication time), one bit per capacity cell.
+//
+// With v == w the DP value row[c] is the largest reachable sum not above c, so the row is
+// described by the set of reachable sums: one bit per cell, and an item is a shift-and-or of
+// the whole set, reach |= reach << w, 32 cells per instruction.  The selection the exact DP
+// walks back (take an item at a cell only when it strictly improves the value, walk from
+// the last item: among optimal subsets the one with the smallest mask) comes out of one
+// more array, first[t] = the first offered item that made the sum t reachable:
+//   the DP keeps item q at cell c exactly when the best sum up to c rises with item q, i.e.
+//   when the target t = row_q[c] was not reachable before q; if q is not kept the target
+//   stays, if it is the target becomes t - w_q.  So the walk is t = row[C]; while t > 0:
+//   q = first[t], take q, t -= w_q - a chain of LDS lookups, one per item taken, with no keep
+//   table and no memory round trips.
+// One wavefront owns an instance (one 64-thread workgroup; no barriers).  Word i of the set
+// (cells 32 i .. 32 i + 31) lives in lane i % 64, register slot i / 64, with a copy in LDS
+// that the shifted operand is read from; first[] (16 bits per cell) and the stage's offered
+// items (weight, index) live in LDS too, so the kernel needs no scratch memory at all.
+// Below the set a guard zone of zero words serves the reads of light items; heavier items
+// clamp their word index into it.
+#include <limits.h>
+
+#include <type_traits>
+
+#include "instance_check.h"
+
+namespace deft {
+
+namespace {
+
+constexpr int kBitsGuardWords = 128;  // zero words below the set: items up to 32 * 126 cells read without clamping
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // one wavefront: LDS executes its instructions in order; only the compiler has to be
+    // kept from reordering
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+template <class Op>
+__device__ __forceinline__ int bits_wave_reduce(int x, Op op)
+{
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0x124, 0xf, 0xf, false));  // row_ror:4
+    x = op(x, __builtin_amdgcn_update_dpp(x, x, 0x128, 0xf, 0xf, false));  // row_ror:8
+    return op(op(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+              op(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+}
+__device__ __forceinline__ int bits_wave_sum(int x) { return bits_wave_reduce(x, [](int a, int b) { return a + b; }); }
+__device__ __forceinline__ int bits_wave_max(int x) { return bits_wave_reduce(x, [](int a, int b) { return max(a, b); }); }
+
+// One stage's sweep over `nact` offered items (weights in lw[], LDS) at capacity C, NB words
+// per lane.  Returns the stage's value (largest reachable sum <= C); first[t] is set for
+// every reachable t in 1 .. C.  The sweep ends early once every sum up to C is reachable
+// (checked after every eighth item): no later item can become the first to reach anything.
+template <int NB>
+__device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const int32_t *lw, int lane, int nact, int C)
+{
+    uint32_t own[NB], need[NB];  // need: the cells of the word that are <= C
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+        const int cell0 = (k * 64 + lane) * 32;
+        need[k] = cell0 + 31 <= C ? 0xffffffffu : cell0 > C ? 0u : (1u << (C - cell0 + 1)) - 1u;
+        own[k] = (k == 0 && lane == 0) ? 1u : 0u;  // the empty sum
+        set[k * 64 + lane] = own[k];
+    }
+    wave_lds_sync();
+    for (int q0 = 0; q0 < nact; q0 += 64) {
+        const int wchunk = q0 + lane < nact ? lw[q0 + lane] : 0;  // 64 weights in a register
+        const int q1 = min(q0 + 64, nact);
+        for (int q = q0; q < q1; ++q) {
+            const int w = __builtin_amdgcn_readlane(wchunk, q & 63);
+            // new word i = old cells 32 i - w .. 32 i - w + 31: two neighbouring old words, funnel-shifted
+            const int ws = w >> 5, bs = w & 31;
+            const int sh = (32 - bs) & 31;
+            const int base = lane - ws - (bs ? 1 : 0);  // old word below the pair of slot 0
+            uint32_t fresh[NB];
+            uint32_t any = 0;
+            if (ws + 2 <= kBitsGuardWords) {
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    const uint32_t lo = set[base + k * 64], hi = set[base + k * 64 + 1];
+                    const uint32_t nw = own[k] | __builtin_amdgcn_alignbit(hi, lo, sh);
+                    fresh[k] = nw & ~own[k] & need[k];
+                    own[k] = nw;
+                    any |= fresh[k];
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    const uint32_t lo = set[max(base + k * 64, -kBitsGuardWords)];
+                    const uint32_t hi = set[max(base + k * 64 + 1, -kBitsGuardWords)];
+                    const uint32_t nw = own[k] | __builtin_amdgcn_alignbit(hi, lo, sh);
+                    fresh[k] = nw & ~own[k] & need[k];
+                    own[k] = nw;
+                    any |= fresh[k];
+                }
+            }
+            wave_lds_sync();  // the old set has been read
+            if (__builtin_amdgcn_ballot_w64(any != 0) != 0ull) {
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    if (__builtin_amdgcn_ballot_w64(fresh[k] != 0) == 0ull) continue;  // nobody reached anything here
+                    set[k * 64 + lane] = own[k];
+                    uint32_t f = fresh[k];
+                    while (f) {  // item q is the first to reach these sums
+                        const int b = __builtin_ctz(f);
+                        f &= f - 1;
+                        first[(k * 64 + lane) * 32 + b] = (uint16_t)q;
+                    }
+                }
+                wave_lds_sync();  // the new set is visible
+            }
+            if ((q & 7) == 7) {
+                bool full = true;
+#pragma unroll
+                for (int k = 0; k < NB; ++k) full = full && (own[k] & need[k]) == need[k];
+                if (__builtin_amdgcn_ballot_w64(!full) == 0ull) return C;  // every sum up to C is reachable
+            }
+        }
+    }
+    int best = 0;
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+        const uint32_t x = own[k] & need[k];
+        if (x) best = max(best, (k * 64 + lane) * 32 + 31 - __builtin_clz(x));
+    }
+    return bits_wave_max(best);
+}
+
+template <int N>
+__device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, uint16_t *first, const int32_t *lw, int lane,
+                                                   int nact, int C)
+{
+    if (nb == N) {
+        return sweep_bits<N>(set, first, lw, lane, nact, C);
+    } else if constexpr (N > 1) {
+        return sweep_bits_dispatch<N - 1>(nb, set, first, lw, lane, nact, C);
+    }
+    return 0;
+}
+
+// K: words per lane the variant is compiled for (capacities up to 2048 K - 1).
+// LDS: [guard zeros][set: row_words][first: first_ints ints][lw: n_pad][li: n_pad]
+template <int K>
+__global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words, int first_ints, int n_pad)
+{
+    extern __shared__ __align__(16) int32_t lds_bits[];
+    const int inst = blockIdx.x, lane = threadIdx.x;
+    uint32_t *set = reinterpret_cast<uint32_t *>(lds_bits) + kBitsGuardWords;
+    uint16_t *first = reinterpret_cast<uint16_t *>(set + row_words);
+    int32_t *lw = reinterpret_cast<int32_t *>(set + row_words) + first_ints;
+    int32_t *li = lw + n_pad;
+
+    int status = check_instance(a, inst, false);
+    const int n = a.n_items[inst], m = a.n_knapsacks[inst];
+    const int32_t *__restrict__ W = a.weights + (size_t)inst * a.item_stride;
+    const int32_t *__restrict__ V = a.values + (size_t)inst * a.item_stride;
+    if (status == DEFT_OK) {  // the handle's promise: every value equals its weight
+        bool differs = false;
+        for (int i = lane; i < n; i += 64) differs = differs || V[i] != W[i];
+        if (__builtin_amdgcn_ballot_w64(differs) != 0ull) status = DEFT_ERR_INVALID_ARG;
+    }
+    clear_outputs(a, inst, status);
+    if (status != DEFT_OK) return;
+
+    for (int i = lane; i < kBitsGuardWords; i += 64) lds_bits[i] = 0;
+    const int32_t *cap = a.capacities + (size_t)inst * a.knap_stride;
+    const int32_t *ord = a.fill_order ? a.fill_order + (size_t)inst * a.knap_stride : nullptr;
+    const int cap_l = lane < m ? cap[lane] : 0;
+    const int ord_l = ord && lane < m ? ord[lane] : lane;
+    const int w_first = lane < n ? W[lane] : 0;
+    int32_t *out_asg = a.assignment + (size_t)inst * a.item_stride;
+    int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
+    int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
+    wave_lds_sync();
+
+    // items already placed: bit (i / 64) of lane (i % 64)
+    unsigned long long placed = 0;
+    long long total = 0;
+    for (int s = 0; s < m; ++s) {
+        const int j = __builtin_amdgcn_readlane(ord_l, s);
+        const int C = __builtin_amdgcn_readlane(cap_l, j);
+        // offered items: not yet placed and able to fit at all, ascending index
+        int cnt = 0, unplaced = 0, offered_weight = 0;
+        for (int i0 = 0; i0 < n; i0 += 64) {
+            const int i = i0 + lane;
+            const int w = i >= n ? 0 : i0 == 0 ? w_first : W[i];
+            const bool open = i < n && ((placed >> (i0 >> 6)) & 1ull) == 0;
+            const bool f = open && w <= C;
+            unplaced += __popcll(__builtin_amdgcn_ballot_w64(open));
+            const unsigned long long mask = __builtin_amdgcn_ballot_w64(f);
+            if (f) {
+                const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+                lw[pos] = w;
+                li[pos] = i;
+                offered_weight += w;
+            }
+            cnt += __popcll(mask);
+        }
+        if (unplaced == 0) break;  // every item is placed: the remaining stages stay empty
+        if (cnt == 0) continue;
+        wave_lds_sync();
+        // (a lane's share is clamped just above the largest capacity, so that the sum stays in
+        // range and still exceeds C whenever the true sum does)
+        offered_weight = bits_wave_sum(min(offered_weight, (1 << 24) + 1));
+        int value;
+        if (offered_weight <= C) {
+            // everything offered fits together: the DP takes it all (every value is positive)
+            for (int p = lane; p < cnt; p += 64) {
+                const int i = li[p];
+                out_asg[i] = j;
+            }
+            for (int i0 = 0; i0 < n; i0 += 64) {
+                const int i = i0 + lane;
+                const int w = i >= n ? 0 : i0 == 0 ? w_first : W[i];
+                if (i < n && ((placed >> (i0 >> 6)) & 1ull) == 0 && w <= C) placed |= 1ull << (i0 >> 6);
+            }
+            value = offered_weight;
+        } else {
+            const int nb = (C / 32 + 64) / 64;  // words per lane covering cells 0 .. C
+            value = sweep_bits_dispatch<K>(nb, set, first, lw, lane, cnt, C);
+            // the walk: every lane follows the same chain; the lane that owns an item's bit marks it
+            int t = value;
+            int guard = cnt;  // (a chain is never longer than the list)
+            while (t > 0 && guard-- > 0) {
+                const int q = first[t];
+                const int w = lw[min(q, cnt - 1)], i = li[min(q, cnt - 1)];
+                if (lane == (i & 63)) placed |= 1ull << (i >> 6);
+                if (lane == 0) out_asg[i] = j;
+                t -= w;
+            }
+            if (t != 0 && lane == 0) a.status[inst] = DEFT_ERR_DEVICE;  // (never expected)
+        }
+        if (lane == 0) {
+            out_kv[j] = value;
+            out_kl[j] = value;
+        }
+        total += value;
+        wave_lds_sync();
+    }
+    if (lane == 0) a.total_value[inst] = total;
+}
+
+struct BitsVariant {
+    int words;  // per lane
+    const void *fn;
+};
+#define DEFT_BITS_VARIANT(K) { K, reinterpret_cast<const void *>(&seq_bits_kernel<K>) }
+const BitsVariant kBitsVariants[] = {
+    DEFT_BITS_VARIANT(2),   // capacity <= 4095
+    DEFT_BITS_VARIANT(5),   // <= 10239
+    DEFT_BITS_VARIANT(7),   // <= 14335
+    DEFT_BITS_VARIANT(10),  // <= 20479
+    DEFT_BITS_VARIANT(13),  // <= 26623
+    DEFT_BITS_VARIANT(19),  // <= 38911
+    DEFT_BITS_VARIANT(32),  // <= 65535
+};
+#undef DEFT_BITS_VARIANT
+constexpr int kNumBitsVariants = 7;
+
+}  // namespace
+
+bool seq_bits_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_wg_bytes, SeqBitsPlan *plan)
+{
+    const int32_t n_pad = (max_items + 7) & ~7;
+    for (int i = 0; i < kNumBitsVariants; ++i) {
+        const int K = kBitsVariants[i].words;
+        if ((int64_t)max_capacity > (int64_t)K * 2048 - 1) continue;
+        const int64_t row_words = (int64_t)K * 64;
+        const int64_t first_ints = ((int64_t)max_capacity + 2 + 1) / 2;  // 16 bits per cell 0 .. max_capacity
+        const int64_t lds = (kBitsGuardWords + row_words + first_ints + 2 * (int64_t)n_pad) * 4;
+        if (lds > lds_per_wg_bytes - 256) return false;
+        plan->variant = i;
+        plan->words_per_lane = K;
+        plan->row_words = (int32_t)row_words;
+        plan->first_ints = (int32_t)first_ints;
+        plan->n_pad = n_pad;
+        plan->lds_bytes = (int32_t)lds;
+        return true;
+    }
+    return false;
+}
+
+hipError_t seq_bits_prepare(const SeqBitsPlan &plan)
+{
+    // the attribute belongs to the kernel, not to the handle: the most any handle may ask for
+    // (a compute unit's LDS less the few static words of the input checks)
+    return hipFuncSetAttribute(kBitsVariants[plan.variant].fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               160 * 1024 - 256);
+}
+
+hipError_t seq_bits_launch(const SeqBitsPlan &p, const BatchArgs &a, hipStream_t st)
+{
+    const dim3 grid((unsigned)a.batch), block(64);
+    const size_t lds = (size_t)p.lds_bytes;
+    switch (p.variant) {
+    case 0: hipLaunchKernelGGL(seq_bits_kernel<2>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    case 1: hipLaunchKernelGGL(seq_bits_kernel<5>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    case 2: hipLaunchKernelGGL(seq_bits_kernel<7>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    case 3: hipLaunchKernelGGL(seq_bits_kernel<10>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    case 4: hipLaunchKernelGGL(seq_bits_kernel<13>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    case 5: hipLaunchKernelGGL(seq_bits_kernel<19>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    case 6: hipLaunchKernelGGL(seq_bits_kernel<32>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace deft

@@ -79,7 +79,8 @@ def test_create_rejects_bad_configs_without_a_device(lib):
 
     assert create(None, ctypes.byref(h)) == 1
     assert create(ctypes.byref(Cfg(**ok)), None) == 1
-    assert rc(flags=2) == 1                              # an unknown flag bit
+    assert rc(flags=4) == 1                              # an unknown flag bit
+    assert rc(flags=2, max_capacity=65536) == 2          # bit-set rows end at 65535 cells
     assert rc(flags=1, max_capacity=26624) == 2          # 16-bit rows end at 26623 cells
     assert rc(flags=1, max_capacity=0, max_c1=10, max_c2=10) == 2   # the flag needs the sequential layout
     assert rc(max_batch=0) == 1

@@ -1,0 +1,98 @@
+"""GPU parity of the bit-set kernels (handles created with DEFT_FLAG_SUBSET_SUM: every value
+equals its weight, one bit per capacity cell, the selection read off the per-cell record of
+the first item that reached each sum), through the C ABI, bit-exact against the oracle's
+int64 DP and walk on every output: every compiled variant, the paper's shapes at full size."""
+import numpy as np
+import pytest
+
+from paper_2503_16815_amd import workloads as W
+from tests.test_gpu_parity import assert_same, binding, run  # noqa: F401  (binding is a fixture)
+from tests.test_gpu_schedule import FIELDS, assert_same as assert_same_schedule
+
+pytestmark = pytest.mark.gpu
+
+FLAG = 2   # DEFT_FLAG_SUBSET_SUM
+
+VARIANTS = [(700, 1023), (4000, 4095), (10000, 10239), (14000, 14335), (20000, 20479), (26000, 26623),
+            (38000, 38911), (65000, 65535)]
+
+
+@pytest.mark.parametrize("cap_hi,max_capacity", VARIANTS)
+def test_random_ragged_every_variant(binding, oracle, cap_hi, max_capacity):
+    """Ragged n and m, random fill order, capacities from 0 up; light items, items of a few
+    hundred to a few thousand cells (word shifts with every bit offset) and items heavier than
+    the guard zone below the set (clamped reads)."""
+    for seed, n_max, w_hi in ((1, 60, max(9, cap_hi // 40)), (2, 45, max(20, cap_hi // 6)), (3, 30, cap_hi)):
+        kb = W.random_sequential(21000 + 7 * cap_hi + seed, batch=37, n_max=n_max, m_max=4, w_hi=w_hi, v_hi=9,
+                                 cap_hi=cap_hi, ties=True)
+        run(binding, oracle, kb, max_capacity=max_capacity, flags=FLAG)
+
+
+@pytest.mark.parametrize("max_capacity,n_max,w_hi,batch", [
+    (4095, 600, 30, 40), (10239, 1450, 30, 28), (14335, 1890, 30, 24), (26623, 3000, 39, 16), (65535, 2000, 140, 8),
+])
+def test_rows_that_fill_early_every_variant(binding, oracle, max_capacity, n_max, w_hi, batch):
+    """Capacities in the upper half of each variant's range, light items, several windows in
+    random order: the sweeps end early and the leftovers feed the next window."""
+    kb = W.filling_rows(22000 + max_capacity, batch=batch, n_max=n_max, m_max=3, w_hi=w_hi,
+                        cap_lo=max_capacity * 55 // 100, cap_hi=max_capacity)
+    run(binding, oracle, kb, max_capacity=max_capacity, flags=FLAG)
+
+
+def test_instances_that_break_the_promise_and_other_faults(binding, oracle):
+    kb = W.random_sequential(25001, batch=8, n_max=12, m_max=2, w_hi=9, v_hi=9, cap_hi=30, ragged=False, ties=True)
+    ref = oracle.solve_batch(kb, cap_limit=30)
+    kb.values[2, 5] += 1            # breaks the promise
+    kb.weights[4, 0] = 0            # invalid anyway
+    kb.values[4, 0] = 0
+    kb.capacities[6, 1] = 31        # above the limit
+    kb.fill_order[7] = [1, 1]       # not a permutation
+    bad = oracle.solve_batch(kb, cap_limit=30)
+    assert bad.status.tolist() == [0, 0, 0, 0, 1, 0, 2, 1]
+    import torch
+    out = binding.solve(kb, max_capacity=30, flags=FLAG)
+    torch.cuda.synchronize()
+    assert out.status.cpu().numpy().tolist() == [0, 0, 1, 0, 1, 0, 2, 1]
+    for b in range(8):
+        if b == 2:
+            assert int(out.total_value[b]) == 0 and (out.assignment[b].cpu().numpy() == -1).all()
+            assert (out.knap_value[b].cpu().numpy() == 0).all() and (out.knap_load[b].cpu().numpy() == 0).all()
+        else:
+            want = bad if b in (4, 6, 7) else ref
+            assert int(out.total_value[b]) == int(want.total_value[b])
+            assert np.array_equal(out.assignment[b].cpu().numpy(), want.assignment[b])
+            assert np.array_equal(out.knap_value[b].cpu().numpy(), want.knap_value[b])
+            assert np.array_equal(out.knap_load[b].cpu().numpy(), want.knap_load[b])
+
+
+def test_create_limits_and_info(binding):
+    with pytest.raises(binding.DeftError) as e:
+        binding.DeftKnapsack(max_batch=4, max_items=8, max_knapsacks=2, max_capacity=65536, flags=FLAG)
+    assert e.value.code == binding.DEFT_ERR_LIMIT
+    with binding.DeftKnapsack(max_batch=4, max_items=8, max_knapsacks=2, max_capacity=13000, flags=FLAG) as h:
+        info = h.info()
+        assert info.seq_path == 4 and info.seq_threads == 64 and info.seq_cells_per_thread == 7 * 32
+
+
+def test_paper_shapes_at_full_size(binding, oracle):
+    """The value-equals-weight sequential workloads of bench.py at their full sizes."""
+    run(binding, oracle, W.resnet101_sweep(), flags=FLAG)
+    run(binding, oracle, W.vgg19_sweep(), flags=FLAG)
+    for k in (1, 3):
+        run(binding, oracle, W.resnet101_shaped(k=k), flags=FLAG)
+    # the other modes of such a handle (rows of 16-bit cells)
+    run(binding, oracle, W.backward_stage_shaped(batch=64), flags=FLAG)
+    run(binding, oracle, W.inflation_sweep_shaped(batch=64), flags=FLAG)
+
+
+def test_task_queues(binding, oracle):
+    """Forward stages on the bit-set kernels, backward stages on rows of 16-bit cells."""
+    import torch
+    sb = W.resnet101_schedules(batch=256)
+    want = oracle.simulate_batch(sb, nthreads=16)
+    cap = int(max(sb.backward_time.max(), sb.forward_time.max()))
+    with binding.DeftKnapsack(max_batch=sb.batch, max_items=sb.n_buckets, max_knapsacks=2, max_capacity=cap,
+                              flags=FLAG) as h:
+        out = binding.simulate_schedule(h, binding.DeviceSchedules(sb, h.device))
+        torch.cuda.synchronize()
+        assert_same_schedule({k: getattr(out, k).cpu().numpy() for k in FIELDS}, want)
