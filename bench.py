@@ -33,15 +33,17 @@ PEAK_INT_LANE_OPS = N_CU * 64 * CLOCK_HZ                              # 39.3e12 
 PEAK_HBM_GBS = 8000.0
 
 
-def cells_not_swept(kb, ref, lds_path: bool, enumerate_small: bool = True):
+def cells_not_swept(kb, ref, lds_path: bool, enumerate_small: bool = True, check_every: int = 8):
     """Touched cells (as the oracle counts them) that the solver never evaluates, for a
     sequential-mode batch; returns (settled, full):
     settled - stages settled without a DP sweep: the offered items (not placed by an earlier
         stage, w <= C) all fit together, or (LDS-row path only) number at most six;
     full    - (LDS-row path, instances whose values all equal their weights) the items of a swept
-        stage that come after the row is full: after every eighth offered item the solver checks
-        whether every sum 0..C can be reached and ends the stage's sweep if so.  Replayed here
-        with the subset-sum bit recurrence on Python integers.
+        stage that come after the capacity itself is reached: after every eighth offered item
+        the solver checks whether the sum C can be reached and ends the stage's sweep if so (the
+        value is final and the walk back from C takes none of the later items).  Replayed here
+        with the subset-sum bit recurrence on Python integers; `check_every` = 1 for the bit-set
+        kernel, which looks after every item.
     The oracle's assignment says which stage placed what."""
     if kb.mode != 0:
         return 0, 0
@@ -70,7 +72,8 @@ def cells_not_swept(kb, ref, lds_path: bool, enumerate_small: bool = True):
                 ws = w[b][offered[b]].tolist()
                 for q, wq in enumerate(ws):
                     bits |= bits << wq
-                    if q % 8 == 7 and (bits & goal) == goal:
+                    bits &= goal
+                    if q % check_every == check_every - 1 and (bits >> C) & 1:
                         full += sum(C - x + 1 for x in ws[q + 1:])
                         break
         placed |= (ref.assignment == j[:, None]) & live[:, None]
@@ -294,10 +297,10 @@ def run_solver(args):
     table = [int(r.table_cells.sum()) for r in refs]
     # The job's cell-updates are the oracle's count (touched cells of every stage).  The solver
     # does not evaluate all of them: stages it settles without a sweep and, where every value
-    # equals its weight, the items after the row is full.  `value` and the roofline are priced
+    # equals its weight, the items after the capacity itself is reached.  `value` and the roofline are priced
     # on the cell-updates it does evaluate (swept_step); both counts are reported.
     not_swept = {path: [cells_not_swept(kb, r, path) for kb, r in zip(calls, refs)] for path in (False, True)}
-    not_swept["bits"] = [cells_not_swept(kb, r, True, enumerate_small=False) for kb, r in zip(calls, refs)]
+    not_swept["bits"] = [cells_not_swept(kb, r, True, enumerate_small=False, check_every=1) for kb, r in zip(calls, refs)]
     settled = sum(x[0] for x in not_swept[True])     # corrected below once the handle says which path runs
     after_full = sum(x[1] for x in not_swept[True])
     cells_step = sum(touched)
@@ -448,7 +451,7 @@ def run_solver(args):
                     lds_bytes_per_workgroup=int(info.seq_lds_bytes),
                     workgroups_per_cu=int(info.seq_workgroups_per_cu), scratch_bytes=int(info.scratch_bytes),
                     oracle_cell_updates_of_stages_settled_without_sweep=settled,
-                    oracle_cell_updates_after_the_row_is_full=after_full,
+                    oracle_cell_updates_after_the_capacity_is_reached=after_full,
                     oracle_recursion_cell_updates_per_step=recursion_cells),
         effective_cell_updates_per_s=cells_step / (ms_step * 1e-3),
         instances_per_s=inst_step / (ms_step * 1e-3), parity_vs_oracle=parity,

@@ -54,8 +54,9 @@ __device__ __forceinline__ int bits_wave_max(int x) { return bits_wave_reduce(x,
 
 // One stage's sweep over `nact` offered items (weights in lw[], LDS) at capacity C, NB words
 // per lane.  Returns the stage's value (largest reachable sum <= C); first[t] is set for
-// every reachable t in 1 .. C.  The sweep ends early once every sum up to C is reachable
-// (checked after every eighth item): no later item can become the first to reach anything.
+// every reachable t in 1 .. C (when the sweep ends early: for every t reached so far).
+// The sweep ends as soon as C itself is reachable: the value is final, and the walk from C
+// only follows sums that were reached by earlier items.
 template <int NB>
 __device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const int32_t *lw, int lane, int nact, int C)
 {
@@ -68,6 +69,8 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const 
         set[k * 64 + lane] = own[k];
     }
     wave_lds_sync();
+    const int c_lane = (C >> 5) & 63;
+    const uint32_t c_bit = 1u << (C & 31);
     for (int q0 = 0; q0 < nact; q0 += 64) {
         const int wchunk = q0 + lane < nact ? lw[q0 + lane] : 0;  // 64 weights in a register
         const int q1 = min(q0 + 64, nact);
@@ -112,13 +115,12 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const 
                         first[(k * 64 + lane) * 32 + b] = (uint16_t)q;
                     }
                 }
+                // the capacity itself has become reachable: the value is final and the walk
+                // back from C only meets sums that were reached earlier
+                // (C's word is in the last slot: NB is the smallest count that covers it)
+                const bool reached = lane == c_lane && (fresh[NB - 1] & c_bit) != 0;
                 wave_lds_sync();  // the new set is visible
-            }
-            if ((q & 7) == 7) {
-                bool full = true;
-#pragma unroll
-                for (int k = 0; k < NB; ++k) full = full && (own[k] & need[k]) == need[k];
-                if (__builtin_amdgcn_ballot_w64(!full) == 0ull) return C;  // every sum up to C is reachable
+                if (__builtin_amdgcn_ballot_w64(reached) != 0ull) return C;
             }
         }
     }

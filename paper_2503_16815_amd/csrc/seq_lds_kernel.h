@@ -245,11 +245,12 @@ constexpr int kSecondBase = 60416;
 // shallower one replaces the incumbent only when strictly greater, as the recursion does
 // on its way back up.
 //
-// VEQW, sequential mode: once every cell up to C holds its own index (every sum up to the
-// capacity can be reached: the kept value row[c] - c is 0 everywhere) no later item can
-// improve anything, so the sweep ends there.  Checked after every eighth item, between two
-// items: a wavefront that still has an unfinished cell stores the check's tag in
-// `unfinished`, and after a barrier everyone looks at it.
+// VEQW, sequential mode: once cell C holds its own index (the capacity itself can be
+// reached: the kept value row[C] - C is 0) the stage's value is final, and no later item is
+// taken at C (a take needs a strict improvement), so the walk back from C passes every later
+// item and only ever reads keep rows up to here: the sweep ends there.  Checked after every
+// eighth item, between two items: the wavefront that owns cell C stores the check's tag in
+// `unfinished` while the cell is short of C, and after a barrier everyone looks at it.
 // Returns the number of items swept (the keep rows beyond were never written).
 template <int T, int NB, int G, int NW, bool ADDTID, bool VEQW, bool REC, bool SKIP_UNCHANGED>
 __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
@@ -407,16 +408,16 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
         if constexpr (ADDTID) wait_lds();
         lds_sync<T>();  // the new row is visible
     };
-    // After item q: is the row full?  (The same answer in every lane of the instance.)
-    auto row_is_full = [&](int q) -> bool {
+    // After item q: can the capacity itself be reached?  (The same answer in every lane of the instance.)
+    auto capacity_reached = [&](int q) -> bool {
         if constexpr (!STOP_WHEN_FULL) {
             return false;
         } else {
             if ((q % kCheckEvery) != kCheckEvery - 1) return false;
             int any = 0;
 #pragma unroll
-            for (int k = 0; k < NB; ++k)  // the cells above C (in the last G slots at most) do not count
-                any |= (k < NB - G || k * T + tid <= C) ? own[k] : 0;
+            for (int k = NB - G; k < NB; ++k)  // cell C sits in one of the last G slots
+                any |= k * T + tid == C ? own[k] : 0;
             const bool wave_full = __builtin_amdgcn_ballot_w64(any != 0) == 0ull;
             if constexpr (T == 64) {
                 return wave_full;
@@ -437,13 +438,13 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             int w = __builtin_amdgcn_readlane(cur.x, q & 63);
             while (w <= light_max) {  // run of light items
                 item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (row_is_full(q)) { hand_over(q); return q + 1; }
+                if (capacity_reached(q)) { hand_over(q); return q + 1; }
                 if (++q >= q1) break;
                 w = __builtin_amdgcn_readlane(cur.x, q & 63);
             }
             if (q < q1) {  // one heavy item
                 item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (row_is_full(q)) { hand_over(q); return q + 1; }
+                if (capacity_reached(q)) { hand_over(q); return q + 1; }
                 ++q;
             }
         }
@@ -653,18 +654,14 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
         wait_lds();
         lds_sync<T>();  // the new row is visible
     };
-    auto row_is_full = [&](int q) -> bool {
+    auto capacity_reached = [&](int q) -> bool {
         if constexpr (!STOP_WHEN_FULL) {
             return false;
         } else {
             if ((q % kCheckEvery) != kCheckEvery - 1) return false;
-            uint32_t any = 0;
-#pragma unroll
-            for (int j = 0; j < NP; ++j) {  // the cells above C (in the top two pairs at most) do not count
-                uint32_t m = 0xffffffffu;
-                if (j >= NP - 2) m = (2 * j * T + tid <= C ? 0xffffu : 0u) | ((2 * j + 1) * T + tid <= C ? 0xffff0000u : 0u);
-                any |= own[j] & m;
-            }
+            // cell C sits in the top pair
+            constexpr int j = NP - 1;
+            const uint32_t any = own[j] & ((2 * j * T + tid == C ? 0xffffu : 0u) | ((2 * j + 1) * T + tid == C ? 0xffff0000u : 0u));
             const bool wave_full = __builtin_amdgcn_ballot_w64(any != 0) == 0ull;
             if constexpr (T == 64) {
                 return wave_full;
@@ -685,7 +682,7 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
             if (w <= wave_first) item(std::integral_constant<int, 0>{}, q, w);
             else if (w <= T) item(std::integral_constant<int, 1>{}, q, w);
             else item(std::integral_constant<int, 2>{}, q, w);
-            if (row_is_full(q)) { hand_over(q); return q + 1; }
+            if (capacity_reached(q)) { hand_over(q); return q + 1; }
         }
         cur = nxt;
         cur_p = nxt_p;

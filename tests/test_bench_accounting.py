@@ -1,5 +1,5 @@
 """bench.py's split of the oracle's cell-updates into those the solver evaluates and those
-it does not (stages settled without a sweep, items after the row is full), no GPU:
+it does not (stages settled without a sweep, items after the capacity is reached), no GPU:
 checked on small cases whose split can be written down by hand."""
 import numpy as np
 
@@ -26,12 +26,20 @@ def test_few_offered_items_count_as_settled_on_the_lds_path_only(oracle):
     assert bench.cells_not_swept(kb, r, False) == (0, 0)
 
 
-def test_items_after_the_row_is_full(oracle):
-    """Twenty items of weight 1 and capacity 7: after the 8th item (the first check) every sum
-    0..7 can be reached, so items 9..20 are never swept: 12 x (7 - 1 + 1) cells."""
+def test_items_after_the_capacity_is_reached(oracle):
+    """Twenty items of weight 1 and capacity 7: at the first check (after the 8th item) the sum
+    7 can be reached, so items 9..20 are never swept: 12 x (7 - 1 + 1) cells.  With a check
+    after every item (the bit-set kernel) the sweep ends after the 7th."""
     kb = make_seq([[1] * 20], [[1] * 20], [[7]])
     r = oracle.solve_batch(kb)
     assert bench.cells_not_swept(kb, r, True) == (0, 12 * 7)
+    assert bench.cells_not_swept(kb, r, True, check_every=1) == (0, 13 * 7)
+    # weight 2, capacity 8: the odd sums are never reached, the capacity is after four items
+    k2 = make_seq([[2] * 20], [[2] * 20], [[8]])
+    assert bench.cells_not_swept(k2, oracle.solve_batch(k2), True) == (0, 12 * 7)
+    # capacity 9: the best is 8, the capacity itself is never reached
+    k3 = make_seq([[2] * 20], [[2] * 20], [[9]])
+    assert bench.cells_not_swept(k3, oracle.solve_batch(k3), True) == (0, 0)
     assert bench.cells_not_swept(kb, r, False) == (0, 0)      # rows in global memory: no such rule
     # values that differ from the weights: the rule does not apply
     kv = make_seq([[1] * 20], [[2] * 20], [[7]])
