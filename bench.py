@@ -40,7 +40,7 @@ def cells_not_swept(kb, ref, lds_path: bool, enumerate_small: bool = True, check
         stage, w <= C) all fit together, or (LDS-row path only) number at most six;
     full    - (LDS-row path, instances whose values all equal their weights) the items of a swept
         stage that come after the capacity itself is reached: after every eighth offered item
-        the solver checks whether the sum C can be reached and ends the stage's sweep if so (the
+        (every second one when at most 64 are offered) the solver checks whether the sum C can be reached and ends the stage's sweep if so (the
         value is final and the walk back from C takes none of the later items).  Replayed here
         with the subset-sum bit recurrence on Python integers; `check_every` = 1 for the bit-set
         kernel, which looks after every item.
@@ -70,10 +70,11 @@ def cells_not_swept(kb, ref, lds_path: bool, enumerate_small: bool = True, check
                 goal = (1 << (C + 1)) - 1
                 bits = 1
                 ws = w[b][offered[b]].tolist()
+                every = check_every if check_every == 1 or len(ws) > 64 else 2
                 for q, wq in enumerate(ws):
                     bits |= bits << wq
                     bits &= goal
-                    if q % check_every == check_every - 1 and (bits >> C) & 1:
+                    if q % every == every - 1 and (bits >> C) & 1:
                         full += sum(C - x + 1 for x in ws[q + 1:])
                         break
         placed |= (ref.assignment == j[:, None]) & live[:, None]

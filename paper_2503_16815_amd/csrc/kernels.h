@@ -73,7 +73,7 @@ struct SeqBitsPlan {
     int32_t variant;         // index into the compiled words-per-lane table
     int32_t words_per_lane;  // K: capacities up to 2048 K - 1
     int32_t row_words;       // 64 K
-    int32_t first_ints;      // LDS ints of the 16-bit per-cell array
+    int32_t first_ints;      // LDS ints of the per-cell array (8-bit cells for at most 255 items, else 16-bit)
     int32_t n_pad;           // entries of the stage's item list in LDS
     int32_t lds_bytes;       // dynamic LDS per workgroup (= per instance)
 };

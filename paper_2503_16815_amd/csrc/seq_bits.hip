@@ -57,8 +57,8 @@ __device__ __forceinline__ int bits_wave_max(int x) { return bits_wave_reduce(x,
 // every reachable t in 1 .. C (when the sweep ends early: for every t reached so far).
 // The sweep ends as soon as C itself is reachable: the value is final, and the walk from C
 // only follows sums that were reached by earlier items.
-template <int NB>
-__device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const int32_t *lw, int lane, int nact, int C)
+template <int NB, class FirstT>
+__device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, const int32_t *lw, int lane, int nact, int C)
 {
     uint32_t own[NB], need[NB];  // need: the cells of the word that are <= C
 #pragma unroll
@@ -106,17 +106,28 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const 
             if (__builtin_amdgcn_ballot_w64(any != 0) != 0ull) {
 #pragma unroll
                 for (int k = 0; k < NB; ++k) {
-                    if (__builtin_amdgcn_ballot_w64(fresh[k] != 0) == 0ull) continue;  // nobody reached anything here
+                    unsigned long long who = __builtin_amdgcn_ballot_w64(fresh[k] != 0);
+                    if (who == 0ull) continue;  // nobody reached anything in this slot
                     set[k * 64 + lane] = own[k];
-                    uint32_t f = fresh[k];
-                    while (f) {  // item q is the first to reach these sums
-                        const int b = __builtin_ctz(f);
-                        f &= f - 1;
-                        first[(k * 64 + lane) * 32 + b] = (uint16_t)q;
-                    }
+                    // Item q is the first to reach these sums.  Few words hold fresh bits (an item
+                    // mostly extends the set by a run of sums at its top), so the words are taken
+                    // one pair at a time and their bits are spread over the lanes: lane b of
+                    // either half of the wavefront marks cell b of its half's word.
+                    do {
+                        const int l0 = __builtin_ctzll(who);
+                        who &= who - 1;
+                        int l1 = l0;  // (an odd count: both halves mark the same word)
+                        if (who != 0ull) {
+                            l1 = __builtin_ctzll(who);
+                            who &= who - 1;
+                        }
+                        const uint32_t bits0 = __builtin_amdgcn_readlane(fresh[k], l0);
+                        const uint32_t bits1 = __builtin_amdgcn_readlane(fresh[k], l1);
+                        const int l = lane < 32 ? l0 : l1;
+                        const uint32_t bits = lane < 32 ? bits0 : bits1;
+                        if ((bits >> (lane & 31)) & 1u) first[(k * 64 + l) * 32 + (lane & 31)] = (FirstT)q;
+                    } while (who != 0ull);
                 }
-                // the capacity itself has become reachable: the value is final and the walk
-                // back from C only meets sums that were reached earlier
                 // (C's word is in the last slot: NB is the smallest count that covers it)
                 const bool reached = lane == c_lane && (fresh[NB - 1] & c_bit) != 0;
                 wave_lds_sync();  // the new set is visible
@@ -133,48 +144,89 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, uint16_t *first, const 
     return bits_wave_max(best);
 }
 
-template <int N>
-__device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, uint16_t *first, const int32_t *lw, int lane,
+template <int N, class FirstT>
+__device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, FirstT *first, const int32_t *lw, int lane,
                                                    int nact, int C)
 {
     if (nb == N) {
-        return sweep_bits<N>(set, first, lw, lane, nact, C);
+        return sweep_bits<N, FirstT>(set, first, lw, lane, nact, C);
     } else if constexpr (N > 1) {
-        return sweep_bits_dispatch<N - 1>(nb, set, first, lw, lane, nact, C);
+        return sweep_bits_dispatch<N - 1, FirstT>(nb, set, first, lw, lane, nact, C);
     }
     return 0;
 }
 
 // K: words per lane the variant is compiled for (capacities up to 2048 K - 1).
 // LDS: [guard zeros][set: row_words][first: first_ints ints][lw: n_pad][li: n_pad]
-template <int K>
+// FirstT: the cell type of first[] (an 8-bit cell serves lists of at most 255 items and
+// halves the instance's LDS, so that twice as many instances share a compute unit).
+template <int K, class FirstT>
 __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words, int first_ints, int n_pad)
 {
     extern __shared__ __align__(16) int32_t lds_bits[];
     const int inst = blockIdx.x, lane = threadIdx.x;
     uint32_t *set = reinterpret_cast<uint32_t *>(lds_bits) + kBitsGuardWords;
-    uint16_t *first = reinterpret_cast<uint16_t *>(set + row_words);
+    FirstT *first = reinterpret_cast<FirstT *>(set + row_words);
     int32_t *lw = reinterpret_cast<int32_t *>(set + row_words) + first_ints;
     int32_t *li = lw + n_pad;
 
-    int status = check_instance(a, inst, false);
-    const int n = a.n_items[inst], m = a.n_knapsacks[inst];
+    // Everything whose address follows from the instance number alone is fetched at once: the
+    // kernel's entry is one memory round trip (two for lists of more than 64 items).
     const int32_t *__restrict__ W = a.weights + (size_t)inst * a.item_stride;
     const int32_t *__restrict__ V = a.values + (size_t)inst * a.item_stride;
-    if (status == DEFT_OK) {  // the handle's promise: every value equals its weight
+    const int32_t *cap = a.capacities + (size_t)inst * a.knap_stride;
+    const int32_t *ord = a.fill_order ? a.fill_order + (size_t)inst * a.knap_stride : nullptr;
+    const int w_first = lane < a.item_stride ? W[lane] : 0;
+    const int v_first = lane < a.item_stride ? V[lane] : 0;
+    const int cap_raw = lane < a.knap_stride ? cap[lane] : 0;
+    const int ord_raw = ord && lane < a.knap_stride ? ord[lane] : lane;
+    const int n = a.n_items[inst], m = a.n_knapsacks[inst];
+
+    // Input checks, in the order every kernel of the library reports them: invalid data, the
+    // handle's limits, overflow of the value sum; then the handle's promise that every value
+    // equals its weight.
+    int status = DEFT_OK;
+    {
+        uint32_t flags = 0;
+        unsigned long long vs = 0;
         bool differs = false;
-        for (int i = lane; i < n; i += 64) differs = differs || V[i] != W[i];
-        if (__builtin_amdgcn_ballot_w64(differs) != 0ull) status = DEFT_ERR_INVALID_ARG;
+        if (n < 0 || n > a.item_stride || m < 0 || m > a.knap_stride) {
+            flags = 1;
+        } else {
+            for (int i0 = 0; i0 < n; i0 += 64) {
+                const int i = i0 + lane;
+                if (i < n) {
+                    const int w = i0 == 0 ? w_first : W[i], v = i0 == 0 ? v_first : V[i];
+                    if (w < 1 || v < 0) flags |= 1; else vs += (unsigned)v;
+                    differs = differs || v != w;
+                }
+            }
+            unsigned long long seen = 0;
+            if (lane < m) {
+                if (cap_raw < 0) flags |= 1; else if (cap_raw > a.max_capacity) flags |= 2;
+                if (ord_raw < 0 || ord_raw >= m) flags |= 1; else seen = 1ull << ord_raw;
+            }
+            // a fill order names every knapsack once: m entries in range with m distinct values
+            auto bit_or = [](int x, int y) { return x | y; };
+            const int seen_lo = bits_wave_reduce((int)(uint32_t)seen, bit_or);
+            const int seen_hi = bits_wave_reduce((int)(uint32_t)(seen >> 32), bit_or);
+            if ((int)(__popc((uint32_t)seen_lo) + __popc((uint32_t)seen_hi)) != m) flags |= 1;
+        }
+        // (a lane adds at most 64 values below 2^31: three 16-bit pieces keep the sums in range)
+        const unsigned long long total_v = (unsigned long long)(unsigned)bits_wave_sum((int)(vs & 0xffffu)) +
+                                           ((unsigned long long)(unsigned)bits_wave_sum((int)((vs >> 16) & 0xffffu)) << 16) +
+                                           ((unsigned long long)(unsigned)bits_wave_sum((int)(vs >> 32)) << 32);
+        if (__builtin_amdgcn_ballot_w64((flags & 1) != 0) != 0ull) status = DEFT_ERR_INVALID_ARG;
+        else if (__builtin_amdgcn_ballot_w64((flags & 2) != 0) != 0ull) status = DEFT_ERR_LIMIT;
+        else if (total_v >= (1ull << 31)) status = DEFT_ERR_OVERFLOW;
+        else if (__builtin_amdgcn_ballot_w64(differs) != 0ull) status = DEFT_ERR_INVALID_ARG;
     }
     clear_outputs(a, inst, status);
     if (status != DEFT_OK) return;
 
     for (int i = lane; i < kBitsGuardWords; i += 64) lds_bits[i] = 0;
-    const int32_t *cap = a.capacities + (size_t)inst * a.knap_stride;
-    const int32_t *ord = a.fill_order ? a.fill_order + (size_t)inst * a.knap_stride : nullptr;
-    const int cap_l = lane < m ? cap[lane] : 0;
-    const int ord_l = ord && lane < m ? ord[lane] : lane;
-    const int w_first = lane < n ? W[lane] : 0;
+    const int cap_l = lane < m ? cap_raw : 0;
+    const int ord_l = lane < m ? ord_raw : lane;
     int32_t *out_asg = a.assignment + (size_t)inst * a.item_stride;
     int32_t *out_kv = a.knap_value + (size_t)inst * a.knap_stride;
     int32_t *out_kl = a.knap_load + (size_t)inst * a.knap_stride;
@@ -224,7 +276,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
             value = offered_weight;
         } else {
             const int nb = (C / 32 + 64) / 64;  // words per lane covering cells 0 .. C
-            value = sweep_bits_dispatch<K>(nb, set, first, lw, lane, cnt, C);
+            value = sweep_bits_dispatch<K, FirstT>(nb, set, first, lw, lane, cnt, C);
             // the walk: every lane follows the same chain; the lane that owns an item's bit marks it
             int t = value;
             int guard = cnt;  // (a chain is never longer than the list)
@@ -247,36 +299,46 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
     if (lane == 0) a.total_value[inst] = total;
 }
 
-struct BitsVariant {
-    int words;  // per lane
-    const void *fn;
-};
-#define DEFT_BITS_VARIANT(K) { K, reinterpret_cast<const void *>(&seq_bits_kernel<K>) }
-const BitsVariant kBitsVariants[] = {
-    DEFT_BITS_VARIANT(2),   // capacity <= 4095
-    DEFT_BITS_VARIANT(5),   // <= 10239
-    DEFT_BITS_VARIANT(7),   // <= 14335
-    DEFT_BITS_VARIANT(10),  // <= 20479
-    DEFT_BITS_VARIANT(13),  // <= 26623
-    DEFT_BITS_VARIANT(19),  // <= 38911
-    DEFT_BITS_VARIANT(32),  // <= 65535
-};
-#undef DEFT_BITS_VARIANT
-constexpr int kNumBitsVariants = 7;
+// Compiled words-per-lane counts (capacities up to 2048 K - 1), each with 16-bit and 8-bit cells.
+constexpr int kBitsWords[] = {2, 5, 7, 10, 13, 19, 32};
+constexpr int kNumBitsWords = 7;
+
+template <class F>
+auto with_bits_kernel(int variant, F &&f)
+{
+    switch (variant) {
+    case 0: return f(&seq_bits_kernel<2, uint16_t>);
+    case 1: return f(&seq_bits_kernel<2, uint8_t>);
+    case 2: return f(&seq_bits_kernel<5, uint16_t>);
+    case 3: return f(&seq_bits_kernel<5, uint8_t>);
+    case 4: return f(&seq_bits_kernel<7, uint16_t>);
+    case 5: return f(&seq_bits_kernel<7, uint8_t>);
+    case 6: return f(&seq_bits_kernel<10, uint16_t>);
+    case 7: return f(&seq_bits_kernel<10, uint8_t>);
+    case 8: return f(&seq_bits_kernel<13, uint16_t>);
+    case 9: return f(&seq_bits_kernel<13, uint8_t>);
+    case 10: return f(&seq_bits_kernel<19, uint16_t>);
+    case 11: return f(&seq_bits_kernel<19, uint8_t>);
+    case 12: return f(&seq_bits_kernel<32, uint16_t>);
+    case 13: return f(&seq_bits_kernel<32, uint8_t>);
+    default: return f(static_cast<void (*)(BatchArgs, int, int, int)>(nullptr));
+    }
+}
 
 }  // namespace
 
 bool seq_bits_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_wg_bytes, SeqBitsPlan *plan)
 {
     const int32_t n_pad = (max_items + 7) & ~7;
-    for (int i = 0; i < kNumBitsVariants; ++i) {
-        const int K = kBitsVariants[i].words;
+    const int cell_bytes = max_items <= 255 ? 1 : 2;  // a cell holds a position in the stage's list
+    for (int i = 0; i < kNumBitsWords; ++i) {
+        const int K = kBitsWords[i];
         if ((int64_t)max_capacity > (int64_t)K * 2048 - 1) continue;
         const int64_t row_words = (int64_t)K * 64;
-        const int64_t first_ints = ((int64_t)max_capacity + 2 + 1) / 2;  // 16 bits per cell 0 .. max_capacity
+        const int64_t first_ints = (((int64_t)max_capacity + 1) * cell_bytes + 3) / 4;  // cells 0 .. max_capacity
         const int64_t lds = (kBitsGuardWords + row_words + first_ints + 2 * (int64_t)n_pad) * 4;
         if (lds > lds_per_wg_bytes - 256) return false;
-        plan->variant = i;
+        plan->variant = 2 * i + (cell_bytes == 1 ? 1 : 0);
         plan->words_per_lane = K;
         plan->row_words = (int32_t)row_words;
         plan->first_ints = (int32_t)first_ints;
@@ -290,26 +352,22 @@ bool seq_bits_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_wg_b
 hipError_t seq_bits_prepare(const SeqBitsPlan &plan)
 {
     // the attribute belongs to the kernel, not to the handle: the most any handle may ask for
-    // (a compute unit's LDS less the few static words of the input checks)
-    return hipFuncSetAttribute(kBitsVariants[plan.variant].fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               160 * 1024 - 256);
+    // (a compute unit's LDS less a small allowance)
+    return with_bits_kernel(plan.variant, [](auto fn) {
+        if (!fn) return hipErrorInvalidValue;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   160 * 1024 - 256);
+    });
 }
 
 hipError_t seq_bits_launch(const SeqBitsPlan &p, const BatchArgs &a, hipStream_t st)
 {
-    const dim3 grid((unsigned)a.batch), block(64);
-    const size_t lds = (size_t)p.lds_bytes;
-    switch (p.variant) {
-    case 0: hipLaunchKernelGGL(seq_bits_kernel<2>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    case 1: hipLaunchKernelGGL(seq_bits_kernel<5>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    case 2: hipLaunchKernelGGL(seq_bits_kernel<7>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    case 3: hipLaunchKernelGGL(seq_bits_kernel<10>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    case 4: hipLaunchKernelGGL(seq_bits_kernel<13>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    case 5: hipLaunchKernelGGL(seq_bits_kernel<19>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    case 6: hipLaunchKernelGGL(seq_bits_kernel<32>, grid, block, lds, st, a, p.row_words, p.first_ints, p.n_pad); break;
-    default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    return with_bits_kernel(p.variant, [&](auto fn) {
+        if (!fn) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(fn, dim3((unsigned)a.batch), dim3(64), (size_t)p.lds_bytes, st, a, p.row_words, p.first_ints,
+                           p.n_pad);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace deft

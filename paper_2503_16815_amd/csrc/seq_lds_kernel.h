@@ -249,7 +249,7 @@ constexpr int kSecondBase = 60416;
 // reached: the kept value row[C] - C is 0) the stage's value is final, and no later item is
 // taken at C (a take needs a strict improvement), so the walk back from C passes every later
 // item and only ever reads keep rows up to here: the sweep ends there.  Checked after every
-// eighth item, between two items: the wavefront that owns cell C stores the check's tag in
+// eighth item (every second one of a list of at most 64), between two items: the wavefront that owns cell C stores the check's tag in
 // `unfinished` while the cell is short of C, and after a barrier everyone looks at it.
 // Returns the number of items swept (the keep rows beyond were never written).
 template <int T, int NB, int G, int NW, bool ADDTID, bool VEQW, bool REC, bool SKIP_UNCHANGED>
@@ -258,7 +258,7 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
                                             BestLevel &best, int C, int32_t *unfinished)
 {
     constexpr bool STOP_WHEN_FULL = VEQW && !REC;
-    constexpr int kCheckEvery = 8;
+    const int check_mask = nact <= 64 ? 1 : 7;  // short lists: after every second item, else every eighth
     // What follows from the lane index alone (a slot's initial value and LDS address, for every
     // slot count instantiated) is cheap to compute here; left visible to the compiler it is all
     // computed at kernel entry instead, parked in scratch memory and fetched back per stage.
@@ -413,7 +413,7 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
         if constexpr (!STOP_WHEN_FULL) {
             return false;
         } else {
-            if ((q % kCheckEvery) != kCheckEvery - 1) return false;
+            if ((q & check_mask) != check_mask) return false;
             int any = 0;
 #pragma unroll
             for (int k = NB - G; k < NB; ++k)  // cell C sits in one of the last G slots
@@ -538,7 +538,7 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
                                                 int32_t *unfinished)
 {
     constexpr bool STOP_WHEN_FULL = !REC;
-    constexpr int kCheckEvery = 8;
+    const int check_mask = nact <= 64 ? 1 : 7;  // short lists: after every second item, else every eighth
     static_assert(NP >= 1 && NP <= 16, "the take bits of a lane fit one keep word");
     asm volatile("" : "+v"(tid));  // (as in sweep_stage: keeps the per-lane constants out of kernel entry)
     const int wave_first = uniform(tid & ~63);
@@ -658,7 +658,7 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
         if constexpr (!STOP_WHEN_FULL) {
             return false;
         } else {
-            if ((q % kCheckEvery) != kCheckEvery - 1) return false;
+            if ((q & check_mask) != check_mask) return false;
             // cell C sits in the top pair
             constexpr int j = NP - 1;
             const uint32_t any = own[j] & ((2 * j * T + tid == C ? 0xffffu : 0u) | ((2 * j + 1) * T + tid == C ? 0xffff0000u : 0u));
@@ -1183,7 +1183,7 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         };
         if (!caps_sweep) {
             if (serial) {
-                const int L = sl;
+                    const int L = sl;
                 unsigned long long chosen;
                 const int c = walk(L, walk_from, walk_cap, chosen);
                 placed |= chosen;

@@ -15,7 +15,8 @@ def test_stage_where_everything_fits_is_settled(oracle):
     settled, full = bench.cells_not_swept(kb, r, True)
     left = [w for w, a in zip(kb.weights[0], r.assignment[0]) if a != 0]
     assert sum(left) <= 20
-    assert settled == sum(20 - w + 1 for w in left) and full == 0
+    # window 1: 6 + 4 reaches the capacity with the third item, the check after the fourth sees it
+    assert settled == sum(20 - w + 1 for w in left) and full == 3 * (10 - 2 + 1)
     assert int(r.touched_cells[0]) == sum(10 - w + 1 for w in kb.weights[0]) + settled
 
 
@@ -27,16 +28,20 @@ def test_few_offered_items_count_as_settled_on_the_lds_path_only(oracle):
 
 
 def test_items_after_the_capacity_is_reached(oracle):
-    """Twenty items of weight 1 and capacity 7: at the first check (after the 8th item) the sum
-    7 can be reached, so items 9..20 are never swept: 12 x (7 - 1 + 1) cells.  With a check
-    after every item (the bit-set kernel) the sweep ends after the 7th."""
+    """Twenty items of weight 1 and capacity 7 (a short list: checked after every second item):
+    the sum 7 can be reached after the 7th item, the check after the 8th sees it, so items
+    9..20 are never swept: 12 x (7 - 1 + 1) cells.  With a check after every item (the bit-set
+    kernel) the sweep ends after the 7th."""
     kb = make_seq([[1] * 20], [[1] * 20], [[7]])
     r = oracle.solve_batch(kb)
     assert bench.cells_not_swept(kb, r, True) == (0, 12 * 7)
     assert bench.cells_not_swept(kb, r, True, check_every=1) == (0, 13 * 7)
     # weight 2, capacity 8: the odd sums are never reached, the capacity is after four items
     k2 = make_seq([[2] * 20], [[2] * 20], [[8]])
-    assert bench.cells_not_swept(k2, oracle.solve_batch(k2), True) == (0, 12 * 7)
+    assert bench.cells_not_swept(k2, oracle.solve_batch(k2), True) == (0, 16 * 7)
+    # a list of more than 64 items is checked after every eighth
+    k4 = make_seq([[2] * 70], [[2] * 70], [[8]])
+    assert bench.cells_not_swept(k4, oracle.solve_batch(k4), True) == (0, 62 * 7)
     # capacity 9: the best is 8, the capacity itself is never reached
     k3 = make_seq([[2] * 20], [[2] * 20], [[9]])
     assert bench.cells_not_swept(k3, oracle.solve_batch(k3), True) == (0, 0)
