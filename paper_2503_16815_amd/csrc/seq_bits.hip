@@ -57,8 +57,12 @@ __device__ __forceinline__ int bits_wave_max(int x) { return bits_wave_reduce(x,
 // every reachable t in 1 .. C (when the sweep ends early: for every t reached so far).
 // The sweep ends as soon as C itself is reachable: the value is final, and the walk from C
 // only follows sums that were reached by earlier items.
-template <int NB, class FirstT>
-__device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, const int32_t *lw, int lane, int nact, int C)
+// SNAP (8-bit cells, lists of 256 .. 511 items): a cell keeps the low eight bits of the
+// position, and `snap` keeps the set as it stood after the item at position 255: a sum in it
+// was first reached by a position below 256, any other by 256 + the cell.
+template <int NB, class FirstT, bool SNAP>
+__device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, uint32_t *snap, const int32_t *lw, int lane,
+                                          int nact, int C)
 {
     uint32_t own[NB], need[NB];  // need: the cells of the word that are <= C
 #pragma unroll
@@ -67,6 +71,7 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, const in
         need[k] = cell0 + 31 <= C ? 0xffffffffu : cell0 > C ? 0u : (1u << (C - cell0 + 1)) - 1u;
         own[k] = (k == 0 && lane == 0) ? 1u : 0u;  // the empty sum
         set[k * 64 + lane] = own[k];
+        if constexpr (SNAP) snap[k * 64 + lane] = 0xffffffffu;  // until position 255 has been swept: everything
     }
     wave_lds_sync();
     const int c_lane = (C >> 5) & 63;
@@ -133,6 +138,12 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, const in
                 wave_lds_sync();  // the new set is visible
                 if (__builtin_amdgcn_ballot_w64(reached) != 0ull) return C;
             }
+            if constexpr (SNAP) {
+                if (q == 255) {
+#pragma unroll
+                    for (int k = 0; k < NB; ++k) snap[k * 64 + lane] = own[k];
+                }
+            }
         }
     }
     int best = 0;
@@ -144,23 +155,24 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, const in
     return bits_wave_max(best);
 }
 
-template <int N, class FirstT>
-__device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, FirstT *first, const int32_t *lw, int lane,
-                                                   int nact, int C)
+template <int N, class FirstT, bool SNAP>
+__device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, FirstT *first, uint32_t *snap, const int32_t *lw,
+                                                   int lane, int nact, int C)
 {
     if (nb == N) {
-        return sweep_bits<N, FirstT>(set, first, lw, lane, nact, C);
+        return sweep_bits<N, FirstT, SNAP>(set, first, snap, lw, lane, nact, C);
     } else if constexpr (N > 1) {
-        return sweep_bits_dispatch<N - 1, FirstT>(nb, set, first, lw, lane, nact, C);
+        return sweep_bits_dispatch<N - 1, FirstT, SNAP>(nb, set, first, snap, lw, lane, nact, C);
     }
     return 0;
 }
 
 // K: words per lane the variant is compiled for (capacities up to 2048 K - 1).
-// LDS: [guard zeros][set: row_words][first: first_ints ints][lw: n_pad][li: n_pad]
-// FirstT: the cell type of first[] (an 8-bit cell serves lists of at most 255 items and
-// halves the instance's LDS, so that twice as many instances share a compute unit).
-template <int K, class FirstT>
+// LDS: [guard zeros][set: row_words][first: first_ints ints][lw: n_pad][li: n_pad][snap: row_words, if SNAP]
+// FirstT: the cell type of first[].  An 8-bit cell serves lists of at most 255 items, with
+// SNAP (one snapshot of the set) of at most 511, and halves the instance's LDS, so that
+// about twice as many instances share a compute unit.
+template <int K, class FirstT, bool SNAP>
 __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words, int first_ints, int n_pad)
 {
     extern __shared__ __align__(16) int32_t lds_bits[];
@@ -169,6 +181,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
     FirstT *first = reinterpret_cast<FirstT *>(set + row_words);
     int32_t *lw = reinterpret_cast<int32_t *>(set + row_words) + first_ints;
     int32_t *li = lw + n_pad;
+    uint32_t *snap = reinterpret_cast<uint32_t *>(li + n_pad);
 
     // Everything whose address follows from the instance number alone is fetched at once: the
     // kernel's entry is one memory round trip (two for lists of more than 64 items).
@@ -276,12 +289,13 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
             value = offered_weight;
         } else {
             const int nb = (C / 32 + 64) / 64;  // words per lane covering cells 0 .. C
-            value = sweep_bits_dispatch<K, FirstT>(nb, set, first, lw, lane, cnt, C);
+            value = sweep_bits_dispatch<K, FirstT, SNAP>(nb, set, first, snap, lw, lane, cnt, C);
             // the walk: every lane follows the same chain; the lane that owns an item's bit marks it
             int t = value;
             int guard = cnt;  // (a chain is never longer than the list)
             while (t > 0 && guard-- > 0) {
-                const int q = first[t];
+                int q = first[t];
+                if constexpr (SNAP) q += ((snap[t >> 5] >> (t & 31)) & 1u) ? 0 : 256;
                 const int w = lw[min(q, cnt - 1)], i = li[min(q, cnt - 1)];
                 if (lane == (i & 63)) placed |= 1ull << (i >> 6);
                 if (lane == 0) out_asg[i] = j;
@@ -303,24 +317,27 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
 constexpr int kBitsWords[] = {2, 5, 7, 10, 13, 19, 32};
 constexpr int kNumBitsWords = 7;
 
+// mode: 0 = 16-bit cells, 1 = 8-bit cells, 2 = 8-bit cells and the snapshot
+template <int K, class F>
+auto with_bits_mode(int mode, F &&f)
+{
+    switch (mode) {
+    case 0: return f(&seq_bits_kernel<K, uint16_t, false>);
+    case 1: return f(&seq_bits_kernel<K, uint8_t, false>);
+    default: return f(&seq_bits_kernel<K, uint8_t, true>);
+    }
+}
 template <class F>
 auto with_bits_kernel(int variant, F &&f)
 {
-    switch (variant) {
-    case 0: return f(&seq_bits_kernel<2, uint16_t>);
-    case 1: return f(&seq_bits_kernel<2, uint8_t>);
-    case 2: return f(&seq_bits_kernel<5, uint16_t>);
-    case 3: return f(&seq_bits_kernel<5, uint8_t>);
-    case 4: return f(&seq_bits_kernel<7, uint16_t>);
-    case 5: return f(&seq_bits_kernel<7, uint8_t>);
-    case 6: return f(&seq_bits_kernel<10, uint16_t>);
-    case 7: return f(&seq_bits_kernel<10, uint8_t>);
-    case 8: return f(&seq_bits_kernel<13, uint16_t>);
-    case 9: return f(&seq_bits_kernel<13, uint8_t>);
-    case 10: return f(&seq_bits_kernel<19, uint16_t>);
-    case 11: return f(&seq_bits_kernel<19, uint8_t>);
-    case 12: return f(&seq_bits_kernel<32, uint16_t>);
-    case 13: return f(&seq_bits_kernel<32, uint8_t>);
+    switch (variant / 3) {
+    case 0: return with_bits_mode<2>(variant % 3, f);
+    case 1: return with_bits_mode<5>(variant % 3, f);
+    case 2: return with_bits_mode<7>(variant % 3, f);
+    case 3: return with_bits_mode<10>(variant % 3, f);
+    case 4: return with_bits_mode<13>(variant % 3, f);
+    case 5: return with_bits_mode<19>(variant % 3, f);
+    case 6: return with_bits_mode<32>(variant % 3, f);
     default: return f(static_cast<void (*)(BatchArgs, int, int, int)>(nullptr));
     }
 }
@@ -330,15 +347,17 @@ auto with_bits_kernel(int variant, F &&f)
 bool seq_bits_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_wg_bytes, SeqBitsPlan *plan)
 {
     const int32_t n_pad = (max_items + 7) & ~7;
-    const int cell_bytes = max_items <= 255 ? 1 : 2;  // a cell holds a position in the stage's list
+    // a cell holds a position in the stage's list
+    const int mode = max_items <= 255 ? 1 : max_items <= 511 ? 2 : 0;
+    const int cell_bytes = mode == 0 ? 2 : 1;
     for (int i = 0; i < kNumBitsWords; ++i) {
         const int K = kBitsWords[i];
         if ((int64_t)max_capacity > (int64_t)K * 2048 - 1) continue;
         const int64_t row_words = (int64_t)K * 64;
         const int64_t first_ints = (((int64_t)max_capacity + 1) * cell_bytes + 3) / 4;  // cells 0 .. max_capacity
-        const int64_t lds = (kBitsGuardWords + row_words + first_ints + 2 * (int64_t)n_pad) * 4;
+        const int64_t lds = (kBitsGuardWords + row_words + first_ints + 2 * (int64_t)n_pad + (mode == 2 ? row_words : 0)) * 4;
         if (lds > lds_per_wg_bytes - 256) return false;
-        plan->variant = 2 * i + (cell_bytes == 1 ? 1 : 0);
+        plan->variant = 3 * i + mode;
         plan->words_per_lane = K;
         plan->row_words = (int32_t)row_words;
         plan->first_ints = (int32_t)first_ints;

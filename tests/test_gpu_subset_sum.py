@@ -21,18 +21,23 @@ VARIANTS = [(700, 1023), (4000, 4095), (10000, 10239), (14000, 14335), (20000, 2
 def test_random_ragged_every_variant(binding, oracle, cap_hi, max_capacity):
     """Ragged n and m, random fill order, capacities from 0 up; light items, items of a few
     hundred to a few thousand cells (word shifts with every bit offset) and items heavier than
-    the guard zone below the set (clamped reads).  Each with both cell widths of first[]
-    (a handle for at most 255 items gets 8-bit cells)."""
+    the guard zone below the set (clamped reads).  With each layout of first[]: a handle for
+    at most 255 items gets 8-bit cells, for at most 511 8-bit cells and a snapshot of the set,
+    beyond that 16-bit cells."""
     for seed, n_max, w_hi in ((1, 60, max(9, cap_hi // 40)), (2, 45, max(20, cap_hi // 6)), (3, 30, cap_hi)):
         kb = W.random_sequential(21000 + 7 * cap_hi + seed, batch=37, n_max=n_max, m_max=4, w_hi=w_hi, v_hi=9,
                                  cap_hi=cap_hi, ties=True)
         run(binding, oracle, kb, max_capacity=max_capacity, flags=FLAG)          # 8-bit cells of first[]
-        if seed != 3:
-            run(binding, oracle, kb, max_capacity=max_capacity, max_items=300, flags=FLAG)   # 16-bit cells
+        if seed == 1:
+            run(binding, oracle, kb, max_capacity=max_capacity, max_items=300, flags=FLAG)   # 8-bit cells + snapshot
+        if seed == 2:
+            run(binding, oracle, kb, max_capacity=max_capacity, max_items=600, flags=FLAG)   # 16-bit cells
 
 
 @pytest.mark.parametrize("max_capacity,n_max,w_hi,batch", [
     (4095, 250, 60, 40), (20479, 255, 300, 24), (38911, 255, 600, 16),     # lists short enough for 8-bit cells
+    (4095, 511, 30, 40), (10239, 500, 70, 28), (14335, 511, 80, 24), (20479, 511, 140, 24),   # 8-bit cells + snapshot
+    (26623, 480, 200, 16), (38911, 511, 260, 16), (65535, 500, 450, 8),
     (4095, 600, 30, 40), (10239, 1450, 30, 28), (14335, 1890, 30, 24), (26623, 3000, 39, 16), (65535, 2000, 140, 8),
 ])
 def test_rows_that_fill_early_every_variant(binding, oracle, max_capacity, n_max, w_hi, batch):
