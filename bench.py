@@ -193,7 +193,11 @@ def run_schedule(args):
     sweep_s = float(prof.sweep_ms) * 1e-3
     launches = int(prof.sweep_launches)
     swept_step = int(prof.swept_cell_updates) // args.steps   # counted by the library: what the sweeps evaluated
-    bytes_per_cell, ops_per_cell = (4.0, 1.75) if packed16 else (8.0, 3.0)
+    bitset = bool(getattr(args, "subset_sum", False))
+    # (a DEFT_FLAG_SUBSET_SUM handle: forward stages on the bit-set kernels, whose cell-updates the
+    # library does not count, backward stages on rows of 16-bit cells - value and fraction then
+    # cover the backward stages' cells over the time of all launches: lower bounds)
+    bytes_per_cell, ops_per_cell = (4.0, 1.75) if packed16 or bitset else (8.0, 3.0)
     achieved = swept_step * args.steps * bytes_per_cell / sweep_s / 1e9 if sweep_s > 0 else 0.0
     ops = swept_step * args.steps * ops_per_cell / sweep_s if sweep_s > 0 else 0.0
     upd = got["update_k"]
@@ -203,7 +207,9 @@ def run_schedule(args):
         vs_baseline=None, dtype="int32", data="synthetic",
         config=dict(workload=f"task-queue simulation (Cases 1-4), ResNet-101-shaped: {sb.batch} candidates x "
                              f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%"
-                             + (" [rows of 16-bit cells]" if packed16 else ""),
+                             + (" [rows of 16-bit cells]" if packed16 else "")
+                             + (" [forward stages on bit-set rows, backward stages on rows of 16-bit cells; only the "
+                                "backward stages' cell-updates are counted]" if bitset else ""),
                     value_counts="cell-updates the sweeps evaluate (counted by the library)",
                     candidates_per_step=sb.batch, iterations=sb.iterations,
                     one_sweep_cell_updates_per_step_estimated_from_sample=cells_step,
@@ -563,7 +569,8 @@ def main() -> int:
                             # (bit-set rows, one wavefront per instance)
                             ("resnet101_bitset", dict(workload="resnet101", subset_sum=True)),
                             ("resnet101_one_call_per_k_bitset", dict(workload="resnet101", per_k_calls=True, subset_sum=True)),
-                            ("vgg19_bitset", dict(workload="vgg19", subset_sum=True))):
+                            ("vgg19_bitset", dict(workload="vgg19", subset_sum=True)),
+                            ("schedule_bitset", dict(workload="schedule", subset_sum=True))):
             sub = argparse.Namespace(**vars(args))
             sub.workload, sub.no_cpu = name, args.no_cpu or "rows16" in name or "bitset" in name
             sub.steps, sub.warmup, sub.single_thread = max(3, min(args.steps, 20)), 3, False

@@ -91,7 +91,10 @@ typedef struct {
  * of the set (32 cells per instruction), and the canonical selection - the one the exact DP
  * walks back, smallest mask among the optima - is read off a per-cell record of the first
  * item that reached each sum.  One wavefront per instance, everything in LDS, no scratch
- * memory.  Results are bit-identical to those of a handle without flags.  The other
+ * memory.  max_items decides the width of that record and with it how many instances share
+ * a compute unit: 8-bit cells up to 255 items, 8-bit cells plus one snapshot of the set up
+ * to 511, 16-bit cells beyond (create returns DEFT_ERR_LIMIT when set, record and item list
+ * exceed a compute unit's LDS).  Results are bit-identical to those of a handle without flags.  The other
  * sequential-layout modes run as under DEFT_FLAG_VALUES_ARE_WEIGHTS when max_capacity <=
  * 26623 and on the 32-bit rows above that.  deft_knapsack_get_info reports seq_path 4.
  */

@@ -14,8 +14,9 @@
 //   table and no memory round trips.
 // One wavefront owns an instance (one 64-thread workgroup; no barriers).  Word i of the set
 // (cells 32 i .. 32 i + 31) lives in lane i % 64, register slot i / 64, with a copy in LDS
-// that the shifted operand is read from; first[] (16 bits per cell) and the stage's offered
-// items (weight, index) live in LDS too, so the kernel needs no scratch memory at all.
+// that the shifted operand is read from; first[] (8 or 16 bits per cell, by the handle's
+// longest list) and the stage's offered items (weight, index) live in LDS too, so the kernel
+// needs no scratch memory at all.  A sweep ends as soon as the capacity itself is reachable.
 // Below the set a guard zone of zero words serves the reads of light items; heavier items
 // clamp their word index into it.
 #include <limits.h>
