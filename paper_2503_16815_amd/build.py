@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdeft_knapsack.so")
 PKG = "paper_2503_16815_amd"
-SOURCES = ["seq_lds.hip", "seq_lds_rec.hip", "seq_lds_p16.hip", "seq_lds_p16_rec.hip", "seq_bits.hip", "joint2.hip", "seq_global.hip", "greedy.hip", "schedule_sim.hip", "api.hip", "profile.hip", "static_scratch.hip", "calibrate.hip"]
+SOURCES = ["seq_lds.hip", "seq_lds_rec.hip", "seq_lds_p16.hip", "seq_lds_p16_rec.hip", "seq_bits.hip", "seq_bits_rec.hip", "joint2.hip", "seq_global.hip", "greedy.hip", "schedule_sim.hip", "api.hip", "profile.hip", "static_scratch.hip", "calibrate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wextra", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]

@@ -52,6 +52,7 @@ struct deft_knapsack {
     unsigned long long *lds_swept = nullptr;      // device counter read by get_profile (LDS path)
 
     bool use_bits = false;        // SEQUENTIAL mode runs the bit-set kernels (DEFT_FLAG_SUBSET_SUM)
+    bool use_bits_rec = false;    // and so does RECURSIVE
     SeqBitsPlan bits_plan{};
 
     void *sim_buffers = nullptr;  // task-queue simulation: allocated by its first call
@@ -195,8 +196,12 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
         } else if (seq_bits_prepare(h->bits_plan) != hipSuccess) {
             (void)hipGetLastError();
             st = DEFT_ERR_DEVICE;
+        } else if (h->bits_plan.lds_bytes_rec > 0 && seq_bits_rec_prepare(h->bits_plan) != hipSuccess) {
+            (void)hipGetLastError();
+            st = DEFT_ERR_DEVICE;
         } else {
             h->use_bits = true;
+            h->use_bits_rec = h->bits_plan.lds_bytes_rec > 0;
         }
     }
     if (st == DEFT_OK && want_joint) {
@@ -278,6 +283,10 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         if (prof) prof->sweep_begin(st);
         e = seq_bits_launch(h->bits_plan, a, st);
         if (prof) prof->sweep_end(st);
+    } else if (b->mode == DEFT_MODE_RECURSIVE && h->use_bits_rec) {
+        if (prof) prof->sweep_begin(st);
+        e = seq_bits_rec_launch(h->bits_plan, a, st);
+        if (prof) prof->sweep_end(st);
     } else if (b->mode == DEFT_MODE_SEQUENTIAL || (probing && !on_lds)) {
         if (h->seq_path == 3) {
             e = seq_global_launch(h->glob_plan, a, h->glob_scratch, st, prof, h->glob_streamed);
@@ -345,9 +354,10 @@ extern "C" deft_status_t deft_knapsack_simulate_schedule(deft_knapsack_t *h, con
     Profiler *prof = h->profiling ? &h->prof : nullptr;
     if (prof && !prof->begin(st)) return DEFT_ERR_DEVICE;
     const auto solve = [&](const BatchArgs &x) -> hipError_t {
-        if (h->use_bits && x.mode == DEFT_MODE_SEQUENTIAL) {
+        if ((h->use_bits && x.mode == DEFT_MODE_SEQUENTIAL) || (h->use_bits_rec && x.mode == DEFT_MODE_RECURSIVE)) {
             if (prof) prof->sweep_begin(st);
-            const hipError_t rc = seq_bits_launch(h->bits_plan, x, st);
+            const hipError_t rc = x.mode == DEFT_MODE_SEQUENTIAL ? seq_bits_launch(h->bits_plan, x, st)
+                                                                 : seq_bits_rec_launch(h->bits_plan, x, st);
             if (prof) prof->sweep_end(st);
             return rc;
         }

@@ -76,10 +76,13 @@ struct SeqBitsPlan {
     int32_t first_ints;      // LDS ints of the per-cell array (8-bit cells for at most 255 items, else 16-bit)
     int32_t n_pad;           // entries of the stage's item list in LDS
     int32_t lds_bytes;       // dynamic LDS per workgroup (= per instance)
+    int32_t lds_bytes_rec;   // the same for the Algorithm 1 kernels (0: they do not fit)
 };
 bool seq_bits_plan(int32_t max_capacity, int32_t max_items, int32_t lds_per_wg_bytes, SeqBitsPlan *plan);
 hipError_t seq_bits_prepare(const SeqBitsPlan &plan);
 hipError_t seq_bits_launch(const SeqBitsPlan &plan, const BatchArgs &args, hipStream_t stream);
+hipError_t seq_bits_rec_prepare(const SeqBitsPlan &plan);  // DEFT_MODE_RECURSIVE (seq_bits_rec.hip)
+hipError_t seq_bits_rec_launch(const SeqBitsPlan &plan, const BatchArgs &args, hipStream_t stream);
 
 // ---- per-call HIP-event timing (profile.hip) ---------------------------------
 class Profiler {

@@ -48,6 +48,22 @@ def test_rows_that_fill_early_every_variant(binding, oracle, max_capacity, n_max
     run(binding, oracle, kb, max_capacity=max_capacity, flags=FLAG)
 
 
+@pytest.mark.parametrize("cap_hi,max_capacity", VARIANTS)
+def test_algorithm1_every_variant(binding, oracle, cap_hi, max_capacity):
+    """DEFT_MODE_RECURSIVE on the bit-set kernels: every level's value read off the set before
+    the item that ends it, the walk from the best level; each layout of first[]."""
+    kr = W.random_recursive(23000 + cap_hi, batch=17, n_max=150, w_hi=max(9, cap_hi // 40), v_hi=9, cap_hi=cap_hi,
+                            t_hi=max(1, cap_hi // 200), ties=True)
+    run(binding, oracle, kr, max_capacity=max_capacity, flags=FLAG)
+    run(binding, oracle, kr, max_capacity=max_capacity, max_items=600, flags=FLAG)
+    kh = W.random_recursive(23500 + cap_hi, batch=17, n_max=70, w_hi=max(20, cap_hi // 2), v_hi=9, cap_hi=cap_hi,
+                            t_hi=max(2, cap_hi // 60), ties=True)          # items heavier than most levels
+    run(binding, oracle, kh, max_capacity=max_capacity, max_items=300, flags=FLAG)
+    kl = W.random_recursive(23700 + cap_hi, batch=9, n_max=500, w_hi=max(3, cap_hi // 150), v_hi=9, cap_hi=cap_hi,
+                            t_hi=max(1, cap_hi // 800), ties=True)         # lists beyond position 255: the snapshot
+    run(binding, oracle, kl, max_capacity=max_capacity, flags=FLAG)
+
+
 def test_instances_that_break_the_promise_and_other_faults(binding, oracle):
     kb = W.random_sequential(25001, batch=8, n_max=12, m_max=2, w_hi=9, v_hi=9, cap_hi=30, ragged=False, ties=True)
     ref = oracle.solve_batch(kb, cap_limit=30)
@@ -89,13 +105,13 @@ def test_paper_shapes_at_full_size(binding, oracle):
     run(binding, oracle, W.vgg19_sweep(), flags=FLAG)
     for k in (1, 3):
         run(binding, oracle, W.resnet101_shaped(k=k), flags=FLAG)
-    # the other modes of such a handle (rows of 16-bit cells)
-    run(binding, oracle, W.backward_stage_shaped(batch=64), flags=FLAG)
+    run(binding, oracle, W.backward_stage_shaped(), flags=FLAG)            # Algorithm 1 on the bit-set kernels
+    # the capacity sweep of such a handle runs on rows of 16-bit cells
     run(binding, oracle, W.inflation_sweep_shaped(batch=64), flags=FLAG)
 
 
 def test_task_queues(binding, oracle):
-    """Forward stages on the bit-set kernels, backward stages on rows of 16-bit cells."""
+    """Forward stages on the sequential bit-set kernels, backward stages on Algorithm 1's."""
     import torch
     sb = W.resnet101_schedules(batch=256)
     want = oracle.simulate_batch(sb, nthreads=16)
