@@ -194,10 +194,13 @@ def run_schedule(args):
     launches = int(prof.sweep_launches)
     swept_step = int(prof.swept_cell_updates) // args.steps   # counted by the library: what the sweeps evaluated
     bitset = bool(getattr(args, "subset_sum", False))
-    # (a DEFT_FLAG_SUBSET_SUM handle: forward stages on the bit-set kernels, whose cell-updates the
-    # library does not count, backward stages on rows of 16-bit cells - value and fraction then
-    # cover the backward stages' cells over the time of all launches: lower bounds)
-    bytes_per_cell, ops_per_cell = (4.0, 1.75) if packed16 or bitset else (8.0, 3.0)
+    bytes_per_cell, ops_per_cell = (4.0, 1.75) if packed16 else (8.0, 3.0)
+    if bitset:
+        # every stage on the bit-set kernels, which count nothing: the one-sweep cells the oracle's
+        # sample gives (what the int32 kernels would be offered), at the bit-set kernels' own 12 LDS
+        # bytes and four vector instructions per 32 cells - for the record, the kernels are bound by latency
+        swept_step = int(cells_step)
+        bytes_per_cell, ops_per_cell = 0.375, 0.125
     achieved = swept_step * args.steps * bytes_per_cell / sweep_s / 1e9 if sweep_s > 0 else 0.0
     ops = swept_step * args.steps * ops_per_cell / sweep_s if sweep_s > 0 else 0.0
     upd = got["update_k"]
@@ -208,9 +211,11 @@ def run_schedule(args):
         config=dict(workload=f"task-queue simulation (Cases 1-4), ResNet-101-shaped: {sb.batch} candidates x "
                              f"{sb.n_buckets} buckets x {sb.iterations} iterations, windows 5900 / 11800 +-10%"
                              + (" [rows of 16-bit cells]" if packed16 else "")
-                             + (" [forward stages on bit-set rows, backward stages on rows of 16-bit cells; only the "
-                                "backward stages' cell-updates are counted]" if bitset else ""),
-                    value_counts="cell-updates the sweeps evaluate (counted by the library)",
+                             + (" [bit-set rows; cell-updates as the oracle's sample counts them for one sweep per stage]"
+                                if bitset else ""),
+                    value_counts=("one-sweep cell-updates per stage as estimated from the oracle's sample (the bit-set "
+                                  "kernels count none)" if bitset else
+                                  "cell-updates the sweeps evaluate (counted by the library)"),
                     candidates_per_step=sb.batch, iterations=sb.iterations,
                     one_sweep_cell_updates_per_step_estimated_from_sample=cells_step,
                     cell_updates_swept_per_step=swept_step, seq_path=int(info.seq_path),
@@ -222,7 +227,8 @@ def run_schedule(args):
         profile=dict(total_ms_per_step=float(prof.total_ms) / args.steps,
                      sweep_ms_per_step=float(prof.sweep_ms) / args.steps),
         roofline=dict(bound="lds", achieved=achieved, peak=PEAK_LDS_GBS, unit="GB/s", frac=achieved / PEAK_LDS_GBS,
-                      traffic=None, kernel="seq_lds_kernel", bytes_per_cell=bytes_per_cell, launches=launches,
+                      traffic=None, kernel="seq_bits_kernel" if bitset else "seq_lds_kernel",
+                      bytes_per_cell=bytes_per_cell, launches=launches,
                       avg_launch_ms=float(prof.sweep_ms) / max(launches, 1),
                       swept_cell_updates_per_s=swept_step * args.steps / sweep_s if sweep_s > 0 else 0.0,
                       alu=dict(ops_per_cell=ops_per_cell, peak_lane_ops_per_s=PEAK_INT_LANE_OPS,

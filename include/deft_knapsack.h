@@ -84,8 +84,8 @@ typedef struct {
 
 /*
  * DEFT_FLAG_SUBSET_SUM: the same promise (every value equals its weight; an instance that
- * breaks it gets DEFT_ERR_INVALID_ARG), 1 <= max_capacity <= 65535.  DEFT_MODE_SEQUENTIAL
- * calls (and the forward stages of deft_knapsack_simulate_schedule) then run kernels that
+ * breaks it gets DEFT_ERR_INVALID_ARG), 1 <= max_capacity <= 65535.  DEFT_MODE_SEQUENTIAL and
+ * DEFT_MODE_RECURSIVE calls (and with them deft_knapsack_simulate_schedule) then run kernels that
  * treat a window as the subset-sum problem it is (Sec. III.B, Problem 1 with profit = time):
  * the DP row is the set of reachable sums, one bit per cell, an item is one shift-and-or
  * of the set (32 cells per instruction), and the canonical selection - the one the exact DP
@@ -94,9 +94,12 @@ typedef struct {
  * memory.  max_items decides the width of that record and with it how many instances share
  * a compute unit: 8-bit cells up to 255 items, 8-bit cells plus one snapshot of the set up
  * to 511, 16-bit cells beyond (create returns DEFT_ERR_LIMIT when set, record and item list
- * exceed a compute unit's LDS).  Results are bit-identical to those of a handle without flags.  The other
- * sequential-layout modes run as under DEFT_FLAG_VALUES_ARE_WEIGHTS when max_capacity <=
- * 26623 and on the 32-bit rows above that.  deft_knapsack_get_info reports seq_path 4.
+ * exceed a compute unit's LDS).  Algorithm 1's levels are read off the same set (a level's
+ * answer is the largest reachable sum not above its remaining time, taken before the item
+ * that ends the level is added).  Results are bit-identical to those of a handle without
+ * flags.  DEFT_MODE_CAPACITY_SWEEP (and DEFT_MODE_RECURSIVE where one more item list does not
+ * fit the LDS) runs as under DEFT_FLAG_VALUES_ARE_WEIGHTS when max_capacity <= 26623 and on
+ * the 32-bit rows above that.  deft_knapsack_get_info reports seq_path 4.
  */
 #define DEFT_FLAG_SUBSET_SUM 2u
 
@@ -328,7 +331,8 @@ typedef struct {
     int64_t scratch_bytes;     /* device memory owned by the handle                        */
     int32_t seq_path;          /* 0 none, 1 wavefront-per-instance LDS, 2 workgroup-per-
                                   instance LDS, 3 rows in global memory, 4 bit-set rows
-                                  (DEFT_FLAG_SUBSET_SUM; what SEQUENTIAL calls run on)     */
+                                  (DEFT_FLAG_SUBSET_SUM; what SEQUENTIAL and RECURSIVE
+                                  calls run on)                                            */
     int32_t seq_threads;       /* threads cooperating on one instance                      */
     int32_t seq_cells_per_thread;
     int32_t seq_lds_bytes;     /* LDS per workgroup                                        */
