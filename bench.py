@@ -422,7 +422,7 @@ def run_solver(args):
     # committed rocprofv3 counter passes of this same command (FETCH_SIZE and WRITE_SIZE scaled
     # by a copy of known size); only for the unmodified workload.
     traffic = traffic_source = None
-    kernel = ("seq_bits_kernel" if (seq and info.seq_path == 4 and calls[0].mode in (0, 2)) else
+    kernel = ("seq_bits_kernel" if (seq and info.seq_path == 4 and calls[0].mode in (0, 2, 5)) else
               "seq_lds_kernel" if (seq and info.seq_path in (1, 2, 4)) else ("sg_sweep_all" if seq else "jt_sweep_all"))
     tf = os.path.join(ROOT, "profiles", f"{kernel}_{args.workload}_traffic.txt")
     if plain_run and os.path.exists(tf):
@@ -577,6 +577,7 @@ def main() -> int:
                             ("resnet101_one_call_per_k_bitset", dict(workload="resnet101", per_k_calls=True, subset_sum=True)),
                             ("vgg19_bitset", dict(workload="vgg19", subset_sum=True)),
                             ("backward_bitset", dict(workload="backward", subset_sum=True)),
+                            ("inflation_bitset", dict(workload="inflation", subset_sum=True)),
                             ("schedule_bitset", dict(workload="schedule", subset_sum=True))):
             sub = argparse.Namespace(**vars(args))
             sub.workload, sub.no_cpu = name, args.no_cpu or "rows16" in name or "bitset" in name

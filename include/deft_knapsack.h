@@ -84,8 +84,9 @@ typedef struct {
 
 /*
  * DEFT_FLAG_SUBSET_SUM: the same promise (every value equals its weight; an instance that
- * breaks it gets DEFT_ERR_INVALID_ARG), 1 <= max_capacity <= 65535.  DEFT_MODE_SEQUENTIAL and
- * DEFT_MODE_RECURSIVE calls (and with them deft_knapsack_simulate_schedule) then run kernels that
+ * breaks it gets DEFT_ERR_INVALID_ARG), 1 <= max_capacity <= 65535.  DEFT_MODE_SEQUENTIAL,
+ * DEFT_MODE_RECURSIVE and DEFT_MODE_CAPACITY_SWEEP calls (and with them
+ * deft_knapsack_simulate_schedule) then run kernels that
  * treat a window as the subset-sum problem it is (Sec. III.B, Problem 1 with profit = time):
  * the DP row is the set of reachable sums, one bit per cell, an item is one shift-and-or
  * of the set (32 cells per instruction), and the canonical selection - the one the exact DP
@@ -96,9 +97,10 @@ typedef struct {
  * to 511, 16-bit cells beyond (create returns DEFT_ERR_LIMIT when set, record and item list
  * exceed a compute unit's LDS).  Algorithm 1's levels are read off the same set (a level's
  * answer is the largest reachable sum not above its remaining time, taken before the item
- * that ends the level is added).  Results are bit-identical to those of a handle without
- * flags.  DEFT_MODE_CAPACITY_SWEEP (and DEFT_MODE_RECURSIVE where one more item list does not
- * fit the LDS) runs as under DEFT_FLAG_VALUES_ARE_WEIGHTS when max_capacity <= 26623 and on
+ * that ends the level is added), and so are the capacity sweep's answers (the final set at
+ * the largest capacity, one walk per capacity).  Results are bit-identical to those of a
+ * handle without flags.  Where the one more item list those two modes need does not fit
+ * the LDS, they run as under DEFT_FLAG_VALUES_ARE_WEIGHTS when max_capacity <= 26623 and on
  * the 32-bit rows above that.  deft_knapsack_get_info reports seq_path 4.
  */
 #define DEFT_FLAG_SUBSET_SUM 2u
@@ -331,8 +333,8 @@ typedef struct {
     int64_t scratch_bytes;     /* device memory owned by the handle                        */
     int32_t seq_path;          /* 0 none, 1 wavefront-per-instance LDS, 2 workgroup-per-
                                   instance LDS, 3 rows in global memory, 4 bit-set rows
-                                  (DEFT_FLAG_SUBSET_SUM; what SEQUENTIAL and RECURSIVE
-                                  calls run on)                                            */
+                                  (DEFT_FLAG_SUBSET_SUM; what SEQUENTIAL, RECURSIVE and
+                                  CAPACITY_SWEEP calls run on)                             */
     int32_t seq_threads;       /* threads cooperating on one instance                      */
     int32_t seq_cells_per_thread;
     int32_t seq_lds_bytes;     /* LDS per workgroup                                        */

@@ -52,7 +52,7 @@ struct deft_knapsack {
     unsigned long long *lds_swept = nullptr;      // device counter read by get_profile (LDS path)
 
     bool use_bits = false;        // SEQUENTIAL mode runs the bit-set kernels (DEFT_FLAG_SUBSET_SUM)
-    bool use_bits_rec = false;    // and so does RECURSIVE
+    bool use_bits_rec = false;    // and so do RECURSIVE and CAPACITY_SWEEP
     SeqBitsPlan bits_plan{};
 
     void *sim_buffers = nullptr;  // task-queue simulation: allocated by its first call
@@ -283,7 +283,7 @@ extern "C" deft_status_t deft_knapsack_solve_batch(deft_knapsack_t *h, const def
         if (prof) prof->sweep_begin(st);
         e = seq_bits_launch(h->bits_plan, a, st);
         if (prof) prof->sweep_end(st);
-    } else if (b->mode == DEFT_MODE_RECURSIVE && h->use_bits_rec) {
+    } else if ((b->mode == DEFT_MODE_RECURSIVE || b->mode == DEFT_MODE_CAPACITY_SWEEP) && h->use_bits_rec) {
         if (prof) prof->sweep_begin(st);
         e = seq_bits_rec_launch(h->bits_plan, a, st);
         if (prof) prof->sweep_end(st);

@@ -213,9 +213,10 @@ __device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, FirstT
 // FirstT: the cell type of first[].  An 8-bit cell serves lists of at most 255 items, with
 // SNAP (one snapshot of the set) of at most 511, and halves the instance's LDS, so that
 // about twice as many instances share a compute unit.
-// REC = false: DEFT_MODE_SEQUENTIAL.  REC = true: DEFT_MODE_RECURSIVE (Algorithm 1 on one
-// window: every item offered in generation order, the best level tracked during the sweep,
-// the walk started at that level's value).
+// REC = false: DEFT_MODE_SEQUENTIAL.  REC = true, chosen by a.mode at run time:
+// DEFT_MODE_RECURSIVE (Algorithm 1 on one window: every item offered in generation order, the
+// best level tracked during the sweep, the walk started at that level's value) and
+// DEFT_MODE_CAPACITY_SWEEP (one sweep at the largest capacity, one walk per capacity).
 template <int K, class FirstT, bool SNAP, bool REC>
 __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words, int first_ints, int n_pad)
 {
@@ -239,6 +240,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
     const int cap_raw = lane < a.knap_stride ? cap[lane] : 0;
     const int ord_raw = ord && lane < a.knap_stride ? ord[lane] : lane;
     const int n = a.n_items[inst], m = a.n_knapsacks[inst];
+    const bool caps_sweep = REC && a.mode == DEFT_MODE_CAPACITY_SWEEP;  // (the REC kernels serve both modes)
 
     // Input checks, in the order every kernel of the library reports them: invalid data, the
     // handle's limits, overflow of the value sum; then the handle's promise that every value
@@ -248,7 +250,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
         uint32_t flags = 0;
         unsigned long long vs = 0;
         bool differs = false;
-        if (n < 0 || n > a.item_stride || m < 0 || m > a.knap_stride || (REC && m != 1)) {
+        if (n < 0 || n > a.item_stride || m < 0 || m > a.knap_stride || (REC && (caps_sweep ? m > 31 : m != 1))) {
             flags = 1;
         } else {
             for (int i0 = 0; i0 < n; i0 += 64) {
@@ -256,7 +258,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
                 if (i < n) {
                     const int w = i0 == 0 ? w_first : W[i], v = i0 == 0 ? v_first : V[i];
                     bool bad = w < 1 || v < 0;
-                    if constexpr (REC) bad = bad || a.drop_time[(size_t)inst * a.item_stride + i] < 0;
+                    if constexpr (REC) bad = bad || (!caps_sweep && a.drop_time[(size_t)inst * a.item_stride + i] < 0);
                     if (bad) flags |= 1; else vs += (unsigned)v;
                     differs = differs || v != w;
                 }
@@ -293,6 +295,54 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
     wave_lds_sync();
 
     if constexpr (REC) {
+        if (caps_sweep) {
+            // The capacity sweep: one sweep over the whole list at the largest capacity; the
+            // final set answers every capacity (the largest reachable sum not above it), and the
+            // chain through first[] from that sum is the selection the DP would walk back at that
+            // capacity.  Lane x takes capacity x: all the walks run side by side, each lane
+            // following its own chain through LDS, and an item's mask collects the capacities
+            // at which it is taken.
+            const int cap_max = bits_wave_max(cap_l);
+            if (n == 0 || m == 0) return;  // (every output is already zero)
+            for (int i = lane; i < n; i += 64) {
+                lw[i] = i < 64 ? w_first : W[i];
+                lp[i] = -1;  // no level ends anywhere
+            }
+            wave_lds_sync();
+            BitsLevel unused{0, 0, 0};
+            const int nb = (cap_max / 32 + 64) / 64;
+            (void)sweep_bits_dispatch<K, FirstT, SNAP, true>(nb, set, first, snap, lw, lp, lane, n, cap_max, unused);
+            int t = 0;
+            if (lane < m) {
+                int wi = cap_l >> 5;
+                uint32_t x = set[wi] & (0xffffffffu >> (31 - (cap_l & 31)));
+                while (x == 0) x = set[--wi];  // (word 0 holds the empty sum)
+                t = wi * 32 + 31 - __builtin_clz(x);
+            }
+            const int value = t;
+            __threadfence_block();  // the cleared masks are in place before bits are set in them
+            int guard = n;          // (a chain is never longer than the list)
+            while (__builtin_amdgcn_ballot_w64(t > 0) != 0ull && guard-- > 0) {
+                if (t > 0) {
+                    int q = first[t];
+                    if constexpr (SNAP) q += ((snap[t >> 5] >> (t & 31)) & 1u) ? 0 : 256;
+                    q = min(q, n - 1);
+                    atomicOr(reinterpret_cast<unsigned int *>(&out_asg[q]), 1u << lane);
+                    t -= lw[q];
+                }
+            }
+            if (lane < m) {
+                out_kv[lane] = value;
+                out_kl[lane] = value;
+            }
+            const int at_largest = bits_wave_max(value);
+            const bool broken = __builtin_amdgcn_ballot_w64(t != 0) != 0ull;  // (never expected)
+            if (lane == 0) {
+                a.total_value[inst] = at_largest;
+                if (broken) a.status[inst] = DEFT_ERR_DEVICE;
+            }
+            return;
+        }
         // Algorithm 1: the whole list is offered in generation order (an item heavier than the
         // remaining time changes nothing, but the levels are counted in list positions).
         // Entry i gets P_i = R - sum of drop[t] over t >= i, from a suffix sum taken 64 items at

@@ -64,6 +64,19 @@ def test_algorithm1_every_variant(binding, oracle, cap_hi, max_capacity):
     run(binding, oracle, kl, max_capacity=max_capacity, flags=FLAG)
 
 
+@pytest.mark.parametrize("cap_hi,max_capacity", VARIANTS)
+def test_capacity_sweep_every_variant(binding, oracle, cap_hi, max_capacity):
+    """DEFT_MODE_CAPACITY_SWEEP on the bit-set kernels: one sweep at the largest capacity, the
+    value at every capacity read off the final set, the walks side by side (one lane each)."""
+    kc = W.random_capacity_sweep(24000 + cap_hi, batch=13, n_max=70, m_max=31, w_hi=max(9, cap_hi // 30), v_hi=9,
+                                 cap_hi=cap_hi, ties=True)
+    run(binding, oracle, kc, max_capacity=max_capacity, flags=FLAG)
+    run(binding, oracle, kc, max_capacity=max_capacity, max_items=600, flags=FLAG)
+    kl = W.random_capacity_sweep(24500 + cap_hi, batch=9, n_max=480, m_max=11, w_hi=max(3, cap_hi // 150), v_hi=9,
+                                 cap_hi=cap_hi, ties=True)              # lists beyond position 255: the snapshot
+    run(binding, oracle, kl, max_capacity=max_capacity, flags=FLAG)
+
+
 def test_instances_that_break_the_promise_and_other_faults(binding, oracle):
     kb = W.random_sequential(25001, batch=8, n_max=12, m_max=2, w_hi=9, v_hi=9, cap_hi=30, ragged=False, ties=True)
     ref = oracle.solve_batch(kb, cap_limit=30)
@@ -106,8 +119,7 @@ def test_paper_shapes_at_full_size(binding, oracle):
     for k in (1, 3):
         run(binding, oracle, W.resnet101_shaped(k=k), flags=FLAG)
     run(binding, oracle, W.backward_stage_shaped(), flags=FLAG)            # Algorithm 1 on the bit-set kernels
-    # the capacity sweep of such a handle runs on rows of 16-bit cells
-    run(binding, oracle, W.inflation_sweep_shaped(batch=64), flags=FLAG)
+    run(binding, oracle, W.inflation_sweep_shaped(), flags=FLAG)           # the capacity sweep on them
 
 
 def test_task_queues(binding, oracle):
