@@ -537,8 +537,8 @@ def main() -> int:
                     help="value-equals-weight workloads: create the handle with DEFT_FLAG_VALUES_ARE_WEIGHTS "
                          "(rows of 16-bit cells)")
     ap.add_argument("--subset-sum", action="store_true",
-                    help="value-equals-weight workloads: create the handle with DEFT_FLAG_SUBSET_SUM (sequential "
-                         "mode on bit-set rows, one wavefront per instance)")
+                    help="value-equals-weight workloads: create the handle with DEFT_FLAG_SUBSET_SUM (bit-set "
+                         "rows, one wavefront per instance)")
     ap.add_argument("--max-stages", type=int, default=0, help="clamp n_knapsacks (debug only)")
     ap.add_argument("--only-k", type=int, default=0, help="keep only the call with this k (debug only)")
     args = ap.parse_args()
@@ -571,7 +571,7 @@ def main() -> int:
                             ("backward_rows16", dict(workload="backward", packed16=True)),
                             ("inflation_rows16", dict(workload="inflation", packed16=True)),
                             ("schedule_rows16", dict(workload="schedule", packed16=True)),
-                            # the sequential-mode workloads on handles created with DEFT_FLAG_SUBSET_SUM
+                            # the value-equals-weight workloads on handles created with DEFT_FLAG_SUBSET_SUM
                             # (bit-set rows, one wavefront per instance)
                             ("resnet101_bitset", dict(workload="resnet101", subset_sum=True)),
                             ("resnet101_one_call_per_k_bitset", dict(workload="resnet101", per_k_calls=True, subset_sum=True)),

@@ -51,7 +51,7 @@ struct deft_knapsack {
     unsigned long long *glob_streamed = nullptr;  // device counter read by get_profile
     unsigned long long *lds_swept = nullptr;      // device counter read by get_profile (LDS path)
 
-    bool use_bits = false;        // SEQUENTIAL mode runs the bit-set kernels (DEFT_FLAG_SUBSET_SUM)
+    bool use_bits = false;        // SEQUENTIAL mode runs on the bit-set kernels (DEFT_FLAG_SUBSET_SUM)
     bool use_bits_rec = false;    // and so do RECURSIVE and CAPACITY_SWEEP
     SeqBitsPlan bits_plan{};
 
@@ -117,8 +117,9 @@ extern "C" deft_status_t deft_knapsack_create(const deft_knapsack_config_t *cfg,
     if (want_joint && cfg->max_knapsacks < 2) return DEFT_ERR_INVALID_ARG;
     const bool subset_sum = (cfg->flags & DEFT_FLAG_SUBSET_SUM) != 0;
     if (subset_sum && (!want_seq || cfg->max_capacity > kMaxSubsetSumCapacity)) return DEFT_ERR_LIMIT;
-    // the other sequential-layout modes of a subset-sum handle run on rows of 16-bit cells where
-    // those reach, on the 32-bit rows beyond
+    // what a subset-sum handle does not run on the bit-set kernels (the greedy mode; Algorithm 1
+    // and the capacity sweep where their extra list does not fit the LDS) runs on rows of 16-bit
+    // cells where those reach, on the 32-bit rows beyond
     const bool packed16 = (cfg->flags & DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0 ||
                           (subset_sum && cfg->max_capacity <= kMaxPacked16Capacity);
     if ((cfg->flags & DEFT_FLAG_VALUES_ARE_WEIGHTS) != 0 && (!want_seq || cfg->max_capacity > kMaxPacked16Capacity))

@@ -66,7 +66,7 @@ hipError_t seq_lds_rec_prepare(const SeqLdsPlan &plan);
 hipError_t seq_lds_rec_launch(const SeqLdsPlan &plan, const BatchArgs &args, void *scratch,
                               hipStream_t stream, unsigned long long *swept_cells);
 
-// ---- sequential mode, value = weight, one bit per cell (seq_bits.hip) -----------
+// ---- sequential layout, value = weight, one bit per cell (seq_bits_kernel.h) -----
 // One wavefront per instance; the reachable sums as a bit set in registers and LDS, the
 // selection from a per-cell "first item that reached this sum" array in LDS.  No scratch.
 struct SeqBitsPlan {
