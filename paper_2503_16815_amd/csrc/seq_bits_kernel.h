@@ -76,7 +76,11 @@ __device__ __forceinline__ int bits_wave_max(int x) { return bits_wave_reduce(x,
 // the largest reachable sum <= P_q: the word that holds P_q read from LDS and, where that one
 // has nothing at or below P_q, a search of the words below.  Levels are met deepest first and
 // a shallower one replaces the incumbent only when strictly greater, as the recursion does
-// on its way back up.  The sweep then goes through the whole list.
+// on its way back up.  With `levels` the sweep ends, as in the sequential mode, once C (the
+// whole remaining time) is reachable: no level is worth more, the levels so far are worth
+// less (their sets did not hold C), and a later level is worth C exactly when its remaining
+// time is C (nothing is dropped after it) - the first such entry, else the whole list, is
+// the answer.  Without `levels` (the capacity sweep) it goes through the whole list.
 struct BitsLevel {
     int value, length, remain;
 };
@@ -94,7 +98,7 @@ __device__ __forceinline__ int largest_sum_up_to(const uint32_t *set, const uint
 }
 template <int NB, class FirstT, bool SNAP, bool REC>
 __device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, uint32_t *snap, const int32_t *lw, const int32_t *lp,
-                                          int lane, int nact, int C, BitsLevel &best)
+                                          int lane, int nact, int C, BitsLevel &best, bool levels)
 {
     uint32_t own[NB], need[NB];  // need: the cells of the word that are <= C
 #pragma unroll
@@ -176,7 +180,24 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, uint32_t
                 // (C's word is in the last slot: NB is the smallest count that covers it)
                 const bool reached = lane == c_lane && (fresh[NB - 1] & c_bit) != 0;
                 wave_lds_sync();  // the new set is visible
-                if (!REC && __builtin_amdgcn_ballot_w64(reached) != 0ull) return C;
+                if (__builtin_amdgcn_ballot_w64(reached) != 0ull) {
+                    if constexpr (!REC) {
+                        return C;
+                    } else if (levels) {
+                        int found = nact;  // the whole list
+                        for (int c0 = (q + 1) & ~63; c0 < nact; c0 += 64) {
+                            const int e = c0 + lane;
+                            const unsigned long long hit =
+                                __builtin_amdgcn_ballot_w64(e > q && e < nact && lp[e] == C);
+                            if (hit != 0ull) {
+                                found = c0 + __builtin_ctzll(hit);
+                                break;
+                            }
+                        }
+                        best = BitsLevel{C, found, C};
+                        return C;
+                    }
+                }
             }
             if constexpr (SNAP) {
                 if (q == 255) {
@@ -197,12 +218,12 @@ __device__ __forceinline__ int sweep_bits(uint32_t *set, FirstT *first, uint32_t
 
 template <int N, class FirstT, bool SNAP, bool REC>
 __device__ __forceinline__ int sweep_bits_dispatch(int nb, uint32_t *set, FirstT *first, uint32_t *snap, const int32_t *lw,
-                                                   const int32_t *lp, int lane, int nact, int C, BitsLevel &best)
+                                                   const int32_t *lp, int lane, int nact, int C, BitsLevel &best, bool levels)
 {
     if (nb == N) {
-        return sweep_bits<N, FirstT, SNAP, REC>(set, first, snap, lw, lp, lane, nact, C, best);
+        return sweep_bits<N, FirstT, SNAP, REC>(set, first, snap, lw, lp, lane, nact, C, best, levels);
     } else if constexpr (N > 1) {
-        return sweep_bits_dispatch<N - 1, FirstT, SNAP, REC>(nb, set, first, snap, lw, lp, lane, nact, C, best);
+        return sweep_bits_dispatch<N - 1, FirstT, SNAP, REC>(nb, set, first, snap, lw, lp, lane, nact, C, best, levels);
     }
     return 0;
 }
@@ -311,7 +332,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
             wave_lds_sync();
             BitsLevel unused{0, 0, 0};
             const int nb = (cap_max / 32 + 64) / 64;
-            (void)sweep_bits_dispatch<K, FirstT, SNAP, true>(nb, set, first, snap, lw, lp, lane, n, cap_max, unused);
+            (void)sweep_bits_dispatch<K, FirstT, SNAP, true>(nb, set, first, snap, lw, lp, lane, n, cap_max, unused, false);
             int t = 0;
             if (lane < m) {
                 int wi = cap_l >> 5;
@@ -369,7 +390,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
         int value = 0;
         if (n > 0) {
             const int nb = (C / 32 + 64) / 64;
-            value = sweep_bits_dispatch<K, FirstT, SNAP, true>(nb, set, first, snap, lw, lp, lane, n, C, best);
+            value = sweep_bits_dispatch<K, FirstT, SNAP, true>(nb, set, first, snap, lw, lp, lane, n, C, best, true);
         }
         if (value > best.value) best = BitsLevel{value, n, C};  // level 0: the whole list
         // the walk from the best level's value: its chain only meets sums first reached by
@@ -439,7 +460,7 @@ __global__ void __launch_bounds__(64) seq_bits_kernel(BatchArgs a, int row_words
         } else {
             const int nb = (C / 32 + 64) / 64;  // words per lane covering cells 0 .. C
             BitsLevel unused{0, 0, 0};
-            value = sweep_bits_dispatch<K, FirstT, SNAP, false>(nb, set, first, snap, lw, lp, lane, cnt, C, unused);
+            value = sweep_bits_dispatch<K, FirstT, SNAP, false>(nb, set, first, snap, lw, lp, lane, cnt, C, unused, false);
             // the walk: every lane follows the same chain; the lane that owns an item's bit marks it
             int t = value;
             int guard = cnt;  // (a chain is never longer than the list)

@@ -62,6 +62,13 @@ def test_algorithm1_every_variant(binding, oracle, cap_hi, max_capacity):
     kl = W.random_recursive(23700 + cap_hi, batch=9, n_max=500, w_hi=max(3, cap_hi // 150), v_hi=9, cap_hi=cap_hi,
                             t_hi=max(1, cap_hi // 800), ties=True)         # lists beyond position 255: the snapshot
     run(binding, oracle, kl, max_capacity=max_capacity, flags=FLAG)
+    # drop times of 0 and 1, some lists with none at all: levels that tie with the whole list once
+    # the remaining time itself is reached (where the sweep ends), the deepest of them wins
+    kz = W.random_recursive(23900 + cap_hi, batch=24, n_max=200, w_hi=max(9, cap_hi // 60), v_hi=9, cap_hi=cap_hi,
+                            t_hi=1, ties=True)
+    kz.drop_time[::3] = 0
+    kz.drop_time[1::3, 40:] = 0
+    run(binding, oracle, kz, max_capacity=max_capacity, flags=FLAG)
 
 
 @pytest.mark.parametrize("cap_hi,max_capacity", VARIANTS)
