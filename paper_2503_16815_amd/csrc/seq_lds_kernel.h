@@ -249,16 +249,21 @@ constexpr int kSecondBase = 60416;
 // reached: the kept value row[C] - C is 0) the stage's value is final, and no later item is
 // taken at C (a take needs a strict improvement), so the walk back from C passes every later
 // item and only ever reads keep rows up to here: the sweep ends there.  Checked after every
-// eighth item (every second one of a list of at most 64), between two items: the wavefront that owns cell C stores the check's tag in
-// `unfinished` while the cell is short of C, and after a barrier everyone looks at it.
+// eighth item (every second one of a list of at most 64), between two items: the wavefront
+// that owns cell C stores the check's tag in `unfinished` while the cell is short of C, and
+// after a barrier everyone looks at it.  Algorithm 1 (`levels`) ends its sweep the same way
+// and settles the levels it has not met (settle_levels below); the capacity sweep, which
+// reads the row at other cells as well, goes through the whole list.
 // Returns the number of items swept (the keep rows beyond were never written).
 template <int T, int NB, int G, int NW, bool ADDTID, bool VEQW, bool REC, bool SKIP_UNCHANGED>
 __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int light_max, int tid, int nact,
                                             const OfferedItem *list, uint32_t *kp, unsigned long long &nzm,
-                                            BestLevel &best, int C, int32_t *unfinished)
+                                            BestLevel &best, int C, int32_t *unfinished, bool levels)
 {
-    constexpr bool STOP_WHEN_FULL = VEQW && !REC;
-    const int check_mask = nact <= 64 ? 1 : 7;  // short lists: after every second item, else every eighth
+    constexpr bool STOP_WHEN_FULL = VEQW;  // (REC: Algorithm 1 only, see settle_levels)
+    // short lists: after every second item, else every eighth; never for the capacity sweep,
+    // which reads the row below C as well
+    const int check_mask = REC && !levels ? INT_MAX : nact <= 64 ? 1 : 7;
     // What follows from the lane index alone (a slot's initial value and LDS address, for every
     // slot count instantiated) is cheap to compute here; left visible to the compiler it is all
     // computed at kernel entry instead, parked in scratch memory and fetched back per stage.
@@ -429,6 +434,28 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
         }
     };
 
+    // Algorithm 1, once the whole remaining time C is reachable (after item q): no level is worth
+    // more; the levels met so far are worth less (their rows did not reach C); a later level is
+    // worth C exactly when its own remaining time is C (nothing is dropped after it).  The first
+    // such entry among those not met yet, else the whole list, is the answer: the deepest level
+    // among equals.
+    auto settle_levels = [&](int q) {
+        if constexpr (REC) {
+            int found = nact;
+            for (int c0 = (q + 1) & ~63; c0 < nact; c0 += 64) {
+                const int e = c0 + lane;
+                const unsigned long long hit =
+                    __builtin_amdgcn_ballot_w64(e > q && e < nact && load_item_pad(list + e) == C);
+                if (hit != 0ull) {
+                    found = c0 + __builtin_ctzll(hit);
+                    break;
+                }
+            }
+            // (the check runs every few items: a level met since C was reached may hold it already)
+            if (best.value < C) best = BestLevel{C, found, C};
+        }
+    };
+
     for (int q0 = 0; q0 < nact; q0 += 64) {
         const int2 nxt = load_chunk(q0 + 64);
         const int nxt_p = load_probe_chunk(q0 + 64);
@@ -438,13 +465,13 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
             int w = __builtin_amdgcn_readlane(cur.x, q & 63);
             while (w <= light_max) {  // run of light items
                 item(std::false_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (capacity_reached(q)) { hand_over(q); return q + 1; }
+                if (capacity_reached(q)) { settle_levels(q); hand_over(q); return q + 1; }
                 if (++q >= q1) break;
                 w = __builtin_amdgcn_readlane(cur.x, q & 63);
             }
             if (q < q1) {  // one heavy item
                 item(std::true_type{}, q, w, VEQW ? w : __builtin_amdgcn_readlane(cur.y, q & 63));
-                if (capacity_reached(q)) { hand_over(q); return q + 1; }
+                if (capacity_reached(q)) { settle_levels(q); hand_over(q); return q + 1; }
                 ++q;
             }
         }
@@ -459,14 +486,14 @@ __device__ __forceinline__ int sweep_stage(int32_t *row, uint32_t row_off, int l
 template <int T, int G, int NW, bool ADDTID, bool VEQW, bool REC, bool SKIP_UNCHANGED, int N>
 __device__ __forceinline__ int sweep_dispatch(int nchunk, int32_t *row, uint32_t row_off, int light_max, int tid,
                                                int nact, const OfferedItem *list, uint32_t *kp,
-                                               unsigned long long &nzm, BestLevel &best, int C, int32_t *unfinished)
+                                               unsigned long long &nzm, BestLevel &best, int C, int32_t *unfinished, bool levels)
 {
     if (nchunk == N) {
         return sweep_stage<T, N * G, G, NW, ADDTID, VEQW, REC, SKIP_UNCHANGED>(row, row_off, light_max, tid, nact, list, kp, nzm,
-                                                            best, C, unfinished);
+                                                            best, C, unfinished, levels);
     } else if constexpr (N > 1) {
         return sweep_dispatch<T, G, NW, ADDTID, VEQW, REC, SKIP_UNCHANGED, N - 1>(nchunk, row, row_off, light_max, tid, nact, list, kp,
-                                                                  nzm, best, C, unfinished);
+                                                                  nzm, best, C, unfinished, levels);
     }
     return 0;
 }
@@ -535,10 +562,12 @@ __device__ __forceinline__ int row16_cell(const int32_t *row, int c)
 template <int T, int NP, bool REC, bool SKIP_UNCHANGED>
 __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, int tid, int nact, const OfferedItem *list,
                                                 uint32_t *kp, unsigned long long &nzm, BestLevel &best, int C,
-                                                int32_t *unfinished)
+                                                int32_t *unfinished, bool levels)
 {
-    constexpr bool STOP_WHEN_FULL = !REC;
-    const int check_mask = nact <= 64 ? 1 : 7;  // short lists: after every second item, else every eighth
+    constexpr bool STOP_WHEN_FULL = true;  // (REC: Algorithm 1 only, see settle_levels)
+    // short lists: after every second item, else every eighth; never for the capacity sweep,
+    // which reads the row below C as well
+    const int check_mask = REC && !levels ? INT_MAX : nact <= 64 ? 1 : 7;
     static_assert(NP >= 1 && NP <= 16, "the take bits of a lane fit one keep word");
     asm volatile("" : "+v"(tid));  // (as in sweep_stage: keeps the per-lane constants out of kernel entry)
     const int wave_first = uniform(tid & ~63);
@@ -673,6 +702,28 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
         }
     };
 
+    // Algorithm 1, once the whole remaining time C is reachable (after item q): no level is worth
+    // more; the levels met so far are worth less (their rows did not reach C); a later level is
+    // worth C exactly when its own remaining time is C (nothing is dropped after it).  The first
+    // such entry among those not met yet, else the whole list, is the answer: the deepest level
+    // among equals.
+    auto settle_levels = [&](int q) {
+        if constexpr (REC) {
+            int found = nact;
+            for (int c0 = (q + 1) & ~63; c0 < nact; c0 += 64) {
+                const int e = c0 + lane;
+                const unsigned long long hit =
+                    __builtin_amdgcn_ballot_w64(e > q && e < nact && load_item_pad(list + e) == C);
+                if (hit != 0ull) {
+                    found = c0 + __builtin_ctzll(hit);
+                    break;
+                }
+            }
+            // (the check runs every few items: a level met since C was reached may hold it already)
+            if (best.value < C) best = BestLevel{C, found, C};
+        }
+    };
+
     for (int q0 = 0; q0 < nact; q0 += 64) {
         const int2 nxt = load_chunk(q0 + 64);
         const int nxt_p = load_probe_chunk(q0 + 64);
@@ -682,7 +733,7 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
             if (w <= wave_first) item(std::integral_constant<int, 0>{}, q, w);
             else if (w <= T) item(std::integral_constant<int, 1>{}, q, w);
             else item(std::integral_constant<int, 2>{}, q, w);
-            if (capacity_reached(q)) { hand_over(q); return q + 1; }
+            if (capacity_reached(q)) { settle_levels(q); hand_over(q); return q + 1; }
         }
         cur = nxt;
         cur_p = nxt_p;
@@ -695,13 +746,13 @@ __device__ __forceinline__ int sweep_stage_p16(int32_t *row, uint32_t row_off, i
 template <int T, bool REC, bool SKIP_UNCHANGED, int N>
 __device__ __forceinline__ int sweep_dispatch_p16(int npair, int32_t *row, uint32_t row_off, int tid, int nact,
                                                    const OfferedItem *list, uint32_t *kp, unsigned long long &nzm,
-                                                   BestLevel &best, int C, int32_t *unfinished)
+                                                   BestLevel &best, int C, int32_t *unfinished, bool levels)
 {
     if (npair == N) {
-        return sweep_stage_p16<T, N, REC, SKIP_UNCHANGED>(row, row_off, tid, nact, list, kp, nzm, best, C, unfinished);
+        return sweep_stage_p16<T, N, REC, SKIP_UNCHANGED>(row, row_off, tid, nact, list, kp, nzm, best, C, unfinished, levels);
     } else if constexpr (N > 1) {
         return sweep_dispatch_p16<T, REC, SKIP_UNCHANGED, N - 1>(npair, row, row_off, tid, nact, list, kp, nzm, best, C,
-                                                                 unfinished);
+                                                                 unfinished, levels);
     }
     return 0;
 }
@@ -1054,13 +1105,13 @@ seq_lds_kernel(BatchArgs a, LdsLayout lay, uint32_t *keep, int64_t keep_words_pe
         int swept;
         if constexpr (P16)
             swept = sweep_dispatch_p16<T, REC, kSkipUnchanged, K / 2>(uniform((C / T + 2) / 2), row, row_off, tid, nact, list, kp,
-                                                                      nzm, best, C, &misc[7]);
+                                                                      nzm, best, C, &misc[7], levels);
         else if (veqw)
             swept = sweep_dispatch<T, G, NW, ADDTID, true, REC, kSkipUnchanged, NCH>(nchunk, row, row_off, light_max, tid, nact, list,
-                                                                     kp, nzm, best, C, &misc[7]);
+                                                                     kp, nzm, best, C, &misc[7], levels);
         else
             swept = sweep_dispatch<T, G, NW, ADDTID, false, REC, kSkipUnchanged, NCH>(nchunk, row, row_off, light_max, tid, nact, list,
-                                                                      kp, nzm, best, C, &misc[7]);
+                                                                      kp, nzm, best, C, &misc[7], levels);
 
         // the value at capacity c as the final row holds it
         auto row_value = [&](int c) {

@@ -71,6 +71,12 @@ def test_algorithm1_and_capacity_sweep_every_variant(binding, oracle, cap_hi, ma
     kh = W.random_recursive(13500 + cap_hi, batch=17, n_max=70, w_hi=max(20, cap_hi // 2), v_hi=9, cap_hi=cap_hi,
                             t_hi=max(2, cap_hi // 60), ties=True)          # items heavier than most levels
     run(binding, oracle, kh, max_capacity=max_capacity, flags=FLAG)
+    # sweeps that end at the reached remaining time; drop times of 0 and 1: tying levels
+    kz = W.random_recursive(13700 + cap_hi, batch=24, n_max=400, w_hi=max(9, cap_hi // 60), v_hi=9,
+                            cap_hi=cap_hi, t_hi=1, ties=True)
+    kz.drop_time[::3] = 0
+    kz.drop_time[1::3, 40:] = 0
+    run(binding, oracle, kz, max_capacity=max_capacity, flags=FLAG)
     kc = W.random_capacity_sweep(14000 + cap_hi, batch=13, n_max=70, m_max=31, w_hi=max(9, cap_hi // 30), v_hi=9,
                                  cap_hi=cap_hi, ties=True)
     run(binding, oracle, kc, max_capacity=max_capacity, flags=FLAG)

@@ -24,6 +24,14 @@ def test_random_ragged_every_lds_variant(binding, oracle, cap_hi, max_capacity):
     kt = W.random_recursive(6000 + cap_hi, batch=17, n_max=70, w_hi=max(9, cap_hi // 40), v_hi=9,
                             cap_hi=cap_hi, t_hi=max(1, cap_hi // 200), ties=True)
     run(binding, oracle, kt, max_capacity=max_capacity)
+    # value = weight, lists long and light enough to reach the remaining time itself (where the
+    # sweep ends), drop times of 0 and 1 and lists with none after some point: the levels that
+    # tie with the whole list, of which the deepest must be reported
+    kz = W.random_recursive(6500 + cap_hi, batch=24, n_max=400, w_hi=max(9, cap_hi // 60), v_hi=9,
+                            cap_hi=cap_hi, t_hi=1, ties=True)
+    kz.drop_time[::3] = 0
+    kz.drop_time[1::3, 40:] = 0
+    run(binding, oracle, kz, max_capacity=max_capacity)
 
 
 def test_levels_that_must_not_win(binding, oracle):
